@@ -1,0 +1,231 @@
+/*
+ * ellm.h — C ABI of libellm: chunk-backed virtual KV tensors, KV append and batched GQA decode
+ * attention for AMD MI355X (gfx950).
+ *
+ * The operations follow the eLLM paper (arXiv 2506.15155):
+ *   - a unified physical pool of fixed-size chunks shared by the KV cache and activations
+ *     (Introduction "Our solution"; Sec. 2.1 "Virtual Tensor Abstraction");
+ *   - a KV virtual tensor ("KV eTensor") per request that reserves its whole token range up
+ *     front, is logically contiguous, and gets physical chunks mapped on demand at write time;
+ *     its slots are aligned to the chunk granularity (Sec. 2.1.1 "Virtualization Design");
+ *   - inflation / deflation: ownership of idle chunks moves between the activation side and the
+ *     KV side of the pool and the chunks are remapped into KV tensors (Sec. 2.2.1);
+ *   - offloading / fetching: the KV chunks of a request are moved to CPU DRAM and brought back
+ *     before the request decodes again (Sec. 2.2.2);
+ *   - decode: every sequence writes one new token per iteration (Sec. 3.1) and attends over its
+ *     whole cached context with standard softmax attention, grouped-query or multi-head
+ *     (Sec. 4.1 "Models"; Sec. 5 "Efficient Kernels").
+ *
+ * The paper maps chunks with the GPU driver's virtual-memory API. This library keeps the
+ * virtual-to-physical map in software instead: one int32 table row per tensor, token t living
+ * in slot t / T_c at row t % T_c of the chunk the table names, read directly by the kernels.
+ *
+ * All pointers say "host" or "device" below. No call allocates memory the caller has to free
+ * except ellm_pool_create (freed by ellm_pool_destroy). A pool is NOT thread-safe: one host
+ * thread drives it. Every call validates its whole argument set on the host before it changes any
+ * state or launches anything; a call that returns an error has changed nothing.
+ */
+#ifndef ELLM_H
+#define ELLM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- return codes (0 = success, negative = error) ------------------------------------------ */
+#define ELLM_OK                 0
+#define ELLM_ERR_INVALID       (-1)  /* malformed argument, bad handle, duplicate id, slot in use  */
+#define ELLM_ERR_OOM           (-2)  /* no free device chunk (even after allowed inflation), or no
+                                        free tensor handle                                          */
+#define ELLM_ERR_OWNED         (-3)  /* chunk is mapped, busy, or belongs to the other owner       */
+#define ELLM_ERR_UNMAPPED      (-4)  /* operation touches a slot that has no chunk                 */
+#define ELLM_ERR_NOT_RESIDENT  (-5)  /* operation touches a slot whose chunk is in host memory     */
+#define ELLM_ERR_RANGE         (-6)  /* slot / token / chunk index outside its range               */
+#define ELLM_ERR_EMPTY         (-7)  /* decode over a tensor that holds no token                   */
+#define ELLM_ERR_HOST_FULL     (-8)  /* not enough free host slots for an offload                  */
+#define ELLM_ERR_HIP           (-9)  /* a HIP runtime call failed (text in ellm_last_error)        */
+#define ELLM_ERR_NO_DEVICE     (-10) /* compute call on a pool created with ELLM_POOL_METADATA_ONLY */
+
+/* ---- constants ------------------------------------------------------------------------------ */
+#define ELLM_OWNER_KV    0   /* chunk belongs to the KV side of the pool          */
+#define ELLM_OWNER_ACT   1   /* chunk belongs to the activation side of the pool  */
+
+#define ELLM_CHUNK_FREE   0  /* idle, may be mapped (KV side) or transferred      */
+#define ELLM_CHUNK_MAPPED 1  /* backs exactly one (tensor, slot)                  */
+#define ELLM_CHUNK_BUSY   2  /* holds live activations; KV side may not touch it  */
+
+#define ELLM_BF16 1          /* the only element type: bfloat16, 2 bytes          */
+
+#define ELLM_MAP_ALLOW_INFLATE 1u  /* map may take FREE activation-owned chunks (Sec. 2.2.1)  */
+
+#define ELLM_POOL_METADATA_ONLY 1u /* pool flag: no device behind the pool. Host state machine
+                                      only: append advances lengths without launching, offload and
+                                      fetch move bookkeeping without copying bytes, decode returns
+                                      ELLM_ERR_NO_DEVICE after validating. For host-logic tests.  */
+
+/* Table-entry encoding (compared bit-exactly by tests):
+ *   e >= 0   device chunk id
+ *   e == -1  slot has no chunk
+ *   e <= -2  chunk content is in host slot (-e - 2)                                            */
+#define ELLM_ENTRY_UNMAPPED (-1)
+#define ELLM_ENTRY_FROM_HOST_SLOT(s) (-(int32_t)(s) - 2)
+#define ELLM_ENTRY_TO_HOST_SLOT(e)   (-(int32_t)(e) - 2)
+
+typedef struct ellm_pool ellm_pool;   /* opaque, owned by the library */
+typedef int32_t ellm_tensor_id;       /* dense handle >= 0            */
+
+/*
+ * Pool geometry.
+ *   bpt  = bytes per token of one layer = 2 (K and V) * n_kv_heads * head_dim * 2 bytes
+ *   T_c  = tokens per chunk             = floor(chunk_bytes / bpt)        (must be >= 1)
+ *   n_chunks     = floor(device_bytes / chunk_bytes)
+ *   n_host_slots = floor(host_bytes   / chunk_bytes)                      (may be 0)
+ *
+ * Layout of one chunk (the migrated bytes and every reader depend on it): element
+ * (kv head h, plane p (0 = K, 1 = V), token row r < T_c, dim d) sits at byte offset
+ *   ((h * 2 + p) * T_c + r) * head_dim * 2 + d * 2.
+ * Bytes past 2 * n_kv_heads * T_c * head_dim * 2 are slack: never read by attention, but copied
+ * by offload / fetch, which always move whole chunks.
+ */
+typedef struct ellm_pool_desc {
+  void*    device_base;      /* device, caller-owned, 256-byte aligned; NULL only with METADATA_ONLY */
+  uint64_t device_bytes;
+  void*    host_base;        /* host, caller-owned, pinned; NULL iff host_bytes < chunk_bytes     */
+  uint64_t host_bytes;
+  uint32_t chunk_bytes;      /* multiple of 256                                                   */
+  uint16_t n_q_heads;
+  uint16_t n_kv_heads;       /* n_q_heads % n_kv_heads == 0; group size G = n_q / n_kv <= 64      */
+  uint16_t head_dim;         /* 64 or 128                                                         */
+  uint16_t dtype;            /* ELLM_BF16                                                         */
+  uint32_t max_tensors;      /* tensor handles 0 .. max_tensors-1                                 */
+  uint32_t max_slots_per_tensor;
+  uint32_t flags;            /* 0 or ELLM_POOL_METADATA_ONLY                                      */
+  uint32_t reserved;         /* must be 0                                                         */
+  const uint8_t* initial_owner; /* host, n_chunks bytes of ELLM_OWNER_*; NULL = all KV.
+                                   Every chunk starts FREE.                                       */
+} ellm_pool_desc;
+
+/* Create a pool over caller-owned buffers (Sec. 2.1: one unified physical pool).
+ * Errors: INVALID for any violated constraint above. No HIP call is made here; device-side
+ * metadata is created lazily by the first call that launches or copies. */
+int ellm_pool_create(const ellm_pool_desc* desc, ellm_pool** out);
+
+/* Drains the library's streams, frees its metadata. Caller buffers are untouched. */
+int ellm_pool_destroy(ellm_pool* pool);
+
+/* Reserve a virtual tensor of max_tokens tokens (Sec. 2.1.1: virtual range = maximum context,
+ * no physical chunk yet). n_slots = ceil(max_tokens / T_c). Returns the lowest unused handle.
+ * Errors: INVALID (max_tokens < 1), RANGE (n_slots > max_slots_per_tensor), OOM (no handle). */
+int ellm_tensor_create(ellm_pool* pool, int64_t max_tokens, ellm_tensor_id* out);
+
+/* Release a tensor: its device chunks become FREE (owner unchanged), its host slots are freed,
+ * the handle becomes reusable. Errors: INVALID (bad handle). */
+int ellm_tensor_destroy(ellm_pool* pool, ellm_tensor_id id);
+
+/* Map chunks into slots [first_slot, first_slot + n_slots) (Sec. 2.1.1 on-demand allocation;
+ * Sec. 2.2.1 steps 1, 3, 4 when ELLM_MAP_ALLOW_INFLATE is set).
+ *   chunk_ids (host): n_slots explicit ids, slot first_slot + i gets chunk_ids[i]; or NULL, then
+ *   the pool takes the lowest-numbered FREE KV-owned chunks in ascending order and, only if those
+ *   run out and ALLOW_INFLATE is set, the lowest-numbered FREE ACT-owned chunks, whose owner
+ *   becomes KV.
+ * Checks, in this order: bad handle or n_slots < 0 -> INVALID; n_slots == 0 -> OK; slot range ->
+ * RANGE; any target slot not empty -> INVALID; explicit ids in order: id outside the pool -> RANGE,
+ * not FREE -> OWNED, repeated -> OWNED, ACT-owned without ALLOW_INFLATE -> OWNED; pool-chosen:
+ * too few chunks -> OOM. */
+int ellm_tensor_map_chunks(ellm_pool* pool, ellm_tensor_id id, int32_t first_slot, int32_t n_slots,
+                           const int32_t* chunk_ids, uint32_t flags);
+
+/* Undo a mapping of slots that hold no live token (slot index >= ceil(len / T_c)), e.g. a
+ * speculative pre-map (Sec. 3.1). Chunks become FREE, host slots are released.
+ * Checks: bad handle or n_slots < 0 -> INVALID; range -> RANGE; a slot below ceil(len / T_c)
+ * -> INVALID; an empty slot -> UNMAPPED. */
+int ellm_tensor_unmap_chunks(ellm_pool* pool, ellm_tensor_id id, int32_t first_slot, int32_t n_slots);
+
+/* Ownership transfer of FREE chunks between the two sides of the pool (Sec. 2.2.1 step 3 for
+ * new_owner = KV, "deflation" for new_owner = ACT). A chunk that already has new_owner is left
+ * as it is. Checks: n < 0 or bad owner -> INVALID; per id in order: outside pool -> RANGE,
+ * not FREE -> OWNED, repeated -> INVALID. */
+int ellm_pool_transfer(ellm_pool* pool, const int32_t* chunk_ids, int32_t n, int new_owner);
+
+/* Stand-in for live activation tensors (the paper's activation allocator and its garbage
+ * collection, Sec. 2.2.1 step 2, are outside this library): mark ACT-owned chunks BUSY (busy = 1,
+ * they must be FREE) or FREE again (busy = 0, they must be BUSY).
+ * Checks per id in order: outside pool -> RANGE, not ACT-owned -> OWNED, wrong state -> OWNED for
+ * busy = 1 / INVALID for busy = 0, repeated -> INVALID. */
+int ellm_pool_set_act_busy(ellm_pool* pool, const int32_t* chunk_ids, int32_t n, int busy);
+
+/* Append new tokens to a batch of tensors (Sec. 3.1: one token per sequence per decode iteration;
+ * n_new > 1 is the prefill-side write).
+ *   ids (host): batch distinct handles. n_new (host): tokens per request, NULL = 1 each.
+ *   k_new, v_new (device): [sum(n_new)][n_kv_heads][head_dim] bf16, request b's tokens start at row
+ *   sum(n_new[0..b)). Token i of request b is written at position len_b + i; afterwards
+ *   len_b += n_new[b]. Enqueued on `stream` (a hipStream_t); returns without waiting.
+ * Checks: batch < 0 -> INVALID; per request in order: bad or repeated handle, n_new < 0 -> INVALID;
+ * len + n_new > max_tokens -> RANGE; slots covering the new tokens in ascending order: empty ->
+ * UNMAPPED, on host -> NOT_RESIDENT. NULL k_new / v_new with tokens to write -> INVALID. */
+int ellm_kv_append(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, const int32_t* n_new,
+                   const void* k_new, const void* v_new, void* stream);
+
+/* Batched decode attention: one query token per request over its whole cached context.
+ *   q (device): [batch][n_q_heads][head_dim] bf16; out (device): same shape, bf16.
+ *   For q head h, kv head g = h / G:  s_t = scale * <q_h, K_t,g>,  w = softmax_t(s),
+ *   out_h = sum_t w_t * V_t,g  for t = 0 .. len-1, no mask. scale = 0 selects 1/sqrt(head_dim).
+ *   fp32 arithmetic, output rounded to nearest-even bf16. Split over the sequence with a partition
+ *   that depends only on the lengths in the batch and the pool geometry, never on physical chunk
+ *   ids, so results are bitwise reproducible and invariant under remapping.
+ * Checks: batch < 0, NULL q / out, non-finite scale -> INVALID; per request in order: bad handle ->
+ * INVALID, len == 0 -> EMPTY; slots 0 .. ceil(len / T_c) - 1 ascending: empty -> UNMAPPED, on host
+ * -> NOT_RESIDENT. Enqueued on `stream`; returns without waiting. */
+int ellm_decode_attention(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, const void* q,
+                          void* out, float scale, void* stream);
+
+/* Offload (Sec. 2.2.2): copy the chunks of slots [first_slot, first_slot + n_slots) to host
+ * slots (lowest free host slot first, slots in ascending order), free the device chunks (owner
+ * stays KV), entry := host code. Copies run on the library's side stream after everything
+ * enqueued so far on the last stream passed to append / decode; later append / decode calls wait
+ * for them on their stream.
+ * Checks: bad handle, n_slots < 0 -> INVALID; range -> RANGE; slots ascending: empty -> UNMAPPED,
+ * already on host -> NOT_RESIDENT; fewer than n_slots free host slots -> HOST_FULL. */
+int ellm_chunk_deflate_to_host(ellm_pool* pool, ellm_tensor_id id, int32_t first_slot, int32_t n_slots);
+
+/* Fetch (Sec. 2.2.2): bring host-resident slots back into FREE KV-owned device chunks
+ * (explicit ids, or NULL = lowest-numbered first; never takes ACT-owned chunks — transfer them
+ * first), release the host slots, entry := new chunk id. Same ordering rules as offload.
+ * Checks: bad handle, n_slots < 0 -> INVALID; range -> RANGE; slots ascending: empty -> UNMAPPED,
+ * already on device -> INVALID; explicit ids in order: outside pool -> RANGE, not FREE / repeated /
+ * ACT-owned -> OWNED; pool-chosen: too few -> OOM. */
+int ellm_chunk_inflate_from_host(ellm_pool* pool, ellm_tensor_id id, int32_t first_slot, int32_t n_slots,
+                                 const int32_t* chunk_ids);
+
+/* Block until all migrations enqueued so far have finished. Returns HIP on an asynchronous fault. */
+int ellm_pool_sync(ellm_pool* pool);
+
+/* ---- introspection (host state, for bit-exact checks) -------------------------------------- */
+/* Geometry: any out pointer may be NULL. */
+int ellm_pool_get_geometry(ellm_pool* pool, int32_t* n_chunks, int32_t* tokens_per_chunk,
+                           int32_t* n_host_slots, uint64_t* bytes_per_token);
+/* Copies min(cap, n_slots) table entries to out (host); n_slots / len may be NULL. */
+int ellm_tensor_get_table(ellm_pool* pool, ellm_tensor_id id, int32_t* out, int32_t cap,
+                          int32_t* n_slots, int64_t* len);
+/* Per chunk (host arrays of n_chunks, any may be NULL): owner, state, and for MAPPED chunks the
+ * (tensor, slot) they back, else -1. */
+int ellm_pool_get_owner_state(ellm_pool* pool, uint8_t* owner, uint8_t* state,
+                              int32_t* mapped_tensor, int32_t* mapped_slot);
+/* Per host slot (host arrays of n_host_slots, any may be NULL): the (tensor, slot) stored, else -1. */
+int ellm_pool_get_host_slots(ellm_pool* pool, int32_t* tensor, int32_t* slot);
+/* Number of sequence splits the next decode over these handles would use per request
+ * (host array of batch), and the tokens per split. For tests of the split partition. */
+int ellm_decode_plan(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch,
+                     int32_t* n_split, int32_t* split_tokens);
+/* Override the split size (tokens, 0 = automatic). For tests that compare partitions. */
+int ellm_pool_set_split_tokens(ellm_pool* pool, int32_t split_tokens);
+
+/* Text of the last error raised on this thread (never NULL). */
+const char* ellm_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ELLM_H */

@@ -1,0 +1,39 @@
+"""Each planted mistake in the oracle (built as a separate, deliberately wrong library on the CPU)
+must fail at least one pin. This shows the pins are sharp enough to notice a dropped term, a wrong
+head mapping, swapped planes, a transposed layout, a missing normalisation, a stale newest token,
+a wrong allocation order and broken migration bookkeeping."""
+import os
+
+import pytest
+
+import oracle
+from oracle import build
+from tests import oracle_pins as P
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+MUTANTS = {
+    1: "q head -> kv head by modulo instead of contiguous groups",
+    2: "softmax scale dropped",
+    3: "K and V planes swapped",
+    4: "weights not normalised",
+    5: "newest token ignored",
+    6: "chunk layout plane-major instead of head-major",
+    7: "last dim dropped from the dot product",
+    8: "pool picks the highest free chunk",
+    9: "offload does not free the device chunk",
+    10: "fetch does not copy the bytes back",
+}
+
+
+@pytest.mark.parametrize("m", sorted(MUTANTS), ids=lambda m: f"mutant{m}")
+def test_mutant_is_caught(tmp_path, m):
+    lib = oracle.load(build.build(force=True, defines=(f"ORC_MUTANT={m}",), out=str(tmp_path / f"mut{m}.so")))
+    failed = []
+    pins = list(P.ALL_PINS) + [lambda l: P.pin_inflation_walkthrough(l, os.path.join(GOLDEN, "inflation_walkthrough.txt"))]
+    for pin in pins:
+        try:
+            pin(lib)
+        except AssertionError:
+            failed.append(getattr(pin, "__name__", "walkthrough"))
+    assert failed, f"no pin noticed: {MUTANTS[m]}"
