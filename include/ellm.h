@@ -222,6 +222,10 @@ int ellm_decode_plan(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch,
 /* Override the split size (tokens, 0 = automatic). For tests that compare partitions. */
 int ellm_pool_set_split_tokens(ellm_pool* pool, int32_t split_tokens);
 
+/* O(n) consistency scan of the host state (tables, chunk records, free lists, host slots agree;
+ * no chunk backs two slots). Returns 0 when consistent, else a positive rule number. */
+int ellm_pool_self_check(ellm_pool* pool);
+
 /* Text of the last error raised on this thread (never NULL). */
 const char* ellm_last_error(void);
 

@@ -1,0 +1,261 @@
+"""ctypes binding of libellm.so: the functions of include/ellm.h under the same names.
+
+Argument marshalling only. Device buffers are passed as torch tensors (or raw integer addresses),
+host arrays as numpy arrays or sequences; a negative return code raises EllmError carrying the
+code, unless `check=False` is given, in which case the code is returned.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libellm.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+        "or python paper_2506_15155_amd/build.py). There is no fallback implementation.")
+
+lib = C.CDLL(LIB_PATH)
+
+ELLM_OWNER_KV, ELLM_OWNER_ACT = 0, 1
+ELLM_CHUNK_FREE, ELLM_CHUNK_MAPPED, ELLM_CHUNK_BUSY = 0, 1, 2
+ELLM_BF16 = 1
+ELLM_MAP_ALLOW_INFLATE = 1
+ELLM_POOL_METADATA_ONLY = 1
+
+
+class ERR:
+    OK, INVALID, OOM, OWNED, UNMAPPED, NOT_RESIDENT, RANGE, EMPTY, HOST_FULL, HIP, NO_DEVICE = (
+        0, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10)
+
+
+class EllmError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libellm error {code}: {text}")
+        self.code = code
+
+
+class _Desc(C.Structure):
+    _fields_ = [("device_base", C.c_void_p), ("device_bytes", C.c_uint64),
+                ("host_base", C.c_void_p), ("host_bytes", C.c_uint64),
+                ("chunk_bytes", C.c_uint32),
+                ("n_q_heads", C.c_uint16), ("n_kv_heads", C.c_uint16), ("head_dim", C.c_uint16), ("dtype", C.c_uint16),
+                ("max_tensors", C.c_uint32), ("max_slots_per_tensor", C.c_uint32),
+                ("flags", C.c_uint32), ("reserved", C.c_uint32),
+                ("initial_owner", C.c_void_p)]
+
+
+_i32p = C.POINTER(C.c_int32)
+_vp = C.c_void_p
+_sigs = {
+    "ellm_pool_create": [C.POINTER(_Desc), C.POINTER(_vp)],
+    "ellm_pool_destroy": [_vp],
+    "ellm_tensor_create": [_vp, C.c_int64, _i32p],
+    "ellm_tensor_destroy": [_vp, C.c_int32],
+    "ellm_tensor_map_chunks": [_vp, C.c_int32, C.c_int32, C.c_int32, _i32p, C.c_uint32],
+    "ellm_tensor_unmap_chunks": [_vp, C.c_int32, C.c_int32, C.c_int32],
+    "ellm_pool_transfer": [_vp, _i32p, C.c_int32, C.c_int],
+    "ellm_pool_set_act_busy": [_vp, _i32p, C.c_int32, C.c_int],
+    "ellm_kv_append": [_vp, _i32p, C.c_int32, _i32p, _vp, _vp, _vp],
+    "ellm_decode_attention": [_vp, _i32p, C.c_int32, _vp, _vp, C.c_float, _vp],
+    "ellm_chunk_deflate_to_host": [_vp, C.c_int32, C.c_int32, C.c_int32],
+    "ellm_chunk_inflate_from_host": [_vp, C.c_int32, C.c_int32, C.c_int32, _i32p],
+    "ellm_pool_sync": [_vp],
+    "ellm_pool_get_geometry": [_vp, _i32p, _i32p, _i32p, C.POINTER(C.c_uint64)],
+    "ellm_tensor_get_table": [_vp, C.c_int32, _i32p, C.c_int32, _i32p, C.POINTER(C.c_int64)],
+    "ellm_pool_get_owner_state": [_vp, _vp, _vp, _i32p, _i32p],
+    "ellm_pool_get_host_slots": [_vp, _i32p, _i32p],
+    "ellm_decode_plan": [_vp, _i32p, C.c_int32, _i32p, _i32p],
+    "ellm_pool_set_split_tokens": [_vp, C.c_int32],
+    "ellm_pool_self_check": [_vp],
+}
+for _n, _a in _sigs.items():
+    getattr(lib, _n).argtypes = _a
+    getattr(lib, _n).restype = C.c_int
+lib.ellm_last_error.restype = C.c_char_p
+lib.ellm_last_error.argtypes = []
+
+EXPORTED = sorted(list(_sigs) + ["ellm_last_error"])
+
+
+def ellm_last_error() -> str:
+    return lib.ellm_last_error().decode()
+
+
+def _ret(rc: int, check: bool):
+    if rc < 0 and check:
+        raise EllmError(rc, ellm_last_error())
+    return rc
+
+
+def _ptr(x) -> int | None:
+    """Device or host address of a torch tensor / numpy array / int."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
+    raise TypeError(type(x))
+
+
+def _i32(a):
+    if a is None:
+        return None, None, 0
+    arr = np.ascontiguousarray(a, dtype=np.int32)
+    return arr, arr.ctypes.data_as(_i32p), arr.size
+
+
+def _stream(stream) -> int | None:
+    """hipStream_t of a torch stream (or a raw handle). None selects torch's current stream."""
+    if stream is None:
+        import torch
+        if not torch.cuda.is_available():
+            return None
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def ellm_pool_create(device_buf, host_buf, chunk_bytes, n_q_heads, n_kv_heads, head_dim, max_tensors,
+                     max_slots_per_tensor, initial_owner=None, flags=0, device_bytes=None, host_bytes=None,
+                     check=True):
+    """device_buf / host_buf: torch uint8 tensors (device / pinned host), or None. Returns the pool
+    handle (an int); with check=False returns (rc, handle)."""
+    d = _Desc()
+    d.device_base = _ptr(device_buf)
+    d.device_bytes = device_bytes if device_bytes is not None else (device_buf.numel() * device_buf.element_size()
+                                                                     if device_buf is not None else 0)
+    d.host_base = _ptr(host_buf)
+    d.host_bytes = host_bytes if host_bytes is not None else (host_buf.numel() * host_buf.element_size()
+                                                               if host_buf is not None else 0)
+    d.chunk_bytes, d.n_q_heads, d.n_kv_heads, d.head_dim, d.dtype = chunk_bytes, n_q_heads, n_kv_heads, head_dim, ELLM_BF16
+    d.max_tensors, d.max_slots_per_tensor, d.flags, d.reserved = max_tensors, max_slots_per_tensor, flags, 0
+    own = None
+    if initial_owner is not None:
+        own = np.ascontiguousarray(initial_owner, dtype=np.uint8)
+        d.initial_owner = own.ctypes.data
+    out = _vp()
+    rc = lib.ellm_pool_create(C.byref(d), C.byref(out))
+    if check:
+        _ret(rc, True)
+        return out.value
+    return rc, out.value
+
+
+def ellm_pool_destroy(pool, check=True):
+    return _ret(lib.ellm_pool_destroy(pool), check)
+
+
+def ellm_tensor_create(pool, max_tokens, check=True):
+    out = C.c_int32(-1)
+    rc = lib.ellm_tensor_create(pool, int(max_tokens), C.byref(out))
+    if check:
+        _ret(rc, True)
+        return out.value
+    return rc, out.value
+
+
+def ellm_tensor_destroy(pool, tid, check=True):
+    return _ret(lib.ellm_tensor_destroy(pool, tid), check)
+
+
+def ellm_tensor_map_chunks(pool, tid, first_slot, n_slots, chunk_ids=None, flags=0, check=True):
+    _, p, _ = _i32(chunk_ids)
+    return _ret(lib.ellm_tensor_map_chunks(pool, tid, first_slot, n_slots, p, flags), check)
+
+
+def ellm_tensor_unmap_chunks(pool, tid, first_slot, n_slots, check=True):
+    return _ret(lib.ellm_tensor_unmap_chunks(pool, tid, first_slot, n_slots), check)
+
+
+def ellm_pool_transfer(pool, chunk_ids, new_owner, check=True):
+    _, p, n = _i32(chunk_ids)
+    return _ret(lib.ellm_pool_transfer(pool, p, n, new_owner), check)
+
+
+def ellm_pool_set_act_busy(pool, chunk_ids, busy, check=True):
+    _, p, n = _i32(chunk_ids)
+    return _ret(lib.ellm_pool_set_act_busy(pool, p, n, int(busy)), check)
+
+
+def ellm_kv_append(pool, ids, k_new, v_new, n_new=None, stream=None, check=True):
+    _, p, n = _i32(ids)
+    _, pn, _ = _i32(n_new)
+    s = _stream(stream)
+    return _ret(lib.ellm_kv_append(pool, p, n, pn, _ptr(k_new), _ptr(v_new), s), check)
+
+
+def ellm_decode_attention(pool, ids, q, out, scale=0.0, stream=None, check=True):
+    _, p, n = _i32(ids)
+    s = _stream(stream)
+    return _ret(lib.ellm_decode_attention(pool, p, n, _ptr(q), _ptr(out), float(scale), s), check)
+
+
+def ellm_chunk_deflate_to_host(pool, tid, first_slot, n_slots, check=True):
+    return _ret(lib.ellm_chunk_deflate_to_host(pool, tid, first_slot, n_slots), check)
+
+
+def ellm_chunk_inflate_from_host(pool, tid, first_slot, n_slots, chunk_ids=None, check=True):
+    _, p, _ = _i32(chunk_ids)
+    return _ret(lib.ellm_chunk_inflate_from_host(pool, tid, first_slot, n_slots, p), check)
+
+
+def ellm_pool_sync(pool, check=True):
+    return _ret(lib.ellm_pool_sync(pool), check)
+
+
+def ellm_pool_get_geometry(pool):
+    a, b, c, d = C.c_int32(), C.c_int32(), C.c_int32(), C.c_uint64()
+    _ret(lib.ellm_pool_get_geometry(pool, C.byref(a), C.byref(b), C.byref(c), C.byref(d)), True)
+    return {"n_chunks": a.value, "tokens_per_chunk": b.value, "n_host_slots": c.value, "bytes_per_token": d.value}
+
+
+def ellm_tensor_get_table(pool, tid):
+    ns, ln = C.c_int32(), C.c_int64()
+    _ret(lib.ellm_tensor_get_table(pool, tid, None, 0, C.byref(ns), C.byref(ln)), True)
+    out = np.empty(ns.value, np.int32)
+    _ret(lib.ellm_tensor_get_table(pool, tid, out.ctypes.data_as(_i32p), ns.value, None, None), True)
+    return out, ln.value
+
+
+def ellm_pool_get_owner_state(pool):
+    n = ellm_pool_get_geometry(pool)["n_chunks"]
+    o, s = np.empty(n, np.uint8), np.empty(n, np.uint8)
+    mt, ms = np.empty(n, np.int32), np.empty(n, np.int32)
+    _ret(lib.ellm_pool_get_owner_state(pool, o.ctypes.data, s.ctypes.data, mt.ctypes.data_as(_i32p),
+                                       ms.ctypes.data_as(_i32p)), True)
+    return o, s, mt, ms
+
+
+def ellm_pool_get_host_slots(pool):
+    n = ellm_pool_get_geometry(pool)["n_host_slots"]
+    t, s = np.empty(max(n, 1), np.int32), np.empty(max(n, 1), np.int32)
+    _ret(lib.ellm_pool_get_host_slots(pool, t.ctypes.data_as(_i32p), s.ctypes.data_as(_i32p)), True)
+    return t[:n], s[:n]
+
+
+def ellm_decode_plan(pool, ids, check=True):
+    a, p, n = _i32(ids)
+    ns = np.zeros(max(n, 1), np.int32)
+    st = C.c_int32()
+    rc = lib.ellm_decode_plan(pool, p, n, ns.ctypes.data_as(_i32p), C.byref(st))
+    if check:
+        _ret(rc, True)
+        return ns[:n], st.value
+    return rc
+
+
+def ellm_pool_set_split_tokens(pool, split_tokens, check=True):
+    return _ret(lib.ellm_pool_set_split_tokens(pool, split_tokens), check)
+
+
+def ellm_pool_self_check(pool):
+    return lib.ellm_pool_self_check(pool)

@@ -1,0 +1,495 @@
+// C-ABI layer of libellm: argument checks, host state machine calls, stream ordering, launches.
+// The contract of every entry point is stated in include/ellm.h.
+#include "ellm.h"
+
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "kernels.hpp"
+#include "pool_core.hpp"
+
+namespace {
+
+thread_local std::string g_last_error = "";
+
+int set_err(int code, const std::string& text) {
+  g_last_error = text;
+  return code;
+}
+
+int hip_err(hipError_t e, const char* where) {
+  char buf[256];
+  snprintf(buf, sizeof buf, "%s: %s", where, hipGetErrorString(e));
+  return set_err(ELLM_ERR_HIP, buf);
+}
+
+#define HIP_TRY(call, where)                          \
+  do {                                                \
+    hipError_t e_ = (call);                           \
+    if (e_ != hipSuccess) return hip_err(e_, where);  \
+  } while (0)
+
+}  // namespace
+
+struct ellm_pool {
+  ellm::Geometry geom;
+  std::unique_ptr<ellm::PoolCore> core;
+  char* device_base = nullptr;
+  char* host_base = nullptr;
+  bool metadata_only = false;
+
+  // device-side metadata, created by the first call that needs the device
+  bool dev_ready = false;
+  int32_t* d_table = nullptr;
+  float* d_ws = nullptr;
+  size_t ws_bytes = 0;
+  hipStream_t side = nullptr;          // migrations
+  hipEvent_t ev_compute = nullptr;     // "everything enqueued so far on the compute stream"
+  hipEvent_t ev_migrate = nullptr;     // "everything enqueued so far on the side stream"
+  bool migrate_pending = false;        // compute streams must wait for ev_migrate
+  hipStream_t last_stream = nullptr;   // last stream given to append / decode
+  bool have_last_stream = false;
+  int32_t split_override = 0;
+
+  // scratch reused across calls
+  std::vector<int32_t> n_eff;
+  std::vector<ellm::Move> moves;
+};
+
+namespace {
+
+using ellm::PoolCore;
+
+int core_err(ellm_pool* p, int rc) {
+  if (rc) g_last_error = p->core->err();
+  return rc;
+}
+
+ellm::PoolView view_of(const ellm_pool* p) {
+  ellm::PoolView v;
+  v.base = p->device_base;
+  v.table = p->d_table;
+  v.chunk_bytes = p->geom.chunk_bytes;
+  v.tokens_per_chunk = p->geom.tokens_per_chunk;
+  v.max_slots = p->geom.max_slots;
+  v.n_q_heads = p->geom.n_q_heads;
+  v.n_kv_heads = p->geom.n_kv_heads;
+  v.head_dim = p->geom.head_dim;
+  v.group = p->geom.group;
+  return v;
+}
+
+int ensure_device(ellm_pool* p) {
+  if (p->dev_ready) return ELLM_OK;
+  const size_t bytes = p->core->table().size() * sizeof(int32_t);
+  HIP_TRY(hipMalloc((void**)&p->d_table, bytes), "hipMalloc(table mirror)");
+  HIP_TRY(hipMemcpy(p->d_table, p->core->table().data(), bytes, hipMemcpyHostToDevice), "hipMemcpy(table mirror)");
+  (void)p->core->take_dirty();   // the full upload covers everything so far
+  HIP_TRY(hipStreamCreateWithFlags(&p->side, hipStreamNonBlocking), "hipStreamCreate(side)");
+  HIP_TRY(hipEventCreateWithFlags(&p->ev_compute, hipEventDisableTiming), "hipEventCreate");
+  HIP_TRY(hipEventCreateWithFlags(&p->ev_migrate, hipEventDisableTiming), "hipEventCreate");
+  p->dev_ready = true;
+  return ELLM_OK;
+}
+
+// push host-side table changes to the device mirror, ordered on `stream`
+int flush_table(ellm_pool* p, hipStream_t stream) {
+  if (!p->core->has_dirty()) return ELLM_OK;
+  std::vector<int64_t> dirty = p->core->take_dirty();
+  const std::vector<int32_t>& tab = p->core->table();
+  if (dirty.size() > 16 * (size_t)ellm::MAX_PATCH) {
+    // bulk change (initial mapping of a large batch): one blocking copy of the whole mirror
+    HIP_TRY(hipStreamSynchronize(stream), "hipStreamSynchronize(table upload)");
+    HIP_TRY(hipMemcpy(p->d_table, tab.data(), tab.size() * sizeof(int32_t), hipMemcpyHostToDevice),
+            "hipMemcpy(table upload)");
+    return ELLM_OK;
+  }
+  ellm::PatchArgs a;
+  size_t i = 0;
+  while (i < dirty.size()) {
+    a.n = 0;
+    for (; i < dirty.size() && a.n < ellm::MAX_PATCH; i++, a.n++) {
+      a.idx[a.n] = (int32_t)dirty[i];
+      a.val[a.n] = tab[dirty[i]];
+    }
+    int e = ellm::launch_table_patch(p->d_table, a, stream);
+    if (e) return hip_err((hipError_t)e, "table patch launch");
+  }
+  return ELLM_OK;
+}
+
+// things every compute call does before launching on `stream`
+int enter_compute(ellm_pool* p, hipStream_t stream) {
+  int rc = ensure_device(p);
+  if (rc) return rc;
+  if (p->migrate_pending) {
+    HIP_TRY(hipStreamWaitEvent(stream, p->ev_migrate, 0), "hipStreamWaitEvent(migration)");
+    p->migrate_pending = false;
+  }
+  rc = flush_table(p, stream);
+  if (rc) return rc;
+  p->last_stream = stream;
+  p->have_last_stream = true;
+  return ELLM_OK;
+}
+
+// side stream waits for everything enqueued so far on the last compute stream
+int enter_migration(ellm_pool* p) {
+  int rc = ensure_device(p);
+  if (rc) return rc;
+  if (p->have_last_stream) {
+    HIP_TRY(hipEventRecord(p->ev_compute, p->last_stream), "hipEventRecord(compute)");
+    HIP_TRY(hipStreamWaitEvent(p->side, p->ev_compute, 0), "hipStreamWaitEvent(compute)");
+  }
+  return ELLM_OK;
+}
+
+int leave_migration(ellm_pool* p) {
+  HIP_TRY(hipEventRecord(p->ev_migrate, p->side), "hipEventRecord(migration)");
+  p->migrate_pending = true;
+  return ELLM_OK;
+}
+
+int ensure_workspace(ellm_pool* p, int64_t n_items) {
+  const size_t need = (size_t)n_items * p->geom.n_q_heads * (p->geom.head_dim + 2) * sizeof(float);
+  if (need <= p->ws_bytes) return ELLM_OK;
+  if (p->d_ws) {
+    HIP_TRY(hipDeviceSynchronize(), "hipDeviceSynchronize(workspace growth)");
+    HIP_TRY(hipFree(p->d_ws), "hipFree(workspace)");
+    p->d_ws = nullptr;
+    p->ws_bytes = 0;
+  }
+  const size_t grow = need + need / 4;
+  HIP_TRY(hipMalloc((void**)&p->d_ws, grow), "hipMalloc(workspace)");
+  p->ws_bytes = grow;
+  return ELLM_OK;
+}
+
+// Tokens per work item. Depends only on the batch's lengths and the pool geometry (never on
+// physical chunk ids), so the partition and with it every rounding is reproducible and invariant
+// under remapping. Aims at enough workgroups to fill 256 compute units several times over while
+// keeping the partials small next to the K/V bytes.
+int32_t choose_split(const ellm_pool* p, const int32_t* ids, int32_t batch) {
+  if (p->split_override > 0) return p->split_override;
+  const int32_t Tc = p->geom.tokens_per_chunk;
+  int64_t total = 0;
+  for (int32_t b = 0; b < batch; b++) total += p->core->tensor(ids[b])->len;
+  const int64_t want_groups = 2048;
+  int64_t s = total * p->geom.n_kv_heads / want_groups;
+  s = std::max<int64_t>(128, std::min<int64_t>(2048, s));
+  if (s >= Tc) return (int32_t)std::max<int64_t>(Tc, (s / Tc) * Tc);   // whole chunks
+  int32_t parts = (int32_t)((Tc + s - 1) / s);                           // equal parts of a chunk
+  int32_t part = (Tc + parts - 1) / parts;
+  return (part + 15) / 16 * 16 >= Tc ? Tc : (part + 15) / 16 * 16;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+extern "C" {
+
+const char* ellm_last_error(void) { return g_last_error.c_str(); }
+
+int ellm_pool_create(const ellm_pool_desc* d, ellm_pool** out) {
+  if (!d || !out) return set_err(ELLM_ERR_INVALID, "pool_create: NULL argument");
+  *out = nullptr;
+  const bool meta = (d->flags & ELLM_POOL_METADATA_ONLY) != 0;
+  if (d->flags & ~ELLM_POOL_METADATA_ONLY || d->reserved) return set_err(ELLM_ERR_INVALID, "pool_create: unknown flags");
+  if (d->dtype != ELLM_BF16) return set_err(ELLM_ERR_INVALID, "pool_create: dtype must be ELLM_BF16");
+  if (d->head_dim != 64 && d->head_dim != 128) return set_err(ELLM_ERR_INVALID, "pool_create: head_dim must be 64 or 128");
+  if (!d->n_kv_heads || !d->n_q_heads || d->n_q_heads % d->n_kv_heads || d->n_q_heads / d->n_kv_heads > 64)
+    return set_err(ELLM_ERR_INVALID, "pool_create: n_q_heads must be a multiple (<= 64x) of n_kv_heads");
+  if (!d->chunk_bytes || d->chunk_bytes % 256) return set_err(ELLM_ERR_INVALID, "pool_create: chunk_bytes must be a positive multiple of 256");
+  const uint64_t bpt = 2ull * d->n_kv_heads * d->head_dim * 2ull;
+  if (d->chunk_bytes < bpt) return set_err(ELLM_ERR_INVALID, "pool_create: a chunk must hold at least one token");
+  const uint64_t n_chunks = d->device_bytes / d->chunk_bytes;
+  const uint64_t n_host = d->host_bytes / d->chunk_bytes;
+  if (n_chunks < 1 || n_chunks > 0x7ffffff0ull || n_host > 0x7ffffff0ull)
+    return set_err(ELLM_ERR_INVALID, "pool_create: pool must hold between 1 and 2^31 chunks");
+  if (!meta && (!d->device_base || ((uintptr_t)d->device_base & 255)))
+    return set_err(ELLM_ERR_INVALID, "pool_create: device_base must be a 256-byte aligned device pointer");
+  if (!meta && n_host > 0 && !d->host_base) return set_err(ELLM_ERR_INVALID, "pool_create: host_base missing");
+  if (!d->max_tensors || !d->max_slots_per_tensor ||
+      (uint64_t)d->max_tensors * d->max_slots_per_tensor > 0x7fffffffull)
+    return set_err(ELLM_ERR_INVALID, "pool_create: max_tensors * max_slots_per_tensor must be in 1 .. 2^31-1");
+  if (d->initial_owner)
+    for (uint64_t c = 0; c < n_chunks; c++)
+      if (d->initial_owner[c] > ELLM_OWNER_ACT) return set_err(ELLM_ERR_INVALID, "pool_create: bad initial owner");
+
+  ellm_pool* p = new ellm_pool();
+  p->geom.n_chunks = (int32_t)n_chunks;
+  p->geom.n_host_slots = (int32_t)n_host;
+  p->geom.chunk_bytes = d->chunk_bytes;
+  p->geom.bytes_per_token = bpt;
+  p->geom.tokens_per_chunk = (int32_t)(d->chunk_bytes / bpt);
+  p->geom.n_q_heads = d->n_q_heads;
+  p->geom.n_kv_heads = d->n_kv_heads;
+  p->geom.head_dim = d->head_dim;
+  p->geom.group = d->n_q_heads / d->n_kv_heads;
+  p->geom.max_tensors = (int32_t)d->max_tensors;
+  p->geom.max_slots = (int32_t)d->max_slots_per_tensor;
+  p->core.reset(new PoolCore(p->geom, d->initial_owner));
+  p->device_base = (char*)d->device_base;
+  p->host_base = (char*)d->host_base;
+  p->metadata_only = meta;
+  *out = p;
+  return ELLM_OK;
+}
+
+int ellm_pool_destroy(ellm_pool* p) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "pool_destroy: NULL pool");
+  int rc = ELLM_OK;
+  if (p->dev_ready) {
+    if (hipStreamSynchronize(p->side) != hipSuccess) rc = ELLM_ERR_HIP;
+    if (p->have_last_stream && hipStreamSynchronize(p->last_stream) != hipSuccess) rc = ELLM_ERR_HIP;
+    (void)hipStreamDestroy(p->side);
+    (void)hipEventDestroy(p->ev_compute);
+    (void)hipEventDestroy(p->ev_migrate);
+    (void)hipFree(p->d_table);
+    if (p->d_ws) (void)hipFree(p->d_ws);
+  }
+  delete p;
+  return rc;
+}
+
+int ellm_tensor_create(ellm_pool* p, int64_t max_tokens, ellm_tensor_id* out) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  return core_err(p, p->core->tensor_create(max_tokens, out));
+}
+
+int ellm_tensor_destroy(ellm_pool* p, ellm_tensor_id id) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  return core_err(p, p->core->tensor_destroy(id));
+}
+
+int ellm_tensor_map_chunks(ellm_pool* p, ellm_tensor_id id, int32_t first_slot, int32_t n_slots,
+                           const int32_t* chunk_ids, uint32_t flags) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  return core_err(p, p->core->map_chunks(id, first_slot, n_slots, chunk_ids, flags));
+}
+
+int ellm_tensor_unmap_chunks(ellm_pool* p, ellm_tensor_id id, int32_t first_slot, int32_t n_slots) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  return core_err(p, p->core->unmap_chunks(id, first_slot, n_slots));
+}
+
+int ellm_pool_transfer(ellm_pool* p, const int32_t* chunk_ids, int32_t n, int new_owner) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  return core_err(p, p->core->transfer(chunk_ids, n, new_owner));
+}
+
+int ellm_pool_set_act_busy(ellm_pool* p, const int32_t* chunk_ids, int32_t n, int busy) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  return core_err(p, p->core->set_act_busy(chunk_ids, n, busy));
+}
+
+int ellm_kv_append(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const int32_t* n_new,
+                   const void* k_new, const void* v_new, void* stream_) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  int64_t total = 0;
+  int rc = core_err(p, p->core->append_check(ids, batch, n_new, p->n_eff, &total));
+  if (rc) return rc;
+  if (total > 0 && (!k_new || !v_new)) return set_err(ELLM_ERR_INVALID, "kv_append: NULL k_new / v_new");
+  if (total > 0x7fffffffll / (2 * p->geom.n_kv_heads)) return set_err(ELLM_ERR_RANGE, "kv_append: too many tokens in one call");
+  if (total > 0 && !p->metadata_only) {
+    hipStream_t stream = (hipStream_t)stream_;
+    rc = enter_compute(p, stream);
+    if (rc) return rc;
+    const ellm::PoolView pv = view_of(p);
+    const size_t tok_bytes = (size_t)p->geom.n_kv_heads * p->geom.head_dim * 2;
+    ellm::AppendArgs a;
+    int64_t row0 = 0;
+    for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
+      const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
+      a.n_req = nb;
+      int32_t t = 0;
+      for (int32_t i = 0; i < nb; i++) {
+        a.tensor[i] = ids[b0 + i];
+        a.len_before[i] = (int32_t)p->core->tensor(ids[b0 + i])->len;
+        a.tok0[i] = t;
+        t += p->n_eff[b0 + i];
+      }
+      a.total_new = t;
+      int e = ellm::launch_kv_append(pv, (const char*)k_new + row0 * tok_bytes, (const char*)v_new + row0 * tok_bytes,
+                                     a, stream);
+      if (e) return hip_err((hipError_t)e, "kv_append launch");
+      row0 += t;
+    }
+  }
+  p->core->append_commit(ids, batch, p->n_eff);
+  return ELLM_OK;
+}
+
+static int build_plan(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, int32_t* split_out,
+                      std::vector<int32_t>* n_split) {
+  const int32_t S = choose_split(p, ids, batch);
+  *split_out = S;
+  if (n_split) {
+    n_split->resize(batch);
+    for (int32_t b = 0; b < batch; b++) {
+      const int64_t len = p->core->tensor(ids[b])->len;
+      (*n_split)[b] = (int32_t)((len + S - 1) / S);
+    }
+  }
+  return ELLM_OK;
+}
+
+int ellm_decode_plan(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, int32_t* n_split, int32_t* split_tokens) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  int rc = core_err(p, p->core->decode_check(ids, batch));
+  if (rc) return rc;
+  int32_t S = 0;
+  std::vector<int32_t> ns;
+  build_plan(p, ids, batch, &S, &ns);
+  if (n_split) std::copy(ns.begin(), ns.end(), n_split);
+  if (split_tokens) *split_tokens = S;
+  return ELLM_OK;
+}
+
+int ellm_pool_set_split_tokens(ellm_pool* p, int32_t split_tokens) {
+  if (!p || split_tokens < 0) return set_err(ELLM_ERR_INVALID, "set_split_tokens: bad argument");
+  p->split_override = split_tokens;
+  return ELLM_OK;
+}
+
+int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const void* q, void* out,
+                          float scale, void* stream_) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  if (batch < 0 || !q || !out || !std::isfinite(scale)) return set_err(ELLM_ERR_INVALID, "decode_attention: bad argument");
+  int rc = core_err(p, p->core->decode_check(ids, batch));
+  if (rc) return rc;
+  if (batch == 0) return ELLM_OK;
+  if (p->metadata_only) return set_err(ELLM_ERR_NO_DEVICE, "decode_attention: pool has no device");
+  hipStream_t stream = (hipStream_t)stream_;
+  rc = enter_compute(p, stream);
+  if (rc) return rc;
+  if (scale == 0.f) scale = 1.0f / std::sqrt((float)p->geom.head_dim);
+  const float scale_log2 = scale * 1.4426950408889634f;
+
+  int32_t S = 0;
+  build_plan(p, ids, batch, &S, nullptr);
+  int64_t total_items = 0;
+  for (int32_t b = 0; b < batch; b++) total_items += (p->core->tensor(ids[b])->len + S - 1) / S;
+  if (total_items > 0x7fffffffll) return set_err(ELLM_ERR_RANGE, "decode_attention: too many work items");
+  rc = ensure_workspace(p, total_items);
+  if (rc) return rc;
+
+  const ellm::PoolView pv = view_of(p);
+  ellm::BatchArgs a;
+  int32_t item_base = 0;
+  for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
+    const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
+    a.n_req = nb;
+    a.item_base = item_base;
+    a.q_row0 = b0;
+    int32_t it = 0;
+    for (int32_t i = 0; i < nb; i++) {
+      const int64_t len = p->core->tensor(ids[b0 + i])->len;
+      a.tensor[i] = ids[b0 + i];
+      a.len[i] = (int32_t)len;
+      a.item0[i] = it;
+      it += (int32_t)((len + S - 1) / S);
+    }
+    a.n_items = it;
+    int e = ellm::launch_decode(pv, q, out, p->d_ws, scale_log2, S, a, stream);
+    if (e) return hip_err((hipError_t)e, "decode launch");
+    item_base += it;
+  }
+  return ELLM_OK;
+}
+
+int ellm_chunk_deflate_to_host(ellm_pool* p, ellm_tensor_id id, int32_t first_slot, int32_t n_slots) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  int rc = core_err(p, p->core->offload_plan(id, first_slot, n_slots, p->moves));
+  if (rc) return rc;
+  if (!p->moves.empty() && !p->metadata_only) {
+    rc = enter_migration(p);
+    if (rc) return rc;
+    const size_t cb = p->geom.chunk_bytes;
+    for (const ellm::Move& m : p->moves)
+      HIP_TRY(hipMemcpyAsync(p->host_base + (size_t)m.host_slot * cb, p->device_base + (size_t)m.chunk * cb, cb,
+                             hipMemcpyDeviceToHost, p->side), "hipMemcpyAsync(offload)");
+    rc = leave_migration(p);
+    if (rc) return rc;
+  }
+  p->core->offload_commit(id, p->moves);
+  return ELLM_OK;
+}
+
+int ellm_chunk_inflate_from_host(ellm_pool* p, ellm_tensor_id id, int32_t first_slot, int32_t n_slots,
+                                 const int32_t* chunk_ids) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  int rc = core_err(p, p->core->fetch_plan(id, first_slot, n_slots, chunk_ids, p->moves));
+  if (rc) return rc;
+  if (!p->moves.empty() && !p->metadata_only) {
+    rc = enter_migration(p);
+    if (rc) return rc;
+    const size_t cb = p->geom.chunk_bytes;
+    for (const ellm::Move& m : p->moves)
+      HIP_TRY(hipMemcpyAsync(p->device_base + (size_t)m.chunk * cb, p->host_base + (size_t)m.host_slot * cb, cb,
+                             hipMemcpyHostToDevice, p->side), "hipMemcpyAsync(fetch)");
+    rc = leave_migration(p);
+    if (rc) return rc;
+  }
+  p->core->fetch_commit(id, p->moves);
+  return ELLM_OK;
+}
+
+int ellm_pool_sync(ellm_pool* p) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  if (!p->dev_ready) return ELLM_OK;
+  HIP_TRY(hipStreamSynchronize(p->side), "hipStreamSynchronize(side)");
+  return ELLM_OK;
+}
+
+int ellm_pool_get_geometry(ellm_pool* p, int32_t* n_chunks, int32_t* tokens_per_chunk, int32_t* n_host_slots,
+                           uint64_t* bytes_per_token) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  if (n_chunks) *n_chunks = p->geom.n_chunks;
+  if (tokens_per_chunk) *tokens_per_chunk = p->geom.tokens_per_chunk;
+  if (n_host_slots) *n_host_slots = p->geom.n_host_slots;
+  if (bytes_per_token) *bytes_per_token = p->geom.bytes_per_token;
+  return ELLM_OK;
+}
+
+int ellm_tensor_get_table(ellm_pool* p, ellm_tensor_id id, int32_t* out, int32_t cap, int32_t* n_slots, int64_t* len) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  const ellm::TensorRec* t = p->core->tensor(id);
+  if (!t) return set_err(ELLM_ERR_INVALID, "get_table: bad tensor handle");
+  if (out && cap > 0) std::memcpy(out, p->core->row(id), sizeof(int32_t) * (size_t)std::min(cap, t->n_slots));
+  if (n_slots) *n_slots = t->n_slots;
+  if (len) *len = t->len;
+  return ELLM_OK;
+}
+
+int ellm_pool_get_owner_state(ellm_pool* p, uint8_t* owner, uint8_t* state, int32_t* mapped_tensor, int32_t* mapped_slot) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  const size_t n = (size_t)p->geom.n_chunks;
+  if (owner) std::memcpy(owner, p->core->owner().data(), n);
+  if (state) std::memcpy(state, p->core->state().data(), n);
+  if (mapped_tensor) std::memcpy(mapped_tensor, p->core->map_tensor().data(), n * sizeof(int32_t));
+  if (mapped_slot) std::memcpy(mapped_slot, p->core->map_slot().data(), n * sizeof(int32_t));
+  return ELLM_OK;
+}
+
+int ellm_pool_get_host_slots(ellm_pool* p, int32_t* tensor, int32_t* slot) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  const size_t n = (size_t)p->geom.n_host_slots;
+  if (tensor && n) std::memcpy(tensor, p->core->host_tensor().data(), n * sizeof(int32_t));
+  if (slot && n) std::memcpy(slot, p->core->host_slot().data(), n * sizeof(int32_t));
+  return ELLM_OK;
+}
+
+int ellm_pool_self_check(ellm_pool* p) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  return p->core->self_check();
+}
+
+}  // extern "C"

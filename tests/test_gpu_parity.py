@@ -1,0 +1,198 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same seeded
+inputs. Tables, owner/state arrays and migrated bytes bit-exact; bf16 attention output within
+max-abs 2e-2 and mean-abs 2e-3 of the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2506_15155_amd as E
+import workloads as W
+from tests import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def run_step(cfg, seed=None, keep_twin=False, split=None, owner_from_placement=True):
+    st = W.draw_step(cfg, seed)
+    B = H.Both(cfg, owner=st.placement.owner if cfg.act_fraction > 0 else None, keep_twin=keep_twin)
+    ids = H.load_step(B, st)
+    assert B.append(ids, st.k_new, st.v_new) == 0
+    if split:
+        E.ellm_pool_set_split_tokens(B.pool, split)
+    rc, out = B.decode(ids, st.q)
+    assert rc == 0
+    rco, ref = B.orc.decode(ids, st.q)
+    assert rco == 0
+    B.compare_state()
+    return B, st, ids, out, ref
+
+
+def test_tiny_config_exhaustive():
+    """Config 1 as stated: every output element, every table entry, every byte of every chunk."""
+    cfg = W.CONFIGS["tiny"]
+    st = W.draw_step(cfg)
+    B = H.Both(cfg, keep_twin=True)
+    poison = np.full(cfg.chunk_bytes // 2, H.POISON, np.uint16).view(np.uint8)
+    for c in range(cfg.n_chunks):
+        B.orc.chunk_set_bytes(c, poison)
+    ids = H.load_step(B, st)
+    assert B.append(ids, st.k_new, st.v_new) == 0
+    rc, out = B.decode(ids, st.q)
+    rco, ref = B.orc.decode(ids, st.q)
+    assert rc == 0 and rco == 0
+    H.check_close(out, ref, "tiny")
+    B.compare_state()
+    for c in range(cfg.n_chunks):      # appended rows landed exactly where the layout says, nothing else moved
+        assert np.array_equal(B.chunk_bytes_dev(c), B.orc.chunk_bytes_of(c)), c
+    lens = [E.ellm_tensor_get_table(B.pool, t)[1] for t in ids]
+    assert lens == [int(x) for x in st.lens]
+    B.close()
+
+
+@pytest.mark.parametrize("split", [16, 64, 256, 4096])
+def test_tiny_split_sizes(split):
+    """One split per request up to sixteen: all within tolerance of the oracle and of each other."""
+    B, st, ids, out, ref = run_step(W.CONFIGS["tiny"], split=split)
+    H.check_close(out, ref, f"split {split}")
+    E.ellm_pool_set_split_tokens(B.pool, 4096)
+    rc, one = B.decode(ids, st.q)
+    assert rc == 0
+    assert np.abs(H.out_f64(out) - H.out_f64(one)).max() <= 2 ** -6   # bf16 rounding of nearly equal fp32 sums
+    B.close()
+
+
+def test_run_to_run_bitwise_determinism():
+    B, st, ids, out, ref = run_step(W.CONFIGS["tiny"], split=32)
+    for _ in range(3):
+        rc, again = B.decode(ids, st.q)
+        assert rc == 0 and torch.equal(out, again)
+    B.close()
+
+
+REDUCED = {
+    # config-2 shapes, fewer and shorter requests: several chunks per request, ragged tails
+    "llama8b_small": W.scaled(W.CONFIGS["llama8b"], batch=12, n_chunks=96, len_lo=64, len_hi=2500, lognormal_median=700),
+    # config-3 shapes: 102 tokens per chunk with slack, half the pool busy activations
+    "mha13b_small": W.scaled(W.CONFIGS["mha13b"], batch=6, n_chunks=160, len_lo=90, len_hi=900, max_tokens=1020),
+    # config-5 shapes: group of 8
+    "long70b_small": W.scaled(W.CONFIGS["long70b"], batch=3, n_chunks=48, len_lo=1500, len_hi=6000, max_tokens=6144),
+}
+
+
+@pytest.mark.parametrize("name", sorted(REDUCED))
+def test_reduced_configs_elementwise(name):
+    B, st, ids, out, ref = run_step(REDUCED[name])
+    mx, mean = H.check_close(out, ref, name)
+    print(f"{name}: max-abs {mx:.2e} mean-abs {mean:.2e}")
+    B.close()
+
+
+@pytest.mark.parametrize("name,split", [("llama8b_small", 128), ("llama8b_small", 1024), ("mha13b_small", 102),
+                                        ("mha13b_small", 64), ("long70b_small", 512)])
+def test_reduced_configs_other_partitions(name, split):
+    B, st, ids, out, ref = run_step(REDUCED[name], split=split)
+    H.check_close(out, ref, f"{name}/{split}")
+    B.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(12, 2, 128), (6, 2, 64), (3, 1, 128), (32, 2, 64), (5, 5, 64)])
+def test_other_group_sizes(Hq, Hkv, D):
+    """Group sizes that are not 1, 2, 4 or 8 are covered by several launches over the same K/V."""
+    cfg = W.Config("g", 9, 5, Hq, Hkv, D, 24 * (2 * Hkv * D * 2), 64, 24 * 12, "uniform", 1, 24 * 12)
+    B, st, ids, out, ref = run_step(cfg, seed=77)
+    H.check_close(out, ref, f"Hq{Hq}/Hkv{Hkv}")
+    B.close()
+
+
+def test_batch_larger_than_one_launch():
+    """More requests than one launch's argument block describes (256)."""
+    cfg = W.Config("wide", 8, 300, 8, 2, 64, 16 * (2 * 2 * 64 * 2), 700, 32, "uniform", 1, 32)
+    B, st, ids, out, ref = run_step(cfg, seed=5)
+    H.check_close(out, ref, "batch 300")
+    B.close()
+
+
+def test_closed_forms_on_gpu():
+    cfg = W.scaled(W.CONFIGS["tiny"], batch=1)
+    rng = np.random.default_rng(3)
+    # L = 1: output is V[0] bit for bit
+    B = H.Both(cfg)
+    t = B.create(64)
+    assert B.map(t, 0, 1, [7]) == 0
+    k, v = W.normal_bf16(rng, (1, 8, 64)), W.normal_bf16(rng, (1, 8, 64))
+    assert B.append([t], k, v) == 0
+    q = W.normal_bf16(rng, (1, 8, 64))
+    rc, out = B.decode([t], q)
+    assert rc == 0 and np.array_equal(H.host_bits(out)[0], v[0])
+    # constant V over 100 tokens: weights sum to one, so the output is that constant (to bf16 rounding)
+    t2 = B.create(128)
+    assert B.map(t2, 0, 7, [1, 60, 2, 59, 3, 58, 4]) == 0
+    c = W.normal_bf16(rng, (8, 64))
+    vv = np.broadcast_to(c, (100, 8, 64)).copy()
+    kk = W.normal_bf16(rng, (100, 8, 64))
+    assert B.append([t2], kk, vv, [100]) == 0
+    rc, out = B.decode([t2], q)
+    cf = W.f32_from_bf16_bits(c).astype(np.float64)
+    assert rc == 0 and np.abs(H.out_f64(out)[0] - cf).max() <= np.abs(cf).max() * 2 ** -8
+    # q = 0: arithmetic mean of V
+    t3 = B.create(128)
+    assert B.map(t3, 0, 3) == 0
+    v3 = W.normal_bf16(rng, (37, 8, 64))
+    assert B.append([t3], W.normal_bf16(rng, (37, 8, 64)), v3, [37]) == 0
+    rc, out = B.decode([t3], np.zeros((1, 8, 64), np.uint16))
+    mean = W.f32_from_bf16_bits(v3).astype(np.float64).mean(axis=0)
+    assert rc == 0 and np.abs(H.out_f64(out)[0] - mean).max() <= 4e-3
+    B.close()
+
+
+def test_offload_fetch_remap_invariance_and_bytes():
+    """Offload two requests' chunks, fetch them into other chunks: tables match the oracle, migrated
+    bytes are identical (device before = host slot = device after), output bits do not change."""
+    cfg = W.scaled(W.CONFIGS["tiny"], host_slots=40, batch=4)
+    st = W.draw_step(cfg, seed=11)
+    B = H.Both(cfg)
+    poison = np.full(cfg.chunk_bytes // 2, H.POISON, np.uint16).view(np.uint8)
+    for c in range(cfg.n_chunks):
+        B.orc.chunk_set_bytes(c, poison)
+    ids = H.load_step(B, st)
+    assert B.append(ids, st.k_new, st.v_new) == 0
+    rc, before = B.decode(ids, st.q)
+    assert rc == 0
+    for b in (0, 2):
+        tab, _ = E.ellm_tensor_get_table(B.pool, ids[b])
+        live = int((tab >= 0).sum())
+        pre = [B.chunk_bytes_dev(int(c)) for c in tab[:live]]
+        assert B.offload(ids[b], 0, live) == 0
+        E.ellm_pool_sync(B.pool)
+        tabh, _ = E.ellm_tensor_get_table(B.pool, ids[b])
+        for i in range(live):
+            hs = -int(tabh[i]) - 2
+            assert np.array_equal(B.host_slot_bytes(hs), pre[i])
+            assert np.array_equal(B.orc.host_slot_bytes(hs), pre[i])
+        assert E.ellm_decode_attention(B.pool, ids, H.dev_bits(st.q), before.clone(), check=False) == E.ERR.NOT_RESIDENT
+        # land in other chunks than before: take the highest free ids
+        _, s, _, _ = E.ellm_pool_get_owner_state(B.pool)
+        free = [c for c in range(cfg.n_chunks - 1, -1, -1) if s[c] == 0 and c not in set(int(x) for x in tab[:live])][:live]
+        assert len(free) == live
+        assert B.fetch(ids[b], 0, live, free) == 0
+        E.ellm_pool_sync(B.pool)
+        for i in range(live):
+            assert np.array_equal(B.chunk_bytes_dev(free[i]), pre[i])
+    B.compare_state()
+    rc, after = B.decode(ids, st.q)
+    assert rc == 0 and torch.equal(before, after)
+    B.close()
+
+
+def test_error_paths_launch_nothing():
+    cfg = W.scaled(W.CONFIGS["tiny"], batch=2, host_slots=4)
+    B = H.Both(cfg)
+    t = B.create(64)
+    q = H.dev_bits(np.zeros((1, 8, 64), np.uint16))
+    out = torch.full_like(q, 123)
+    assert E.ellm_decode_attention(B.pool, [t], q, out, check=False) == E.ERR.EMPTY
+    assert E.ellm_kv_append(B.pool, [t], q, q, check=False) == E.ERR.UNMAPPED
+    assert E.ellm_decode_attention(B.pool, [5], q, out, check=False) == E.ERR.INVALID
+    torch.cuda.synchronize()
+    assert (out == 123).all()
+    B.close()

@@ -1,0 +1,249 @@
+"""Host state machine of the library (pool, chunk tables, error paths) against the oracle's own
+pool model, through the C ABI on a pool created with ELLM_POOL_METADATA_ONLY (no device needed).
+Tables, owner/state arrays, host-slot maps and return codes must agree bit for bit after every call
+of seeded random call sequences. The two sides share no code: the library is C++ (pool_core.cpp),
+the oracle plain C (ellm_oracle.c)."""
+import re
+import os
+
+import numpy as np
+import pytest
+
+import paper_2506_15155_amd as E
+from oracle.model import OraclePool
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+DUMMY = 4096   # non-NULL stand-in for device pointers; never dereferenced in metadata-only mode
+
+
+class Pair:
+    """The library pool and the oracle pool driven by the same calls."""
+
+    def __init__(self, n_chunks=48, n_host=10, Hq=8, Hkv=8, D=64, Tc=16, max_tensors=6, max_slots=12, owner=None):
+        cb = Tc * 2 * Hkv * D * 2
+        self.lib = E.ellm_pool_create(None, None, cb, Hq, Hkv, D, max_tensors, max_slots, owner,
+                                      flags=E.ELLM_POOL_METADATA_ONLY, device_bytes=n_chunks * cb,
+                                      host_bytes=n_host * cb)
+        self.orc = OraclePool(n_chunks, cb, n_host, Hq, Hkv, D, max_tensors, max_slots, owner, keep_twin=False)
+        self.n_chunks, self.n_host, self.Tc, self.max_tensors = n_chunks, n_host, Tc, max_tensors
+        self.Hkv, self.D = Hkv, D
+
+    def close(self):
+        E.ellm_pool_destroy(self.lib)
+        self.orc.close()
+
+    def compare(self):
+        lo, ls, lmt, lms = E.ellm_pool_get_owner_state(self.lib)
+        oo, os_, omt, oms = self.orc.owner_state()
+        assert np.array_equal(lo, oo) and np.array_equal(ls, os_)
+        assert np.array_equal(lmt, omt) and np.array_equal(lms, oms)
+        lt, lsl = E.ellm_pool_get_host_slots(self.lib)
+        ot, osl = self.orc.host_slots()
+        assert np.array_equal(lt, ot) and np.array_equal(lsl, osl)
+        for tid in range(self.max_tensors):
+            try:
+                tab, ln = E.ellm_tensor_get_table(self.lib, tid)
+                alive = True
+            except E.EllmError:
+                alive = False
+            try:
+                otab, oln = self.orc.table(tid)
+                oalive = True
+            except Exception:
+                oalive = False
+            assert alive == oalive
+            if alive:
+                assert np.array_equal(tab, otab) and ln == oln
+        assert E.ellm_pool_self_check(self.lib) == 0
+        assert self.orc.check_invariants() == 0
+        # no physical chunk backs two slots
+        mapped = [int(e) for tid in range(self.max_tensors) if self._alive(tid)
+                  for e in E.ellm_tensor_get_table(self.lib, tid)[0] if e >= 0]
+        assert len(mapped) == len(set(mapped))
+
+    def _alive(self, tid):
+        try:
+            E.ellm_tensor_get_table(self.lib, tid)
+            return True
+        except E.EllmError:
+            return False
+
+
+def random_walk(seed, steps=600, **kw):
+    rng = np.random.default_rng(seed)
+    owner = (rng.random(kw.get("n_chunks", 48)) < 0.35).astype(np.uint8)
+    P = Pair(owner=owner, **kw)
+    seen_codes = set()
+    for _ in range(steps):
+        op = rng.choice(["create", "destroy", "map", "map_ids", "unmap", "transfer", "busy", "append",
+                         "decode", "offload", "fetch", "fetch_ids"],
+                        p=[.08, .04, .16, .08, .04, .08, .08, .2, .06, .08, .06, .04])
+        alive = [t for t in range(P.max_tensors) if P._alive(t)]
+        if alive and rng.random() < 0.8:
+            # mostly plausible arguments, so the walk reaches deep states (full host buffer, long tensors)
+            tid = int(rng.choice(alive))
+            tab, ln = E.ellm_tensor_get_table(P.lib, tid)
+            first = int(rng.integers(0, tab.size))
+            n = int(rng.integers(0, min(5, tab.size - first) + 1))
+        else:
+            tid = int(rng.integers(-1, P.max_tensors + 1))
+            first = int(rng.integers(-1, 13))
+            n = int(rng.integers(-1, 6))
+        ids = rng.integers(-1, P.n_chunks + 1, size=max(n, 0)).astype(np.int32)
+        if op == "create":
+            mt = int(rng.integers(0, 16 * 13))
+            a = E.ellm_tensor_create(P.lib, mt, check=False)
+            b = P.orc.tensor_create(mt)
+            assert a == b, (op, a, b)
+            rc = a[0]
+        elif op == "destroy":
+            rc = E.ellm_tensor_destroy(P.lib, tid, check=False)
+            assert rc == P.orc.tensor_destroy(tid)
+        elif op == "map":
+            fl = int(rng.integers(0, 2))
+            rc = E.ellm_tensor_map_chunks(P.lib, tid, first, n, None, fl, check=False)
+            assert rc == P.orc.map_chunks(tid, first, n, None, fl), op
+        elif op == "map_ids":
+            fl = int(rng.integers(0, 2))
+            rc = E.ellm_tensor_map_chunks(P.lib, tid, first, n, ids if n > 0 else None, fl, check=False)
+            assert rc == P.orc.map_chunks(tid, first, n, ids if n > 0 else None, fl), op
+        elif op == "unmap":
+            rc = E.ellm_tensor_unmap_chunks(P.lib, tid, first, n, check=False)
+            assert rc == P.orc.unmap_chunks(tid, first, n), op
+        elif op == "transfer":
+            own = int(rng.integers(0, 3))
+            rc = E.ellm_pool_transfer(P.lib, ids, own, check=False)
+            assert rc == P.orc.transfer(ids, own), op
+        elif op == "busy":
+            busy = int(rng.integers(0, 2))
+            rc = E.ellm_pool_set_act_busy(P.lib, ids, busy, check=False)
+            assert rc == P.orc.set_act_busy(ids, busy), op
+        elif op == "append":
+            nb = int(rng.integers(0, 4))
+            tids = rng.integers(-1, P.max_tensors, size=nb).astype(np.int32)
+            if alive and rng.random() < 0.8:
+                tids = rng.choice(alive, size=min(nb, len(alive)), replace=False).astype(np.int32)
+                nb = tids.size
+            nn = rng.integers(-1, 40, size=nb).astype(np.int32)
+            tot = int(np.clip(nn, 0, None).sum())
+            kv = np.zeros((max(tot, 1), P.Hkv, P.D), np.uint16)
+            use_n = None if (nb and rng.random() < 0.3) else nn
+            rc = E.ellm_kv_append(P.lib, tids, DUMMY, DUMMY, use_n, stream=0, check=False)
+            kv1 = np.zeros((max(nb, 1), P.Hkv, P.D), np.uint16)
+            assert rc == P.orc.append(tids, kv if use_n is not None else kv1, kv if use_n is not None else kv1, use_n), op
+        elif op == "decode":
+            nb = int(rng.integers(0, 4))
+            tids = rng.integers(-1, P.max_tensors, size=nb).astype(np.int32)
+            rc = E.ellm_decode_attention(P.lib, tids, DUMMY, DUMMY, stream=0, check=False)
+            orc_rc, _ = P.orc.decode(tids, np.zeros((max(nb, 1), 8, P.D), np.uint16), threads=1)
+            # with no device behind it the library validates, then reports NO_DEVICE instead of OK
+            assert (rc == orc_rc) or (orc_rc == 0 and rc == (E.ERR.NO_DEVICE if nb else 0)), (rc, orc_rc)
+        elif op == "offload":
+            rc = E.ellm_chunk_deflate_to_host(P.lib, tid, first, n, check=False)
+            assert rc == P.orc.offload(tid, first, n), op
+        elif op == "fetch":
+            rc = E.ellm_chunk_inflate_from_host(P.lib, tid, first, n, None, check=False)
+            assert rc == P.orc.fetch(tid, first, n, None), op
+        else:
+            rc = E.ellm_chunk_inflate_from_host(P.lib, tid, first, n, ids if n > 0 else None, check=False)
+            assert rc == P.orc.fetch(tid, first, n, ids if n > 0 else None), op
+        seen_codes.add(rc)
+        P.compare()
+    P.close()
+    return seen_codes
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4])
+def test_random_call_sequences_match_oracle(seed):
+    random_walk(seed)
+
+
+def test_random_walks_reach_every_error_code():
+    seen = set()
+    for seed in range(10, 16):
+        seen |= random_walk(seed, steps=500, n_host=3 if seed % 2 else 10)
+    for code in (E.ERR.OK, E.ERR.INVALID, E.ERR.OOM, E.ERR.OWNED, E.ERR.UNMAPPED, E.ERR.NOT_RESIDENT,
+                 E.ERR.RANGE, E.ERR.EMPTY, E.ERR.HOST_FULL):
+        assert code in seen, code
+
+
+def test_non_power_of_two_tokens_per_chunk():
+    """13B-shaped geometry: 2 MiB chunks, bpt 20480 -> 102 tokens per chunk, 8192 bytes of slack."""
+    P = E.ellm_pool_create(None, None, 2 << 20, 40, 40, 128, 2, 162, flags=1, device_bytes=8 * (2 << 20))
+    g = E.ellm_pool_get_geometry(P)
+    assert g["tokens_per_chunk"] == 102 and g["bytes_per_token"] == 20480 and g["n_chunks"] == 8
+    t = E.ellm_tensor_create(P, 16384 + 102)
+    tab, ln = E.ellm_tensor_get_table(P, t)
+    assert tab.size == 162 and ln == 0
+    assert E.ellm_tensor_create(P, 102 * 162 + 1, check=False)[0] == E.ERR.RANGE
+    E.ellm_pool_destroy(P)
+
+
+def test_failed_calls_change_nothing():
+    P = Pair()
+    t = E.ellm_tensor_create(P.lib, 64)
+    P.orc.tensor_create(64)
+    before = E.ellm_pool_get_owner_state(P.lib)
+    assert E.ellm_tensor_map_chunks(P.lib, t, 0, 3, [5, 6, 5], check=False) == E.ERR.OWNED      # repeated id
+    assert E.ellm_tensor_map_chunks(P.lib, t, 0, 3, [5, 6, 99], check=False) == E.ERR.RANGE
+    assert E.ellm_tensor_map_chunks(P.lib, t, 2, 3, None, check=False) == E.ERR.RANGE
+    assert E.ellm_kv_append(P.lib, [t], DUMMY, DUMMY, stream=0, check=False) == E.ERR.UNMAPPED
+    assert E.ellm_decode_attention(P.lib, [t], DUMMY, DUMMY, stream=0, check=False) == E.ERR.EMPTY
+    assert "no token" in E.ellm_last_error()
+    after = E.ellm_pool_get_owner_state(P.lib)
+    for a, b in zip(before, after):
+        assert np.array_equal(a, b)
+    assert (E.ellm_tensor_get_table(P.lib, t)[0] == -1).all()
+    P.close()
+
+
+def test_pool_create_rejects_bad_geometry():
+    ok = dict(device_buf=None, host_buf=None, chunk_bytes=32768, n_q_heads=8, n_kv_heads=8, head_dim=64,
+              max_tensors=4, max_slots_per_tensor=4, flags=1, device_bytes=4 * 32768)
+    assert E.ellm_pool_create(**ok, check=False)[0] == 0
+    for k, v in [("head_dim", 96), ("n_kv_heads", 3), ("chunk_bytes", 1000), ("chunk_bytes", 1024),
+                 ("device_bytes", 100), ("max_tensors", 0), ("flags", 3)]:
+        bad = dict(ok)
+        bad[k] = v
+        assert E.ellm_pool_create(**bad, check=False)[0] == E.ERR.INVALID, k
+    # a real (non metadata-only) pool needs a device pointer
+    bad = dict(ok)
+    bad["flags"] = 0
+    assert E.ellm_pool_create(**bad, check=False)[0] == E.ERR.INVALID
+
+
+def test_library_exports_every_declared_symbol():
+    """Every function include/ellm.h declares is exported by the built library and bound in Python."""
+    text = open(os.path.join(ROOT, "include", "ellm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(ellm_[a-z_0-9]+)\s*\(", text))
+    assert len(declared) >= 20
+    for name in declared:
+        assert hasattr(E.lib, name), name
+        assert callable(getattr(E, name)), name
+    assert declared == set(E.binding.EXPORTED)
+
+
+def test_split_plan_depends_only_on_lengths():
+    """The sequence partition is a function of the batch's lengths and the geometry, not of which
+    physical chunks back the tensors."""
+    plans = []
+    for perm_seed in (0, 1):
+        rng = np.random.default_rng(perm_seed)
+        cb = 2 << 20
+        P = E.ellm_pool_create(None, None, cb, 32, 8, 128, 8, 17, flags=1, device_bytes=256 * cb)
+        perm = list(rng.permutation(256))
+        ids = []
+        for L in (64, 700, 3000, 8192):
+            t = E.ellm_tensor_create(P, 8704)
+            ns = -(-L // 512)
+            E.ellm_tensor_map_chunks(P, t, 0, ns, [perm.pop() for _ in range(ns)])
+            E.ellm_kv_append(P, [t], DUMMY, DUMMY, [L], stream=0)
+            ids.append(t)
+        ns, S = E.ellm_decode_plan(P, ids)
+        plans.append((list(ns), S))
+        assert S > 0 and all(n == -(-L // S) for n, L in zip(ns, (64, 700, 3000, 8192)))
+        E.ellm_pool_set_split_tokens(P, 64)
+        assert E.ellm_decode_plan(P, ids)[1] == 64
+        E.ellm_pool_destroy(P)
+    assert plans[0] == plans[1]
