@@ -1,0 +1,264 @@
+"""Benchmark: decode attention + KV append over chunk-backed KV on one MI355X.
+
+Workload (default): the Llama-3-8B-shaped configuration — 32 q / 8 kv heads, head_dim 128, bf16,
+batch 64, context lengths lognormal (median 1k, clipped 64..8k), 2 MiB chunks shuffled in one
+unified pool — for all 32 layers of such a model: every (layer, request) is a virtual KV tensor of
+its own, so one step streams 32 different layers' K/V (about 13 GB) and the last-level cache cannot
+serve the reads. One step = for every layer: map a chunk ahead for requests about to cross a
+chunk boundary, append one token per request, decode-attend over the whole context.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, public specification
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="llama8b", choices=["llama8b", "mha13b", "long70b", "tiny"])
+    ap.add_argument("--layers", type=int, default=0, help="0 = the model's layer count for the shape")
+    ap.add_argument("--split", type=int, default=0, help="override tokens per work item (0 = automatic)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true")
+    ap.add_argument("--migration", action="store_true", help="also time offload / fetch of 25%% of the requests")
+    return ap.parse_args()
+
+
+DEFAULT_LAYERS = {"llama8b": 32, "mha13b": 2, "long70b": 4, "tiny": 4}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
+              "(the path needs no collective; sharding is described in DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2506_15155_amd as E
+    import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = W.CONFIGS[args.config]
+    n_layers = args.layers or DEFAULT_LAYERS[args.config]
+    K, Wm = args.steps, args.warmup
+    B, Hq, Hkv, D, Tc = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.tokens_per_chunk
+    rng = np.random.default_rng(cfg.seed)
+    lens_final = W.draw_lengths(cfg, rng)                  # lengths after the LAST timed step
+    grow = K + Wm + (0 if args.no_cpu_baseline else 1)
+    lens0 = np.maximum(lens_final - grow, 1)               # lengths before the first step's append
+    max_tokens = int(lens_final.max()) + Tc
+
+    # one unified pool for all layers; 1/8 of it starts on the activation side (idle), so that
+    # map-ahead can borrow from it when the KV side runs dry
+    slots_now = [int(-(-int(l) // Tc)) for l in lens0]
+    need = n_layers * sum(slots_now)
+    n_chunks = int(need * 1.15) + 64
+    owner = np.zeros(n_chunks, np.uint8)
+    owner[rng.random(n_chunks) < 0.125] = 1
+    kv_ids = np.flatnonzero(owner == 0).astype(np.int32)
+    rng.shuffle(kv_ids)
+    dev = torch.empty(n_chunks * cfg.chunk_bytes, dtype=torch.uint8, device="cuda")
+    dev.view(torch.int16).fill_(0x7FC0)                    # NaN poison everywhere that is not KV
+    n_host = 0
+    host = None
+    if args.migration:
+        n_host = 2 * max(slots_now) * (B // 4 + 1)
+        host = torch.empty(n_host * cfg.chunk_bytes, dtype=torch.uint8, pin_memory=True)
+    pool = E.ellm_pool_create(dev, host, cfg.chunk_bytes, Hq, Hkv, D, n_layers * B, -(-max_tokens // Tc), owner)
+    if args.split:
+        E.ellm_pool_set_split_tokens(pool, args.split)
+
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(cfg.seed)
+    n_oracle_layers = 0 if args.no_cpu_baseline else 1
+    oracle_hist = []
+    ids, pos = [], 0
+    for l in range(n_layers):
+        lid = []
+        for b in range(B):
+            t = E.ellm_tensor_create(pool, max_tokens)
+            E.ellm_tensor_map_chunks(pool, t, 0, slots_now[b], kv_ids[pos:pos + slots_now[b]])
+            pos += slots_now[b]
+            lid.append(t)
+        ids.append(np.array(lid, np.int32))
+        tot = int(lens0.sum())
+        k = torch.randn((tot, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        v = torch.randn((tot, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        E.ellm_kv_append(pool, ids[l], k, v, lens0.astype(np.int32))
+        if l < n_oracle_layers:
+            oracle_hist.append((k.view(torch.int16).cpu().numpy().view(np.uint16),
+                                v.view(torch.int16).cpu().numpy().view(np.uint16)))
+        torch.cuda.synchronize()
+        del k, v
+    k_new = [torch.randn((B, Hkv, D), generator=gen, device="cuda").to(torch.bfloat16) for _ in range(n_layers)]
+    v_new = [torch.randn((B, Hkv, D), generator=gen, device="cuda").to(torch.bfloat16) for _ in range(n_layers)]
+    q = [torch.randn((B, Hq, D), generator=gen, device="cuda").to(torch.bfloat16) for _ in range(n_layers)]
+    out = [torch.empty((B, Hq, D), device="cuda", dtype=torch.bfloat16) for _ in range(n_layers)]
+    stream = torch.cuda.current_stream()
+
+    lens = lens0.copy()
+
+    # the timed loop calls the C ABI with arguments marshalled once, so the host stays ahead of the GPU
+    import ctypes as C
+    c_pool, c_stream = C.c_void_p(pool), C.c_void_p(stream.cuda_stream or None)
+    c_ids = [a.ctypes.data_as(C.POINTER(C.c_int32)) for a in ids]
+    c_k = [C.c_void_p(t.data_ptr()) for t in k_new]
+    c_v = [C.c_void_p(t.data_ptr()) for t in v_new]
+    c_q = [C.c_void_p(t.data_ptr()) for t in q]
+    c_o = [C.c_void_p(t.data_ptr()) for t in out]
+    c_scale = C.c_float(0.0)
+    f_append, f_decode = E.lib.ellm_kv_append, E.lib.ellm_decode_attention
+
+    def step():
+        # a3: requests whose next token opens a new chunk get one mapped (inflating if needed)
+        for b in np.flatnonzero(lens % Tc == 0):
+            for l in range(n_layers):
+                E.ellm_tensor_map_chunks(pool, int(ids[l][b]), int(lens[b]) // Tc, 1, None, E.ELLM_MAP_ALLOW_INFLATE)
+        for l in range(n_layers):
+            rc = f_append(c_pool, c_ids[l], B, None, c_k[l], c_v[l], c_stream)
+            rc |= f_decode(c_pool, c_ids[l], B, c_q[l], c_o[l], c_scale, c_stream)
+            if rc:
+                raise E.EllmError(rc, E.ellm_last_error())
+        lens[:] += 1
+
+    for _ in range(Wm):
+        step()
+    torch.cuda.synchronize()
+    use_events = not args.no_kernel_events
+    if use_events:
+        E.ellm_pool_profile_enable(pool, K * n_layers * 2)
+    n_split_now, S = E.ellm_decode_plan(pool, ids[0])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    kern_ms = E.ellm_pool_profile_collect(pool, K * n_layers * 2) if use_events else np.zeros(0, np.float32)
+    if use_events:
+        E.ellm_pool_profile_enable(pool, 0)
+
+    # algorithmic bytes: lengths at the middle of the timed region
+    lens_mid = lens - (K + 1) // 2
+    n_items = int(sum(-(-int(x) // S) for x in lens_mid))
+    ab = W.algorithmic_bytes(cfg, lens_mid, n_items)
+    step_bytes = ab["total"] * n_layers
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    # dominant kernel: the partial pass reads K/V, q and table entries and writes the partials
+    partial_bytes = ab["kv"] + ab["q_out"] // 2 + ab["table"] + ab["partials"] // 2
+    roofline = None
+    if use_events and len(kern_ms):
+        avg = float(np.mean(kern_ms))
+        ach = partial_bytes / (avg * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "decode_partial_kernel", "achieved": round(ach, 1),
+                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "avg_launch_us": round(avg * 1e3, 2), "launches": int(len(kern_ms)),
+                    "algorithmic_bytes_per_launch": int(partial_bytes)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, lens0, oracle_hist, ab, lens)
+
+    mig = None
+    if args.migration:
+        mig = time_migration(E, torch, pool, ids, lens, Tc, cfg, B)
+
+    res = {
+        "metric": "decode-attention achieved HBM GB/s (% of peak) + tokens/s, chunk-backed KV, 1 GPU",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "pct_of_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "tokens_per_s": round(B / (ms_per_step * 1e-3), 1),
+        "tokens_per_s_per_layer": round(B * n_layers / (ms_per_step * 1e-3), 1),
+        "config": {"workload": f"{args.config}: {Hq}q/{Hkv}kv heads, head_dim {D}, batch {B}, {n_layers} layers, "
+                               f"lengths {cfg.length_dist} {cfg.len_lo}..{cfg.len_hi} (mean {float(lens_mid.mean()):.0f}), "
+                               f"{cfg.chunk_bytes >> 10} KiB chunks shuffled in one pool of {n_chunks}, "
+                               "step = per layer map-ahead + append 1 token/request + decode",
+                   "global_batch": B, "layers": n_layers, "split_tokens": int(S), "work_items_per_layer": n_items,
+                   "algorithmic_bytes_per_step": int(step_bytes)},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    if mig:
+        res["migration"] = mig
+    E.ellm_pool_destroy(pool)
+    print(json.dumps(res))
+
+
+def cpu_baseline(cfg, lens0, oracle_hist, ab, lens_now):
+    """The oracle, as it stands, on the host cores: one layer of the same workload (all requests:
+    history append is setup, then one timed append + decode step)."""
+    import workloads as W
+    from oracle.model import OraclePool
+    B, Tc = cfg.batch, cfg.tokens_per_chunk
+    slots = [int(-(-(int(l) + 1) // Tc)) for l in lens0]
+    n_chunks = sum(slots)
+    orc = OraclePool(n_chunks, cfg.chunk_bytes, 0, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, B,
+                     max(slots), None, False)
+    rng = np.random.default_rng(cfg.seed + 1000)
+    perm = rng.permutation(n_chunks).astype(np.int32)
+    ids, pos = [], 0
+    for b in range(B):
+        rc, t = orc.tensor_create(max(slots) * Tc)
+        assert rc == 0 and orc.map_chunks(t, 0, slots[b], perm[pos:pos + slots[b]]) == 0
+        pos += slots[b]
+        ids.append(t)
+    kh, vh = oracle_hist[0]
+    assert orc.append(ids, kh, vh, lens0.astype(np.int32)) == 0
+    k1 = W.normal_bf16(rng, (B, cfg.n_kv_heads, cfg.head_dim))
+    v1 = W.normal_bf16(rng, (B, cfg.n_kv_heads, cfg.head_dim))
+    q1 = W.normal_bf16(rng, (B, cfg.n_q_heads, cfg.head_dim))
+    cores = os.cpu_count() or 1
+    cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+    t0 = time.perf_counter()
+    assert orc.append(ids, k1, v1) == 0
+    rc, _ = orc.decode(ids, q1, threads=cores)
+    t1 = time.perf_counter()
+    assert rc == 0
+    nbytes = W.algorithmic_bytes(cfg, lens0 + 1, 0)["total"]
+    orc.close()
+    return {"value": round(nbytes / (t1 - t0) / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"1 of the layers, all {B} requests, one append + decode step "
+                      f"({int((lens0 + 1).sum())} cached tokens), fp64 C oracle with pthreads",
+            "seconds": round(t1 - t0, 3), "tokens_per_s_per_layer": round(B / (t1 - t0), 2)}
+
+
+def time_migration(E, torch, pool, ids, lens, Tc, cfg, B):
+    """Offload then fetch all chunks of 25% of the requests of layer 0; GB/s each way."""
+    sel = list(range(0, B, 4))
+    slots = [int(-(-int(lens[b]) // Tc)) for b in sel]
+    nbytes = sum(slots) * cfg.chunk_bytes
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for b, s in zip(sel, slots):
+        E.ellm_chunk_deflate_to_host(pool, int(ids[0][b]), 0, s)
+    E.ellm_pool_sync(pool)
+    t1 = time.perf_counter()
+    for b, s in zip(sel, slots):
+        E.ellm_chunk_inflate_from_host(pool, int(ids[0][b]), 0, s)
+    E.ellm_pool_sync(pool)
+    t2 = time.perf_counter()
+    return {"requests": len(sel), "chunks": int(sum(slots)), "bytes": int(nbytes),
+            "offload_GBps": round(nbytes / (t1 - t0) / 1e9, 2), "fetch_GBps": round(nbytes / (t2 - t1) / 1e9, 2)}
+
+
+if __name__ == "__main__":
+    main()

@@ -172,9 +172,11 @@ int ellm_kv_append(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, co
  *   q (device): [batch][n_q_heads][head_dim] bf16; out (device): same shape, bf16.
  *   For q head h, kv head g = h / G:  s_t = scale * <q_h, K_t,g>,  w = softmax_t(s),
  *   out_h = sum_t w_t * V_t,g  for t = 0 .. len-1, no mask. scale = 0 selects 1/sqrt(head_dim).
- *   fp32 arithmetic, output rounded to nearest-even bf16. Split over the sequence with a partition
- *   that depends only on the lengths in the batch and the pool geometry, never on physical chunk
- *   ids, so results are bitwise reproducible and invariant under remapping.
+ *   fp32 accumulation (softmax weights are rounded to bf16 before they multiply V and before they
+ *   are summed), output rounded to nearest-even bf16. Split over the sequence with a partition
+ *   that depends only on the lengths in the batch, the pool geometry and the device's wave
+ *   capacity, never on physical chunk ids, so results are bitwise reproducible and invariant
+ *   under remapping.
  * Checks: batch < 0, NULL q / out, non-finite scale -> INVALID; per request in order: bad handle ->
  * INVALID, len == 0 -> EMPTY; slots 0 .. ceil(len / T_c) - 1 ascending: empty -> UNMAPPED, on host
  * -> NOT_RESIDENT. Enqueued on `stream`; returns without waiting. */
@@ -215,12 +217,34 @@ int ellm_pool_get_owner_state(ellm_pool* pool, uint8_t* owner, uint8_t* state,
                               int32_t* mapped_tensor, int32_t* mapped_slot);
 /* Per host slot (host arrays of n_host_slots, any may be NULL): the (tensor, slot) stored, else -1. */
 int ellm_pool_get_host_slots(ellm_pool* pool, int32_t* tensor, int32_t* slot);
-/* Number of sequence splits the next decode over these handles would use per request
- * (host array of batch), and the tokens per split. For tests of the split partition. */
+/* The partition the next decode over these handles would use: n_split[b] (host array of batch) is
+ * the largest number of partial results any (request b, kv head) pair is split into, *split_tokens
+ * the tokens each wave of the partial pass handles. For tests of the split partition. */
 int ellm_decode_plan(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch,
                      int32_t* n_split, int32_t* split_tokens);
-/* Override the split size (tokens, 0 = automatic). For tests that compare partitions. */
+/* Override the tokens per wave (rounded down to whole 64-token tiles, at least one; 0 = automatic).
+ * For tests that compare partitions. */
 int ellm_pool_set_split_tokens(ellm_pool* pool, int32_t split_tokens);
+
+/* Measurement hooks. profile_enable(max_records > 0) makes each decode launch record a pair of
+ * HIP events on the caller's stream around its partial-pass kernel (the kernel that streams K/V),
+ * for up to max_records launches; max_records = 0 switches it off. profile_collect waits for the
+ * recorded launches, writes their durations in milliseconds to ms (host, cap entries), stores the
+ * number recorded in *n and starts over. Not part of the paper's method. */
+int ellm_pool_profile_enable(ellm_pool* pool, int32_t max_records);
+int ellm_pool_profile_collect(ellm_pool* pool, float* ms, int32_t cap, int32_t* n);
+
+/* Calibration kernels for measurement; none computes anything of the method.
+ *   debug_copy: dst[0..bytes) = src[0..bytes) (device, bytes % 16 == 0): the known-size kernel that
+ *     hardware byte counters are scaled against.
+ *   debug_stream_read: reads src[0..bytes) (device) and discards it: the read ceiling of the GPU.
+ *     sink: device, 4 bytes.
+ *   debug_kv_stream_read: reads exactly the K/V rows a decode over `ids` would read, with the same
+ *     work partition and load shape, and discards them: the ceiling of the access pattern.
+ *     Same checks as ellm_decode_attention. */
+int ellm_debug_copy(void* dst, const void* src, uint64_t bytes, void* stream);
+int ellm_debug_stream_read(const void* src, uint64_t bytes, void* sink, void* stream);
+int ellm_debug_kv_stream_read(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, void* sink, void* stream);
 
 /* O(n) consistency scan of the host state (tables, chunk records, free lists, host slots agree;
  * no chunk backs two slots). Returns 0 when consistent, else a positive rule number. */

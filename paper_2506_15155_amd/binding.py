@@ -72,6 +72,11 @@ _sigs = {
     "ellm_decode_plan": [_vp, _i32p, C.c_int32, _i32p, _i32p],
     "ellm_pool_set_split_tokens": [_vp, C.c_int32],
     "ellm_pool_self_check": [_vp],
+    "ellm_debug_copy": [_vp, _vp, C.c_uint64, _vp],
+    "ellm_debug_stream_read": [_vp, C.c_uint64, _vp, _vp],
+    "ellm_debug_kv_stream_read": [_vp, _i32p, C.c_int32, _vp, _vp],
+    "ellm_pool_profile_enable": [_vp, C.c_int32],
+    "ellm_pool_profile_collect": [_vp, C.POINTER(C.c_float), C.c_int32, _i32p],
 }
 for _n, _a in _sigs.items():
     getattr(lib, _n).argtypes = _a
@@ -259,3 +264,28 @@ def ellm_pool_set_split_tokens(pool, split_tokens, check=True):
 
 def ellm_pool_self_check(pool):
     return lib.ellm_pool_self_check(pool)
+
+
+def ellm_pool_profile_enable(pool, max_records, check=True):
+    return _ret(lib.ellm_pool_profile_enable(pool, int(max_records)), check)
+
+
+def ellm_pool_profile_collect(pool, cap):
+    """Durations (ms) of the partial-pass kernels recorded since the last collect."""
+    ms = np.zeros(max(cap, 1), np.float32)
+    n = C.c_int32()
+    _ret(lib.ellm_pool_profile_collect(pool, ms.ctypes.data_as(C.POINTER(C.c_float)), cap, C.byref(n)), True)
+    return ms[:min(cap, n.value)]
+
+
+def ellm_debug_copy(dst, src, nbytes, stream=None, check=True):
+    return _ret(lib.ellm_debug_copy(_ptr(dst), _ptr(src), int(nbytes), _stream(stream)), check)
+
+
+def ellm_debug_stream_read(src, nbytes, sink, stream=None, check=True):
+    return _ret(lib.ellm_debug_stream_read(_ptr(src), int(nbytes), _ptr(sink), _stream(stream)), check)
+
+
+def ellm_debug_kv_stream_read(pool, ids, sink, stream=None, check=True):
+    _, p, n = _i32(ids)
+    return _ret(lib.ellm_debug_kv_stream_read(pool, p, n, _ptr(sink), _stream(stream)), check)

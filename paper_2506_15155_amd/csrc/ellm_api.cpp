@@ -57,10 +57,16 @@ struct ellm_pool {
   hipStream_t last_stream = nullptr;   // last stream given to append / decode
   bool have_last_stream = false;
   int32_t split_override = 0;
+  int32_t wave_slots = 0;              // resident partial-pass waves on the whole GPU (0 = not asked yet)
+
+  // optional timing of the partial (dominant) kernel with events on the caller's stream
+  std::vector<hipEvent_t> prof_ev;     // 2 per record
+  int32_t prof_used = 0;
 
   // scratch reused across calls
   std::vector<int32_t> n_eff;
   std::vector<ellm::Move> moves;
+  std::vector<ellm::BatchArgs> launches;
 };
 
 namespace {
@@ -78,6 +84,7 @@ ellm::PoolView view_of(const ellm_pool* p) {
   v.table = p->d_table;
   v.chunk_bytes = p->geom.chunk_bytes;
   v.tokens_per_chunk = p->geom.tokens_per_chunk;
+  v.tiles_per_chunk = (p->geom.tokens_per_chunk + ellm::TILE_TOKENS - 1) / ellm::TILE_TOKENS;
   v.max_slots = p->geom.max_slots;
   v.n_q_heads = p->geom.n_q_heads;
   v.n_kv_heads = p->geom.n_kv_heads;
@@ -157,8 +164,8 @@ int leave_migration(ellm_pool* p) {
   return ELLM_OK;
 }
 
-int ensure_workspace(ellm_pool* p, int64_t n_items) {
-  const size_t need = (size_t)n_items * p->geom.n_q_heads * (p->geom.head_dim + 2) * sizeof(float);
+int ensure_workspace(ellm_pool* p, int64_t n_slots) {
+  const size_t need = (size_t)n_slots * p->geom.group * (p->geom.head_dim + ellm::WS_ROW_PAD) * sizeof(float);
   if (need <= p->ws_bytes) return ELLM_OK;
   if (p->d_ws) {
     HIP_TRY(hipDeviceSynchronize(), "hipDeviceSynchronize(workspace growth)");
@@ -172,22 +179,60 @@ int ensure_workspace(ellm_pool* p, int64_t n_items) {
   return ELLM_OK;
 }
 
-// Tokens per work item. Depends only on the batch's lengths and the pool geometry (never on
-// physical chunk ids), so the partition and with it every rounding is reproducible and invariant
-// under remapping. Aims at enough workgroups to fill 256 compute units several times over while
-// keeping the partials small next to the K/V bytes.
-int32_t choose_split(const ellm_pool* p, const int32_t* ids, int32_t batch) {
-  if (p->split_override > 0) return p->split_override;
+// Resident waves of the partial-pass kernel on the whole GPU. Without a device (metadata-only pools,
+// planning calls on a host without GPU) a nominal MI355X figure is used: 256 compute units x 8 waves.
+int32_t wave_slots(ellm_pool* p) {
+  if (p->wave_slots > 0) return p->wave_slots;
+  int32_t slots = 256 * 8;
+  if (!p->metadata_only) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      slots = cus * ellm::partial_waves_per_cu(p->geom.head_dim, p->geom.group);
+    else
+      (void)hipGetLastError();
+  }
+  p->wave_slots = slots;
+  return slots;
+}
+
+// The partition of one launch (at most MAX_LAUNCH_REQ requests). All tiles of all (kv head, request)
+// pairs form one sequence; every wave gets the same number of consecutive tiles, chosen so that the
+// whole launch is resident at once. It depends only on the batch's lengths, the pool geometry and
+// the device's wave capacity, never on physical chunk ids, so the partition, and with it every
+// rounding, is reproducible and invariant under remapping.
+void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0, int64_t ws_slot0, ellm::BatchArgs& a) {
   const int32_t Tc = p->geom.tokens_per_chunk;
-  int64_t total = 0;
-  for (int32_t b = 0; b < batch; b++) total += p->core->tensor(ids[b])->len;
-  const int64_t want_groups = 2048;
-  int64_t s = total * p->geom.n_kv_heads / want_groups;
-  s = std::max<int64_t>(128, std::min<int64_t>(2048, s));
-  if (s >= Tc) return (int32_t)std::max<int64_t>(Tc, (s / Tc) * Tc);   // whole chunks
-  int32_t parts = (int32_t)((Tc + s - 1) / s);                           // equal parts of a chunk
-  int32_t part = (Tc + parts - 1) / parts;
-  return (part + 15) / 16 * 16 >= Tc ? Tc : (part + 15) / 16 * 16;
+  const int32_t tpc = (Tc + ellm::TILE_TOKENS - 1) / ellm::TILE_TOKENS;
+  a.n_req = n_req;
+  a.q_row0 = q_row0;
+  int64_t prefix = 0;
+  int32_t longest = 0;
+  for (int32_t i = 0; i < n_req; i++) {
+    const int64_t len = p->core->tensor(ids[i])->len;
+    const int64_t full = len / Tc, rem = len - full * Tc;
+    const int64_t tiles = full * tpc + (rem + ellm::TILE_TOKENS - 1) / ellm::TILE_TOKENS;
+    a.tensor[i] = ids[i];
+    a.len[i] = (int32_t)len;
+    a.tile_prefix[i] = (int32_t)prefix;
+    prefix += tiles;
+    longest = std::max<int32_t>(longest, (int32_t)tiles);
+  }
+  a.tile_prefix[n_req] = (int32_t)prefix;
+  a.tiles_per_head = (int32_t)prefix;
+  const int64_t total = prefix * p->geom.n_kv_heads;
+  int64_t per_wave;
+  if (p->split_override > 0) per_wave = std::max<int64_t>(1, p->split_override / ellm::TILE_TOKENS);
+  else per_wave = std::max<int64_t>(1, (total + wave_slots(p) - 1) / wave_slots(p));
+  a.tiles_per_wave = (int32_t)per_wave;
+  a.n_waves = (int32_t)((total + per_wave - 1) / per_wave);
+  a.max_partials = (int32_t)((longest + per_wave - 1) / per_wave) + 1;
+  a.ws_slot0 = (int32_t)ws_slot0;
+  a.pad = 0;
+}
+
+int64_t launch_ws_slots(const ellm_pool* p, const ellm::BatchArgs& a) {
+  return (int64_t)a.n_req * p->geom.n_kv_heads * a.max_partials;
 }
 
 }  // namespace
@@ -253,6 +298,7 @@ int ellm_pool_destroy(ellm_pool* p) {
     (void)hipEventDestroy(p->ev_compute);
     (void)hipEventDestroy(p->ev_migrate);
     (void)hipFree(p->d_table);
+    for (hipEvent_t e : p->prof_ev) (void)hipEventDestroy(e);
     if (p->d_ws) (void)hipFree(p->d_ws);
   }
   delete p;
@@ -327,29 +373,28 @@ int ellm_kv_append(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const
   return ELLM_OK;
 }
 
-static int build_plan(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, int32_t* split_out,
-                      std::vector<int32_t>* n_split) {
-  const int32_t S = choose_split(p, ids, batch);
-  *split_out = S;
-  if (n_split) {
-    n_split->resize(batch);
-    for (int32_t b = 0; b < batch; b++) {
-      const int64_t len = p->core->tensor(ids[b])->len;
-      (*n_split)[b] = (int32_t)((len + S - 1) / S);
-    }
-  }
-  return ELLM_OK;
-}
-
 int ellm_decode_plan(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, int32_t* n_split, int32_t* split_tokens) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
   int rc = core_err(p, p->core->decode_check(ids, batch));
   if (rc) return rc;
-  int32_t S = 0;
-  std::vector<int32_t> ns;
-  build_plan(p, ids, batch, &S, &ns);
-  if (n_split) std::copy(ns.begin(), ns.end(), n_split);
-  if (split_tokens) *split_tokens = S;
+  ellm::BatchArgs a;
+  int32_t per_wave = 0;
+  for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
+    const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
+    plan_launch(p, ids + b0, nb, b0, 0, a);
+    per_wave = std::max(per_wave, a.tiles_per_wave);
+    if (n_split)
+      for (int32_t i = 0; i < nb; i++) {
+        int32_t most = 0;
+        for (int32_t g = 0; g < p->geom.n_kv_heads; g++) {
+          const int64_t f0 = (int64_t)g * a.tiles_per_head + a.tile_prefix[i];
+          const int64_t f1 = (int64_t)g * a.tiles_per_head + a.tile_prefix[i + 1];
+          most = std::max<int32_t>(most, (int32_t)((f1 - 1) / a.tiles_per_wave - f0 / a.tiles_per_wave + 1));
+        }
+        n_split[b0 + i] = most;
+      }
+  }
+  if (split_tokens) *split_tokens = per_wave * ellm::TILE_TOKENS;
   return ELLM_OK;
 }
 
@@ -373,34 +418,33 @@ int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch
   if (scale == 0.f) scale = 1.0f / std::sqrt((float)p->geom.head_dim);
   const float scale_log2 = scale * 1.4426950408889634f;
 
-  int32_t S = 0;
-  build_plan(p, ids, batch, &S, nullptr);
-  int64_t total_items = 0;
-  for (int32_t b = 0; b < batch; b++) total_items += (p->core->tensor(ids[b])->len + S - 1) / S;
-  if (total_items > 0x7fffffffll) return set_err(ELLM_ERR_RANGE, "decode_attention: too many work items");
-  rc = ensure_workspace(p, total_items);
+  // plan every launch first: the workspace must hold all of them
+  std::vector<ellm::BatchArgs>& launches = p->launches;
+  launches.clear();
+  int64_t ws_slots = 0;
+  for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
+    const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
+    launches.emplace_back();
+    plan_launch(p, ids + b0, nb, b0, ws_slots, launches.back());
+    ws_slots += launch_ws_slots(p, launches.back());
+    if ((int64_t)launches.back().tiles_per_head * p->geom.n_kv_heads > 0x7fffffffll || ws_slots > 0x7fffffffll)
+      return set_err(ELLM_ERR_RANGE, "decode_attention: too much work for one call");
+  }
+  rc = ensure_workspace(p, ws_slots);
   if (rc) return rc;
 
   const ellm::PoolView pv = view_of(p);
-  ellm::BatchArgs a;
-  int32_t item_base = 0;
-  for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
-    const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
-    a.n_req = nb;
-    a.item_base = item_base;
-    a.q_row0 = b0;
-    int32_t it = 0;
-    for (int32_t i = 0; i < nb; i++) {
-      const int64_t len = p->core->tensor(ids[b0 + i])->len;
-      a.tensor[i] = ids[b0 + i];
-      a.len[i] = (int32_t)len;
-      a.item0[i] = it;
-      it += (int32_t)((len + S - 1) / S);
+  for (const ellm::BatchArgs& a : launches) {
+    const bool prof = (size_t)(p->prof_used + 1) * 2 <= p->prof_ev.size();
+    if (prof) HIP_TRY(hipEventRecord(p->prof_ev[2 * p->prof_used], stream), "hipEventRecord(profile)");
+    int e = ellm::launch_decode_partial(pv, q, p->d_ws, scale_log2, a, stream);
+    if (e) return hip_err((hipError_t)e, "decode partial launch");
+    if (prof) {
+      HIP_TRY(hipEventRecord(p->prof_ev[2 * p->prof_used + 1], stream), "hipEventRecord(profile)");
+      p->prof_used++;
     }
-    a.n_items = it;
-    int e = ellm::launch_decode(pv, q, out, p->d_ws, scale_log2, S, a, stream);
-    if (e) return hip_err((hipError_t)e, "decode launch");
-    item_base += it;
+    e = ellm::launch_decode_combine(pv, p->d_ws, out, a, stream);
+    if (e) return hip_err((hipError_t)e, "decode combine launch");
   }
   return ELLM_OK;
 }
@@ -484,6 +528,66 @@ int ellm_pool_get_host_slots(ellm_pool* p, int32_t* tensor, int32_t* slot) {
   const size_t n = (size_t)p->geom.n_host_slots;
   if (tensor && n) std::memcpy(tensor, p->core->host_tensor().data(), n * sizeof(int32_t));
   if (slot && n) std::memcpy(slot, p->core->host_slot().data(), n * sizeof(int32_t));
+  return ELLM_OK;
+}
+
+int ellm_pool_profile_enable(ellm_pool* p, int32_t max_records) {
+  if (!p || max_records < 0) return set_err(ELLM_ERR_INVALID, "profile_enable: bad argument");
+  if (p->metadata_only) return set_err(ELLM_ERR_NO_DEVICE, "profile_enable: pool has no device");
+  for (hipEvent_t e : p->prof_ev) (void)hipEventDestroy(e);
+  p->prof_ev.clear();
+  p->prof_used = 0;
+  for (int32_t i = 0; i < 2 * max_records; i++) {
+    hipEvent_t e;
+    HIP_TRY(hipEventCreate(&e), "hipEventCreate(profile)");
+    p->prof_ev.push_back(e);
+  }
+  return ELLM_OK;
+}
+
+int ellm_pool_profile_collect(ellm_pool* p, float* ms, int32_t cap, int32_t* n) {
+  if (!p || cap < 0 || (cap > 0 && !ms)) return set_err(ELLM_ERR_INVALID, "profile_collect: bad argument");
+  const int32_t m = std::min(cap, p->prof_used);
+  for (int32_t i = 0; i < m; i++) {
+    HIP_TRY(hipEventSynchronize(p->prof_ev[2 * i + 1]), "hipEventSynchronize(profile)");
+    HIP_TRY(hipEventElapsedTime(&ms[i], p->prof_ev[2 * i], p->prof_ev[2 * i + 1]), "hipEventElapsedTime(profile)");
+  }
+  if (n) *n = p->prof_used;
+  p->prof_used = 0;
+  return ELLM_OK;
+}
+
+int ellm_debug_copy(void* dst, const void* src, uint64_t bytes, void* stream) {
+  if (!dst || !src || bytes % 16) return set_err(ELLM_ERR_INVALID, "debug_copy: bad argument");
+  int e = ellm::launch_copy(dst, src, (int64_t)bytes, (hipStream_t)stream);
+  if (e) return hip_err((hipError_t)e, "copy launch");
+  return ELLM_OK;
+}
+
+int ellm_debug_stream_read(const void* src, uint64_t bytes, void* sink, void* stream) {
+  if (!src || !sink || bytes % 16) return set_err(ELLM_ERR_INVALID, "debug_stream_read: bad argument");
+  int e = ellm::launch_read(src, (int64_t)bytes, (uint32_t*)sink, (hipStream_t)stream);
+  if (e) return hip_err((hipError_t)e, "read launch");
+  return ELLM_OK;
+}
+
+int ellm_debug_kv_stream_read(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, void* sink, void* stream_) {
+  if (!p || !sink) return set_err(ELLM_ERR_INVALID, "debug_kv_stream_read: bad argument");
+  int rc = core_err(p, p->core->decode_check(ids, batch));
+  if (rc) return rc;
+  if (batch == 0) return ELLM_OK;
+  if (p->metadata_only) return set_err(ELLM_ERR_NO_DEVICE, "debug_kv_stream_read: pool has no device");
+  hipStream_t stream = (hipStream_t)stream_;
+  rc = enter_compute(p, stream);
+  if (rc) return rc;
+  const ellm::PoolView pv = view_of(p);
+  ellm::BatchArgs a;
+  for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
+    const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
+    plan_launch(p, ids + b0, nb, b0, 0, a);
+    int e = ellm::launch_kv_stream(pv, (uint32_t*)sink, a, stream);
+    if (e) return hip_err((hipError_t)e, "kv stream launch");
+  }
   return ELLM_OK;
 }
 

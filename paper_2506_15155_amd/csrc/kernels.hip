@@ -5,22 +5,22 @@
 // around 128-bit coalesced loads from the scattered chunks and keep all arithmetic on ordinary
 // vector lanes; there is no dense contraction here that would pay for the matrix cores.
 //
-// Per-launch metadata (which tensors, their lengths, where each request's work items start) is
-// passed by value in the kernel arguments, so a launch needs no host-to-device copy and no staging
-// buffer whose lifetime would have to be tracked. The chunk tables live in a device mirror that is
-// patched, also through kernel arguments, whenever the host changes an entry.
+// Per-launch metadata (which tensors, their lengths, how the tiles are dealt out) is passed by value
+// in the kernel arguments, so a launch needs no host-to-device copy and no staging buffer whose
+// lifetime would have to be tracked. The chunk tables live in a device mirror that is patched, also
+// through kernel arguments, whenever the host changes an entry.
 #include "kernels.hpp"
 
 #include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <type_traits>
 
 namespace ellm {
 
 // ---------------------------------------------------------------------------------------------
 // small helpers
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
-
 // fp32 -> bf16 bits, round to nearest even; NaN stays NaN
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   uint32_t u = __float_as_uint(f);
@@ -39,17 +39,65 @@ constexpr int DPP_QUAD_XOR2 = 0x4E;        // quad_perm [2,3,0,1]
 constexpr int DPP_ROW_HALF_MIRROR = 0x141; // lane i <-> 7 - i within each 8 lanes
 constexpr int DPP_ROW_MIRROR = 0x140;      // lane i <-> 15 - i within each 16 lanes
 
-// sum over the LPR (8 or 16) consecutive lanes that share one K row; every lane gets the sum
-template <int LPR>
-__device__ __forceinline__ float row_sum(float v) {
+__device__ __forceinline__ float wave_max(float v) {
+  v = fmaxf(v, dpp_f32<DPP_QUAD_XOR1>(v));
+  v = fmaxf(v, dpp_f32<DPP_QUAD_XOR2>(v));
+  v = fmaxf(v, dpp_f32<DPP_ROW_HALF_MIRROR>(v));
+  v = fmaxf(v, dpp_f32<DPP_ROW_MIRROR>(v));
+  v = fmaxf(v, __shfl_xor(v, 16));
+  v = fmaxf(v, __shfl_xor(v, 32));
+  return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
   v += dpp_f32<DPP_QUAD_XOR1>(v);
   v += dpp_f32<DPP_QUAD_XOR2>(v);
   v += dpp_f32<DPP_ROW_HALF_MIRROR>(v);
-  if (LPR == 16) v += dpp_f32<DPP_ROW_MIRROR>(v);
+  v += dpp_f32<DPP_ROW_MIRROR>(v);
+  v += __shfl_xor(v, 16);
+  v += __shfl_xor(v, 32);
   return v;
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+// c + a.lo * b.lo + a.hi * b.hi on packed bf16 pairs, fp32 accumulate
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+
+// The same, with the first operand taken from lane N of this lane's row of 16 (a DPP broadcast
+// folded into the instruction): lets 16 lanes share one register of query values.
+template <int N>
+__device__ __forceinline__ float dot2_bf16_rowlane(uint32_t row_shared, uint32_t b, float c) {
+  asm("v_dot2c_f32_bf16_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+      : "+v"(c) : "v"(row_shared), "v"(b), "n"(N));
+  return c;
+}
+
+// The compiler cannot see that the inline-asm instruction above is a dot product, so it does not
+// insert the wait states the hardware needs between a dot product's result and its first use by a
+// different instruction (nor between a register write and its first use as a DPP source). Passing
+// the value through this makes the gap explicit.
+__device__ __forceinline__ void settle(float& v) { asm volatile("s_nop 3" : "+v"(v)); }
+__device__ __forceinline__ void settle(uint32_t& v) { asm volatile("s_nop 1" : "+v"(v)); }
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+typedef const __attribute__((address_space(1))) void* global_cptr_t;
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const int32_t __attribute__((address_space(4)))* const_i32_ptr;
+
+// s_waitcnt immediates (gfx9 encoding): vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8
+constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
 constexpr float NEG_BIG = -1.0e30f;   // finite stand-in for "no score yet"; exp2(NEG_BIG - x) == 0
 
@@ -95,202 +143,251 @@ __global__ __launch_bounds__(256) void kv_append_kernel(PoolView pv, const uint4
 }
 
 // ---------------------------------------------------------------------------------------------
-// decode attention, partial pass (split-K)
-//
-// One workgroup (4 waves) per (work item, kv head). A work item is a token range [t0, t1) of one
-// request, at most split_tokens long. A K or V row of D bf16 is read by LPR = D/8 consecutive
-// lanes with one 128-bit load each, so one wave-wide load covers RPW = 64/LPR consecutive rows
-// (1 KiB, contiguous inside a chunk). Each lane keeps, for the G query heads of the group, the
-// dot-product slice of its 8 dims; a DPP butterfly over the LPR lanes completes the score. The
-// online softmax state (running max m, running sum l, weighted-V accumulator for the lane's 8
-// dims) is per lane row-group; row-groups are merged with wave shuffles at the end, waves through
-// LDS, and the merged (m, l, acc) goes to the workspace for the combine pass.
-// Scores are kept in log2 units: q is pre-multiplied by scale * log2(e).
+// work partition shared by the partial pass, the combine pass and the calibration kernel
 // ---------------------------------------------------------------------------------------------
-template <int D, int G>
-__global__ __launch_bounds__(256) void decode_partial_kernel(PoolView pv, const uint16_t* __restrict__ q,
-                                                             float* __restrict__ ws, float scale_log2,
-                                                             int32_t split_tokens, int32_t g_first,
-                                                             BatchArgs a) {
-  constexpr int LPR = D / 8;       // lanes per row
-  constexpr int RPW = 64 / LPR;    // rows per wave-wide load
-  constexpr int U = 4;             // loads in flight per lane and plane
-  constexpr int TB = RPW * U;      // tokens per wave block
-  constexpr int ROWB = D * 2;      // bytes per row
-
-  __shared__ float sm_acc[4][G][D];
-  __shared__ float sm_ml[4][G][2];
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int sub = lane % LPR, rg = lane / LPR;
-  const int item = blockIdx.x;
-  const int g = blockIdx.y;                           // kv head
-  const int hq0 = g * pv.group + g_first;            // first q head handled here
-
-  // request of this item: number of item0[] entries <= item, minus one
-  const int b = __syncthreads_count(tid < a.n_req && a.item0[tid] <= item) - 1;
-  const int32_t tensor = a.tensor[b];
-  const int32_t len = a.len[b];
-  const int32_t t0 = (item - a.item0[b]) * split_tokens;
-  const int32_t t1 = min(len, t0 + split_tokens);
-
-  // q slice of this lane: 8 dims of each of the G heads, pre-scaled
-  float qf[G][8];
-  {
-    const uint16_t* qb = q + ((int64_t)(a.q_row0 + b) * pv.n_q_heads + hq0) * D + sub * 8;
-#pragma unroll
-    for (int i = 0; i < G; i++) {
-      uint4 w = *reinterpret_cast<const uint4*>(qb + i * D);
-      qf[i][0] = bf16_lo(w.x) * scale_log2; qf[i][1] = bf16_hi(w.x) * scale_log2;
-      qf[i][2] = bf16_lo(w.y) * scale_log2; qf[i][3] = bf16_hi(w.y) * scale_log2;
-      qf[i][4] = bf16_lo(w.z) * scale_log2; qf[i][5] = bf16_hi(w.z) * scale_log2;
-      qf[i][6] = bf16_lo(w.w) * scale_log2; qf[i][7] = bf16_hi(w.w) * scale_log2;
-    }
+// request b with tile_prefix[b] <= pos < tile_prefix[b + 1] (wave-uniform result)
+__device__ __forceinline__ int find_request(const BatchArgs& a, int pos, int lane) {
+  int cnt = 0;
+  for (int base = 0; base < a.n_req; base += 64) {
+    const int i = base + lane;
+    cnt += __popcll(__ballot(i < a.n_req && a.tile_prefix[i] <= pos));
   }
-
-  float m[G], l[G], acc[G][8];
-#pragma unroll
-  for (int i = 0; i < G; i++) {
-    m[i] = NEG_BIG; l[i] = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; e++) acc[i][e] = 0.f;
-  }
-
-  // walk the chunks the token range touches; wave blocks are dealt round-robin over the 4 waves
-  const int32_t Tc = pv.tokens_per_chunk;
-  int32_t slot = t0 / Tc;
-  int32_t r_begin = t0 - slot * Tc;
-  int32_t remaining = t1 - t0;
-  int32_t blk = 0;
-  const int32_t* trow = pv.table + (int64_t)tensor * pv.max_slots;
-  while (remaining > 0) {
-    const int32_t rows = min(Tc - r_begin, remaining);
-    const int32_t chunk = trow[slot];
-    const char* kbase = pv.base + (uint64_t)chunk * pv.chunk_bytes +
-                        ((uint64_t)(g * 2) * Tc + r_begin) * ROWB;
-    const char* vbase = kbase + (uint64_t)Tc * ROWB;
-    const int32_t nblk = (rows + TB - 1) / TB;
-    for (int32_t ib = (wave - blk) & 3; ib < nblk; ib += 4) {
-      uint4 kr[U], vr[U];
-      bool ok[U];
-#pragma unroll
-      for (int u = 0; u < U; u++) {
-        const int32_t rr = ib * TB + u * RPW + rg;
-        ok[u] = rr < rows;
-        const uint32_t off = (uint32_t)rr * ROWB + sub * 16;
-        kr[u] = make_uint4(0, 0, 0, 0);
-        vr[u] = make_uint4(0, 0, 0, 0);
-        if (ok[u]) {
-          kr[u] = *reinterpret_cast<const uint4*>(kbase + off);
-          vr[u] = *reinterpret_cast<const uint4*>(vbase + off);
-        }
-      }
-      float s[U][G];
-#pragma unroll
-      for (int u = 0; u < U; u++) {
-        float kf[8] = {bf16_lo(kr[u].x), bf16_hi(kr[u].x), bf16_lo(kr[u].y), bf16_hi(kr[u].y),
-                       bf16_lo(kr[u].z), bf16_hi(kr[u].z), bf16_lo(kr[u].w), bf16_hi(kr[u].w)};
-#pragma unroll
-        for (int i = 0; i < G; i++) {
-          float d = 0.f;
-#pragma unroll
-          for (int e = 0; e < 8; e++) d = fmaf(qf[i][e], kf[e], d);
-          d = row_sum<LPR>(d);
-          s[u][i] = ok[u] ? d : -INFINITY;
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < G; i++) {
-        float mn = m[i];
-#pragma unroll
-        for (int u = 0; u < U; u++) mn = fmaxf(mn, s[u][i]);
-        const float alpha = fast_exp2(m[i] - mn);
-        m[i] = mn;
-        l[i] *= alpha;
-#pragma unroll
-        for (int e = 0; e < 8; e++) acc[i][e] *= alpha;
-#pragma unroll
-        for (int u = 0; u < U; u++) s[u][i] = fast_exp2(s[u][i] - mn);
-      }
-#pragma unroll
-      for (int u = 0; u < U; u++) {
-        float vf[8] = {bf16_lo(vr[u].x), bf16_hi(vr[u].x), bf16_lo(vr[u].y), bf16_hi(vr[u].y),
-                       bf16_lo(vr[u].z), bf16_hi(vr[u].z), bf16_lo(vr[u].w), bf16_hi(vr[u].w)};
-#pragma unroll
-        for (int i = 0; i < G; i++) {
-          const float p = s[u][i];
-          l[i] += p;
-#pragma unroll
-          for (int e = 0; e < 8; e++) acc[i][e] = fmaf(p, vf[e], acc[i][e]);
-        }
-      }
-    }
-    blk += nblk;
-    remaining -= rows;
-    slot += 1;
-    r_begin = 0;
-  }
-
-  // merge the RPW row-groups of the wave (lanes that hold the same dims)
-#pragma unroll
-  for (int off = LPR; off < 64; off <<= 1) {
-#pragma unroll
-    for (int i = 0; i < G; i++) {
-      const float mo = __shfl_xor(m[i], off);
-      const float lo = __shfl_xor(l[i], off);
-      const float mn = fmaxf(m[i], mo);
-      const float ca = fast_exp2(m[i] - mn), cb = fast_exp2(mo - mn);
-      l[i] = l[i] * ca + lo * cb;
-#pragma unroll
-      for (int e = 0; e < 8; e++) {
-        const float ao = __shfl_xor(acc[i][e], off);
-        acc[i][e] = acc[i][e] * ca + ao * cb;
-      }
-      m[i] = mn;
-    }
-  }
-  if (rg == 0) {
-#pragma unroll
-    for (int i = 0; i < G; i++) {
-      float4* dst = reinterpret_cast<float4*>(&sm_acc[wave][i][sub * 8]);
-      dst[0] = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
-      dst[1] = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
-      if (sub == 0) { sm_ml[wave][i][0] = m[i]; sm_ml[wave][i][1] = l[i]; }
-    }
-  }
-  __syncthreads();
-  // merge the 4 waves and write the partial: [item][q head][D + 2] = acc..., m, l
-  float* wout = ws + ((int64_t)(a.item_base + item) * pv.n_q_heads + hq0) * (D + 2);
-  for (int idx = tid; idx < G * D; idx += 256) {
-    const int i = idx / D, d = idx - i * D;
-    float mn = sm_ml[0][i][0];
-#pragma unroll
-    for (int w = 1; w < 4; w++) mn = fmaxf(mn, sm_ml[w][i][0]);
-    float lsum = 0.f, asum = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; w++) {
-      const float c = fast_exp2(sm_ml[w][i][0] - mn);
-      lsum += sm_ml[w][i][1] * c;
-      asum += sm_acc[w][i][d] * c;
-    }
-    wout[i * (D + 2) + d] = asum;
-    if (d == 0) { wout[i * (D + 2) + D] = mn; wout[i * (D + 2) + D + 1] = lsum; }
-  }
+  return __builtin_amdgcn_readfirstlane(cnt - 1);
 }
 
 // ---------------------------------------------------------------------------------------------
-// combine pass: merge the partials of every (request, q head) in split order, normalise, round
+// decode attention, partial pass (split-K): one wave per equal share of the launch's tiles
+//
+// A tile is up to 64 consecutive rows of one chunk of one (request, kv head). Per tile:
+//   K  64 rows are fetched with coalesced 128-bit loads (LPR = D/8 lanes per row) that write straight
+//      into LDS (no staging registers), then read back transposed: lane t owns token t and reads
+//      its whole row, so a score needs no cross-lane reduction. The query values of the G heads of
+//      the group stay in registers, one packed bf16 pair per lane and 16 lanes per row sharing a
+//      register; v_dot2_f32_bf16 with a DPP row broadcast multiplies two pairs per lane-op.
+//   softmax  one score per lane and head; the tile maximum is a wave reduction; weights are
+//      rounded to bf16 (the running sum l uses the rounded weights, so they still sum to one)
+//      and handed to the PV layout through LDS.
+//   V  is consumed straight from registers in the load layout (lane = 8 dims of one row, RPW rows
+//      per wave-wide load): rows of two consecutive loads are interleaved with v_perm_b32 so that
+//      one v_dot2_f32_bf16 adds two tokens' contributions to a dim.
+// V of the tile is in flight while its scores are computed, K of the next tile while V is multiplied.
+// Scores are kept in log2 units (scale_log2 = scale * log2 e).
+// ---------------------------------------------------------------------------------------------
+template <int D, int G>
+__global__ __launch_bounds__(64) void decode_partial_kernel(PoolView pv, const uint16_t* __restrict__ q,
+                                                            float* __restrict__ ws, float scale_log2,
+                                                            int32_t g_first, BatchArgs a) {
+  constexpr int LPR = D / 8;             // lanes per row = 16-byte pieces per row
+  constexpr int RPW = 64 / LPR;          // rows per wave-wide load
+  constexpr int NL = 64 / RPW;           // wave-wide loads per 64-row tile and plane
+  constexpr int ROWB = D * 2;            // bytes per row
+  constexpr int QR = D / 32;             // registers holding one head's query (16 lanes x 1 pair each)
+  constexpr int K_OFF = 0;               // one LDS buffer: K tile | weights
+  constexpr int P_OFF = 64 * ROWB;
+  __shared__ __attribute__((aligned(16))) char smem[P_OFF + G * 64 * 2];
+
+  const int lane = threadIdx.x;
+  const int sub = lane % LPR, rg = lane / LPR;
+  const int w = blockIdx.x;
+  const int32_t Tc = pv.tokens_per_chunk;
+  const int32_t TT = a.tiles_per_head;
+  const uint64_t plane = (uint64_t)Tc * ROWB;        // V plane follows the K plane of the same head
+
+  int32_t pos = w * a.tiles_per_wave;                                  // position in the tile sequence
+  const int32_t pos_end = min(TT * pv.n_kv_heads, pos + a.tiles_per_wave);
+  if (pos >= pos_end) return;
+  int32_t g = pos / TT;                                                 // kv head
+  int32_t rem = pos - g * TT;
+  int32_t b = find_request(a, rem, lane);
+
+  // Tile loads. Lane (rg, sub) handles piece `sub` of tile rows RPW*u + rg, u = 0 .. NL-1. Rows past
+  // nv are replaced by row nv - 1, so every load is in bounds and returns finite data; those
+  // rows are masked later (score -inf, weight 0).
+  // K goes straight from global memory into LDS (one 16-byte slot per lane, slots in lane order, so a
+  // wave-wide load fills RPW consecutive LDS rows). To make the transposed reads conflict-free the
+  // swizzle is applied on the source side: LDS slot (row, c) receives piece c ^ (row % LPR).
+  const int sx = sub ^ rg;    // (RPW*u + rg) % LPR == ((RPW*u) % LPR) | rg
+  const int kswz = lane % LPR;
+#define ELLM_LOAD_K_TILE(base, nvalid)                                                              \
+  _Pragma("unroll") for (int u = 0; u < NL; u++) {                                                  \
+    const uint32_t off_ = (uint32_t)min(RPW * u + rg, (nvalid) - 1) * ROWB +                        \
+                          (uint32_t)((sx ^ ((RPW * u) % LPR)) * 16);                                \
+    __builtin_amdgcn_global_load_lds((global_cptr_t)((base) + off_),                                \
+                                     (lds_ptr_t)(smem + K_OFF + u * (RPW * ROWB)), 16, 0, 0);       \
+  }
+#define ELLM_LOAD_V_TILE(dst, base, nvalid)                                                         \
+  _Pragma("unroll") for (int u = 0; u < NL; u++) {                                                  \
+    const uint32_t off_ = (uint32_t)min(RPW * u + rg, (nvalid) - 1) * ROWB + sub * 16;              \
+    dst[u] = *reinterpret_cast<const uint4*>((base) + off_);                                        \
+  }
+
+  while (pos < pos_end) {
+    // ---- one piece: tiles [tile0, tile0 + n_tiles) of request b, kv head g ----------------------
+    const int32_t tile0 = rem - a.tile_prefix[b];
+    const int32_t tiles_b = a.tile_prefix[b + 1] - a.tile_prefix[b];
+    const int32_t n_tiles = min(tiles_b - tile0, pos_end - pos);
+    const int32_t len = a.len[b];
+    const int hq0 = g * pv.group + g_first;            // first q head handled here
+    // the table row is read-only for the kernel's lifetime: uniform (scalar) loads
+    const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)a.tensor[b] * pv.max_slots);
+
+    // query: lane keeps pair (16 c + lane % 16) of each head in qreg[.][c]
+    uint32_t qreg[G][QR];
+    {
+      const uint32_t* qsrc = reinterpret_cast<const uint32_t*>(q + ((int64_t)(a.q_row0 + b) * pv.n_q_heads + hq0) * D);
+#pragma unroll
+      for (int i = 0; i < G; i++)
+#pragma unroll
+        for (int c = 0; c < QR; c++) qreg[i][c] = qsrc[i * (D / 2) + c * 16 + (lane & 15)];
+#pragma unroll
+      for (int i = 0; i < G; i++)
+#pragma unroll
+        for (int c = 0; c < QR; c++) settle(qreg[i][c]);
+    }
+
+    float m[G], l[G], acc[G][8];
+#pragma unroll
+    for (int i = 0; i < G; i++) {
+      m[i] = NEG_BIG; l[i] = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; e++) acc[i][e] = 0.f;
+    }
+
+    // cursor: tile index -> (slot, first row, valid rows)
+    int32_t slot = tile0 / pv.tiles_per_chunk;
+    int32_t r = (tile0 - slot * pv.tiles_per_chunk) * TILE_TOKENS;
+    int32_t nv = min(TILE_TOKENS, min(Tc - r, len - (slot * Tc + r)));
+    const char* kb = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + ((uint64_t)(g * 2) * Tc + r) * ROWB;
+    ELLM_LOAD_K_TILE(kb, nv)
+
+    for (int32_t it = 0; it < n_tiles; it++) {
+      // the K tile is the only load outstanding here: wait until it has landed in LDS, then start
+      // this tile's V, which stays in flight while the scores are computed
+      __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+      __builtin_amdgcn_wave_barrier();
+      uint4 vr[NL];
+      ELLM_LOAD_V_TILE(vr, kb + plane, nv)
+
+      // scores: lane = token
+      float s[G];
+#pragma unroll
+      for (int i = 0; i < G; i++) s[i] = 0.f;
+      static_for<0, LPR>([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        const uint4 kp = *reinterpret_cast<const uint4*>(smem + K_OFF + lane * ROWB + ((j ^ kswz) * 16));
+#pragma unroll
+        for (int i = 0; i < G; i++) {
+          s[i] = dot2_bf16_rowlane<4 * (j % 4) + 0>(qreg[i][j / 4], kp.x, s[i]);
+          s[i] = dot2_bf16_rowlane<4 * (j % 4) + 1>(qreg[i][j / 4], kp.y, s[i]);
+          s[i] = dot2_bf16_rowlane<4 * (j % 4) + 2>(qreg[i][j / 4], kp.z, s[i]);
+          s[i] = dot2_bf16_rowlane<4 * (j % 4) + 3>(qreg[i][j / 4], kp.w, s[i]);
+        }
+      });
+#pragma unroll
+      for (int i = 0; i < G; i++) settle(s[i]);
+      // online softmax over the tile; weights go to LDS as bf16 in the order the PV lanes read them
+      const int pidx = (lane % RPW) * NL + lane / RPW;
+#pragma unroll
+      for (int i = 0; i < G; i++) {
+        const float sc = lane < nv ? s[i] * scale_log2 : -INFINITY;
+        const float mn = fmaxf(m[i], wave_max(sc));
+        const float alpha = fast_exp2(m[i] - mn);
+        m[i] = mn;
+        uint32_t pu = __float_as_uint(fast_exp2(sc - mn));
+        pu = (pu + 0x7fffu + ((pu >> 16) & 1u)) & 0xffff0000u;      // round to bf16, nearest even
+        l[i] = l[i] * alpha + __uint_as_float(pu);
+        *reinterpret_cast<uint16_t*>(smem + P_OFF + (i * 64 + pidx) * 2) = (uint16_t)(pu >> 16);
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc[i][e] *= alpha;
+      }
+      __builtin_amdgcn_wave_barrier();
+
+      // the K tile has been consumed: fetch the next one while V is multiplied
+      if (it + 1 < n_tiles) {
+        r += TILE_TOKENS;
+        if (r >= Tc) { r = 0; slot += 1; }
+        nv = min(TILE_TOKENS, min(Tc - r, len - (slot * Tc + r)));
+        kb = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + ((uint64_t)(g * 2) * Tc + r) * ROWB;
+        ELLM_LOAD_K_TILE(kb, nv)
+      }
+      __builtin_amdgcn_wave_barrier();
+
+      // weighted V: two tokens per dot2
+#pragma unroll
+      for (int i = 0; i < G; i++) {
+        uint32_t pp[NL / 2];
+#pragma unroll
+        for (int x = 0; x < NL / 8; x++) {
+          const uint4 t4 = *reinterpret_cast<const uint4*>(smem + P_OFF + (i * 64 + rg * NL + x * 8) * 2);
+          pp[x * 4 + 0] = t4.x; pp[x * 4 + 1] = t4.y; pp[x * 4 + 2] = t4.z; pp[x * 4 + 3] = t4.w;
+        }
+#pragma unroll
+        for (int v = 0; v < NL / 2; v++) {
+          const uint4 A = vr[2 * v], Bv = vr[2 * v + 1];
+          acc[i][0] = dot2_bf16(__builtin_amdgcn_perm(Bv.x, A.x, 0x05040100u), pp[v], acc[i][0]);
+          acc[i][1] = dot2_bf16(__builtin_amdgcn_perm(Bv.x, A.x, 0x07060302u), pp[v], acc[i][1]);
+          acc[i][2] = dot2_bf16(__builtin_amdgcn_perm(Bv.y, A.y, 0x05040100u), pp[v], acc[i][2]);
+          acc[i][3] = dot2_bf16(__builtin_amdgcn_perm(Bv.y, A.y, 0x07060302u), pp[v], acc[i][3]);
+          acc[i][4] = dot2_bf16(__builtin_amdgcn_perm(Bv.z, A.z, 0x05040100u), pp[v], acc[i][4]);
+          acc[i][5] = dot2_bf16(__builtin_amdgcn_perm(Bv.z, A.z, 0x07060302u), pp[v], acc[i][5]);
+          acc[i][6] = dot2_bf16(__builtin_amdgcn_perm(Bv.w, A.w, 0x05040100u), pp[v], acc[i][6]);
+          acc[i][7] = dot2_bf16(__builtin_amdgcn_perm(Bv.w, A.w, 0x07060302u), pp[v], acc[i][7]);
+        }
+      }
+    }
+
+    // every row-group holds the same dims for different tokens under one common maximum: add them up
+#pragma unroll
+    for (int i = 0; i < G; i++) {
+#pragma unroll
+      for (int off = LPR; off < 64; off <<= 1) {
+#pragma unroll
+        for (int e = 0; e < 8; e++) acc[i][e] += __shfl_xor(acc[i][e], off);
+      }
+      l[i] = wave_sum(l[i]);
+    }
+    // partial number (w - first wave of this pair) of pair (b, g): [q head][D accumulators, m, l, 2 unused]
+    const int32_t w_first = (g * TT + a.tile_prefix[b]) / a.tiles_per_wave;
+    float* wout = ws + (((int64_t)a.ws_slot0 + (int64_t)(b * pv.n_kv_heads + g) * a.max_partials + (w - w_first)) * pv.group +
+                        g_first) * (D + WS_ROW_PAD);
+    if (rg == 0) {
+#pragma unroll
+      for (int i = 0; i < G; i++) {
+        float4* dst = reinterpret_cast<float4*>(wout + i * (D + WS_ROW_PAD) + sub * 8);
+        dst[0] = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+        dst[1] = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
+        if (sub == 0) { wout[i * (D + WS_ROW_PAD) + D] = m[i]; wout[i * (D + WS_ROW_PAD) + D + 1] = l[i]; }
+      }
+    }
+
+    // next piece: same kv head, next request; or next kv head from its first request
+    pos += n_tiles;
+    rem += n_tiles;
+    if (rem == TT) { rem = 0; g += 1; b = 0; }
+    else if (tile0 + n_tiles == tiles_b) b += 1;
+    __builtin_amdgcn_wave_barrier();
+  }
+#undef ELLM_LOAD_K_TILE
+#undef ELLM_LOAD_V_TILE
+}
+
+// ---------------------------------------------------------------------------------------------
+// combine pass: merge the partials of every (request, q head) in wave order, normalise, round
 // ---------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(D) void decode_combine_kernel(const float* __restrict__ ws, uint16_t* __restrict__ out,
-                                                           int32_t n_q_heads, BatchArgs a) {
+                                                           int32_t n_q_heads, int32_t n_kv_heads, int32_t group,
+                                                           BatchArgs a) {
   const int b = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
-  const int j0 = a.item0[b];
-  const int j1 = (b + 1 < a.n_req) ? a.item0[b + 1] : a.n_items;
+  const int g = h / group;
+  const int f0 = g * a.tiles_per_head + a.tile_prefix[b];
+  const int f1 = g * a.tiles_per_head + a.tile_prefix[b + 1];
+  const int w0 = f0 / a.tiles_per_wave, w1 = (f1 - 1) / a.tiles_per_wave;
+  const float* p = ws + ((a.ws_slot0 + (int64_t)(b * n_kv_heads + g) * a.max_partials) * group + (h - g * group)) *
+                            (D + WS_ROW_PAD);
+  const int64_t stride = (int64_t)group * (D + WS_ROW_PAD);
   float M = NEG_BIG, L = 0.f, A = 0.f;
-  for (int j = j0; j < j1; j++) {
-    const float* p = ws + ((int64_t)(a.item_base + j) * n_q_heads + h) * (D + 2);
+  for (int j = 0; j <= w1 - w0; j++, p += stride) {
     const float mj = p[D], lj = p[D + 1], aj = p[d];
     const float mn = fmaxf(M, mj);
     const float c0 = fast_exp2(M - mn), c1 = fast_exp2(mj - mn);
@@ -299,6 +396,82 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(const float* __restri
     M = mn;
   }
   out[((int64_t)(a.q_row0 + b) * n_q_heads + h) * D + d] = (uint16_t)f32_to_bf16_bits(A / L);
+}
+
+// ---------------------------------------------------------------------------------------------
+// calibration kernels (measurement only; they compute nothing of the method)
+// ---------------------------------------------------------------------------------------------
+// plain copy of n 16-byte words: the known-size kernel the HBM byte counters are scaled against
+__global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * 256 * 4;
+  for (int64_t i = (int64_t)blockIdx.x * 256 * 4 + threadIdx.x; i < n; i += stride) {
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++) { v[u] = make_uint4(0, 0, 0, 0); if (i + u * 256 < n) v[u] = src[i + u * 256]; }
+#pragma unroll
+    for (int u = 0; u < 4; u++) if (i + u * 256 < n) dst[i + u * 256] = v[u];
+  }
+}
+
+// contiguous read of n 16-byte words: the read ceiling of this GPU for a streaming kernel
+__global__ __launch_bounds__(256) void read_kernel(const uint4* __restrict__ src, int64_t n, uint32_t* __restrict__ sink) {
+  const int64_t stride = (int64_t)gridDim.x * 256 * 8;
+  uint32_t x = 0;
+  for (int64_t i = (int64_t)blockIdx.x * 256 * 8 + threadIdx.x; i < n; i += stride) {
+    uint4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) { v[u] = make_uint4(0, 0, 0, 0); if (i + u * 256 < n) v[u] = src[i + u * 256]; }
+#pragma unroll
+    for (int u = 0; u < 8; u++) x ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  if (x == 0x9e3779b9u) sink[0] = x;      // practically never true; keeps the loads alive
+}
+
+// the K/V rows a decode over this batch reads, with the same work partition and load shape (one
+// wave per equal share of tiles, 64-row tiles, 128-bit loads), but no arithmetic
+template <int D>
+__global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __restrict__ sink, BatchArgs a) {
+  constexpr int LPR = D / 8, RPW = 64 / LPR, NL = 64 / RPW, ROWB = D * 2;
+  const int lane = threadIdx.x;
+  const int sub = lane % LPR, rg = lane / LPR;
+  const int w = blockIdx.x;
+  const int32_t Tc = pv.tokens_per_chunk, TT = a.tiles_per_head;
+  int32_t pos = w * a.tiles_per_wave;
+  const int32_t pos_end = min(TT * pv.n_kv_heads, pos + a.tiles_per_wave);
+  if (pos >= pos_end) return;
+  int32_t g = pos / TT, rem = pos - g * TT;
+  int32_t b = find_request(a, rem, lane);
+  uint32_t x = 0;
+  while (pos < pos_end) {
+    const int32_t tile0 = rem - a.tile_prefix[b];
+    const int32_t tiles_b = a.tile_prefix[b + 1] - a.tile_prefix[b];
+    const int32_t n_tiles = min(tiles_b - tile0, pos_end - pos);
+    const int32_t len = a.len[b];
+    const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)a.tensor[b] * pv.max_slots);
+    int32_t slot = tile0 / pv.tiles_per_chunk;
+    int32_t r = (tile0 - slot * pv.tiles_per_chunk) * TILE_TOKENS;
+    for (int32_t it = 0; it < n_tiles; it++) {
+      const int32_t nv = min(TILE_TOKENS, min(Tc - r, len - (slot * Tc + r)));
+      const char* kb = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + ((uint64_t)(g * 2) * Tc + r) * ROWB;
+      const char* vb = kb + (uint64_t)Tc * ROWB;
+      uint4 kr[NL], vr[NL];
+#pragma unroll
+      for (int u = 0; u < NL; u++) {
+        const uint32_t off = (uint32_t)min(RPW * u + rg, nv - 1) * ROWB + sub * 16;
+        kr[u] = *reinterpret_cast<const uint4*>(kb + off);
+        vr[u] = *reinterpret_cast<const uint4*>(vb + off);
+      }
+#pragma unroll
+      for (int u = 0; u < NL; u++) x ^= kr[u].x ^ kr[u].y ^ kr[u].z ^ kr[u].w ^ vr[u].x ^ vr[u].y ^ vr[u].z ^ vr[u].w;
+      r += TILE_TOKENS;
+      if (r >= Tc) { r = 0; slot += 1; }
+    }
+    pos += n_tiles;
+    rem += n_tiles;
+    if (rem == TT) { rem = 0; g += 1; b = 0; }
+    else if (tile0 + n_tiles == tiles_b) b += 1;
+  }
+  if (x == 0x9e3779b9u) sink[0] = x;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -334,42 +507,95 @@ int launch_kv_append(const PoolView& pv, const void* k_new, const void* v_new, c
   return 0;
 }
 
+// widest template instance that does not exceed the q heads still to do in a group
+static int group_step(int left) { return left >= 8 ? 8 : left >= 4 ? 4 : left >= 2 ? 2 : 1; }
+
+template <int D>
+static const void* partial_kernel_ptr(int step) {
+  switch (step) {
+    case 8: return (const void*)decode_partial_kernel<D, 8>;
+    case 4: return (const void*)decode_partial_kernel<D, 4>;
+    case 2: return (const void*)decode_partial_kernel<D, 2>;
+    default: return (const void*)decode_partial_kernel<D, 1>;
+  }
+}
+
+int partial_waves_per_cu(int head_dim, int group) {
+  // the q heads of a group are handled 8, 4, 2 or 1 at a time; plan for the widest instance used
+  const int step = group_step(group);
+  const void* f = head_dim == 128 ? partial_kernel_ptr<128>(step) : partial_kernel_ptr<64>(step);
+  int n = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, f, 64, 0) != hipSuccess || n < 1) n = 1;
+  return n;
+}
+
 template <int D, int G>
-static void launch_partial_t(const PoolView& pv, const void* q, float* ws, float scale_log2, int32_t split_tokens,
-                             int32_t g_first, const BatchArgs& a, hipStream_t stream) {
-  hipLaunchKernelGGL((decode_partial_kernel<D, G>), dim3(a.n_items, pv.n_kv_heads), dim3(256), 0, stream, pv,
-                     (const uint16_t*)q, ws, scale_log2, split_tokens, g_first, a);
+static void launch_partial_t(const PoolView& pv, const void* q, float* ws, float scale_log2, int32_t g_first,
+                             const BatchArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL((decode_partial_kernel<D, G>), dim3(a.n_waves), dim3(64), 0, stream, pv,
+                     (const uint16_t*)q, ws, scale_log2, g_first, a);
 }
 
 template <int D>
-static int launch_partial_d(const PoolView& pv, const void* q, float* ws, float scale_log2, int32_t split_tokens,
-                            const BatchArgs& a, hipStream_t stream) {
-  // the q heads of a group are handled 8, 4, 2 or 1 at a time; a group size that is not one of
-  // those is covered by several launches over the same K/V
+static int launch_partial_d(const PoolView& pv, const void* q, float* ws, float scale_log2, const BatchArgs& a,
+                            hipStream_t stream) {
+  // a group size that is not 8, 4, 2 or 1 is covered by several launches over the same K/V
   int done = 0;
   while (done < pv.group) {
-    const int left = pv.group - done;
-    if (left >= 8) { launch_partial_t<D, 8>(pv, q, ws, scale_log2, split_tokens, done, a, stream); done += 8; }
-    else if (left >= 4) { launch_partial_t<D, 4>(pv, q, ws, scale_log2, split_tokens, done, a, stream); done += 4; }
-    else if (left >= 2) { launch_partial_t<D, 2>(pv, q, ws, scale_log2, split_tokens, done, a, stream); done += 2; }
-    else { launch_partial_t<D, 1>(pv, q, ws, scale_log2, split_tokens, done, a, stream); done += 1; }
+    const int step = group_step(pv.group - done);
+    if (step == 8) launch_partial_t<D, 8>(pv, q, ws, scale_log2, done, a, stream);
+    else if (step == 4) launch_partial_t<D, 4>(pv, q, ws, scale_log2, done, a, stream);
+    else if (step == 2) launch_partial_t<D, 2>(pv, q, ws, scale_log2, done, a, stream);
+    else launch_partial_t<D, 1>(pv, q, ws, scale_log2, done, a, stream);
     ELLM_HIP_CHECK_LAUNCH();
+    done += step;
   }
   return 0;
 }
 
-int launch_decode(const PoolView& pv, const void* q, void* out, float* ws, float scale_log2, int32_t split_tokens,
-                  const BatchArgs& a, hipStream_t stream) {
+int launch_decode_partial(const PoolView& pv, const void* q, float* ws, float scale_log2, const BatchArgs& a,
+                          hipStream_t stream) {
+  if (a.n_req <= 0 || a.n_waves <= 0) return 0;
+  return pv.head_dim == 128 ? launch_partial_d<128>(pv, q, ws, scale_log2, a, stream)
+                            : launch_partial_d<64>(pv, q, ws, scale_log2, a, stream);
+}
+
+int launch_decode_combine(const PoolView& pv, const float* ws, void* out, const BatchArgs& a, hipStream_t stream) {
   if (a.n_req <= 0) return 0;
-  int rc = pv.head_dim == 128 ? launch_partial_d<128>(pv, q, ws, scale_log2, split_tokens, a, stream)
-                              : launch_partial_d<64>(pv, q, ws, scale_log2, split_tokens, a, stream);
-  if (rc) return rc;
   if (pv.head_dim == 128)
     hipLaunchKernelGGL(decode_combine_kernel<128>, dim3(a.n_req, pv.n_q_heads), dim3(128), 0, stream, ws,
-                       (uint16_t*)out, pv.n_q_heads, a);
+                       (uint16_t*)out, pv.n_q_heads, pv.n_kv_heads, pv.group, a);
   else
     hipLaunchKernelGGL(decode_combine_kernel<64>, dim3(a.n_req, pv.n_q_heads), dim3(64), 0, stream, ws,
-                       (uint16_t*)out, pv.n_q_heads, a);
+                       (uint16_t*)out, pv.n_q_heads, pv.n_kv_heads, pv.group, a);
+  ELLM_HIP_CHECK_LAUNCH();
+  return 0;
+}
+
+int launch_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream) {
+  const int64_t n = bytes / 16;
+  if (n <= 0) return 0;
+  const int64_t blocks = std::min<int64_t>((n + 1023) / 1024, 256 * 32);
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (uint4*)dst, (const uint4*)src, n);
+  ELLM_HIP_CHECK_LAUNCH();
+  return 0;
+}
+
+int launch_read(const void* src, int64_t bytes, uint32_t* sink, hipStream_t stream) {
+  const int64_t n = bytes / 16;
+  if (n <= 0) return 0;
+  const int64_t blocks = std::min<int64_t>((n + 2047) / 2048, 256 * 32);
+  hipLaunchKernelGGL(read_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (const uint4*)src, n, sink);
+  ELLM_HIP_CHECK_LAUNCH();
+  return 0;
+}
+
+int launch_kv_stream(const PoolView& pv, uint32_t* sink, const BatchArgs& a, hipStream_t stream) {
+  if (a.n_req <= 0 || a.n_waves <= 0) return 0;
+  if (pv.head_dim == 128)
+    hipLaunchKernelGGL(kv_stream_kernel<128>, dim3(a.n_waves), dim3(64), 0, stream, pv, sink, a);
+  else
+    hipLaunchKernelGGL(kv_stream_kernel<64>, dim3(a.n_waves), dim3(64), 0, stream, pv, sink, a);
   ELLM_HIP_CHECK_LAUNCH();
   return 0;
 }

@@ -8,6 +8,8 @@ namespace ellm {
 
 constexpr int MAX_LAUNCH_REQ = 256;   // requests described by one launch's kernel arguments
 constexpr int MAX_PATCH = 448;        // table entries patched by one launch
+constexpr int TILE_TOKENS = 64;       // rows of K (and V) one wave handles at a time
+constexpr int WS_ROW_PAD = 4;         // a partial row is head_dim accumulators, m, l and 2 unused floats
 
 // what a kernel needs to turn (tensor, token) into an address
 struct PoolView {
@@ -15,18 +17,30 @@ struct PoolView {
   const int32_t* table;       // device mirror of the chunk tables, [max_tensors][max_slots]
   uint32_t chunk_bytes;
   int32_t tokens_per_chunk;
+  int32_t tiles_per_chunk;    // ceil(tokens_per_chunk / TILE_TOKENS); a tile never straddles a chunk
   int32_t max_slots;
   int32_t n_q_heads, n_kv_heads, head_dim, group;
 };
 
-// one decode launch: requests [q_row0, q_row0 + n_req) of the caller's batch
+// One decode launch: requests [q_row0, q_row0 + n_req) of the caller's batch.
+// The tiles of all (kv head, request) pairs are laid out in one sequence, kv head major:
+//   position = g * tiles_per_head + tile_prefix[b] + tile.
+// Wave w of the partial pass handles positions [w * tiles_per_wave, (w + 1) * tiles_per_wave), so every
+// wave gets the same number of tiles whatever the mix of lengths; where its range crosses from one
+// (request, kv head) to the next it writes one partial per piece. The partial of wave w for
+// (b, g) is number w - first_wave(b, g) of that pair.
 struct BatchArgs {
-  int32_t n_req, n_items;     // n_items = work items of these requests
-  int32_t item_base;          // first workspace item of this launch
+  int32_t n_req;
   int32_t q_row0;             // row of the first request in q / out
+  int32_t tiles_per_head;     // = tile_prefix[n_req]
+  int32_t tiles_per_wave;
+  int32_t n_waves;            // ceil(tiles_per_head * n_kv_heads / tiles_per_wave)
+  int32_t max_partials;       // partial slots per (request, kv head)
+  int32_t ws_slot0;           // first partial slot of this launch in the workspace
+  int32_t pad;
   int32_t tensor[MAX_LAUNCH_REQ];
   int32_t len[MAX_LAUNCH_REQ];
-  int32_t item0[MAX_LAUNCH_REQ];   // first work item of request b, relative to this launch
+  int32_t tile_prefix[MAX_LAUNCH_REQ + 1];
 };
 
 struct AppendArgs {
@@ -42,11 +56,20 @@ struct PatchArgs {
   int32_t val[MAX_PATCH];
 };
 
+// resident waves of the partial-pass kernel per compute unit (occupancy query), per (head_dim, group)
+int partial_waves_per_cu(int head_dim, int group);
+
 // each returns 0 or a hipError_t value
 int launch_table_patch(int32_t* table, const PatchArgs& a, hipStream_t stream);
 int launch_kv_append(const PoolView& pv, const void* k_new, const void* v_new, const AppendArgs& a,
                      hipStream_t stream);
-int launch_decode(const PoolView& pv, const void* q, void* out, float* ws, float scale_log2, int32_t split_tokens,
-                  const BatchArgs& a, hipStream_t stream);
+int launch_decode_partial(const PoolView& pv, const void* q, float* ws, float scale_log2, const BatchArgs& a,
+                          hipStream_t stream);
+int launch_decode_combine(const PoolView& pv, const float* ws, void* out, const BatchArgs& a, hipStream_t stream);
+
+// calibration (measurement only)
+int launch_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream);
+int launch_read(const void* src, int64_t bytes, uint32_t* sink, hipStream_t stream);
+int launch_kv_stream(const PoolView& pv, uint32_t* sink, const BatchArgs& a, hipStream_t stream);
 
 }  // namespace ellm

@@ -116,7 +116,7 @@ def test_closed_forms_on_gpu():
     cfg = W.scaled(W.CONFIGS["tiny"], batch=1)
     rng = np.random.default_rng(3)
     # L = 1: output is V[0] bit for bit
-    B = H.Both(cfg)
+    B = H.Both(cfg, max_tensors=4)
     t = B.create(64)
     assert B.map(t, 0, 1, [7]) == 0
     k, v = W.normal_bf16(rng, (1, 8, 64)), W.normal_bf16(rng, (1, 8, 64))
