@@ -218,11 +218,11 @@ int ellm_pool_get_owner_state(ellm_pool* pool, uint8_t* owner, uint8_t* state,
 /* Per host slot (host arrays of n_host_slots, any may be NULL): the (tensor, slot) stored, else -1. */
 int ellm_pool_get_host_slots(ellm_pool* pool, int32_t* tensor, int32_t* slot);
 /* The partition the next decode over these handles would use: n_split[b] (host array of batch) is
- * the largest number of partial results any (request b, kv head) pair is split into, *split_tokens
- * the tokens each wave of the partial pass handles. For tests of the split partition. */
+ * the number of pieces (partial results) each (request b, kv head) pair is cut into, *split_tokens
+ * the tokens per piece. For tests of the split partition. */
 int ellm_decode_plan(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch,
                      int32_t* n_split, int32_t* split_tokens);
-/* Override the tokens per wave (rounded down to whole 64-token tiles, at least one; 0 = automatic).
+/* Override the tokens per piece (rounded down to whole 64-token tiles, at least one; 0 = automatic).
  * For tests that compare partitions. */
 int ellm_pool_set_split_tokens(ellm_pool* pool, int32_t split_tokens);
 
@@ -245,6 +245,11 @@ int ellm_pool_profile_collect(ellm_pool* pool, float* ms, int32_t cap, int32_t* 
 int ellm_debug_copy(void* dst, const void* src, uint64_t bytes, void* stream);
 int ellm_debug_stream_read(const void* src, uint64_t bytes, void* sink, void* stream);
 int ellm_debug_kv_stream_read(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, void* sink, void* stream);
+
+/* How the partial pass hands pieces to waves, for A/B measurements: 0 = automatic, 1 = one wave
+ * per piece, 2 = resident waves that take pieces from a shared counter. The cut into pieces, and
+ * with it every result bit, is the same in all three. */
+int ellm_debug_set_schedule(ellm_pool* pool, int schedule);
 
 /* O(n) consistency scan of the host state (tables, chunk records, free lists, host slots agree;
  * no chunk backs two slots). Returns 0 when consistent, else a positive rule number. */

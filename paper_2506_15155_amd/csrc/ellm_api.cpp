@@ -58,6 +58,9 @@ struct ellm_pool {
   bool have_last_stream = false;
   int32_t split_override = 0;
   int32_t wave_slots = 0;              // resident partial-pass waves on the whole GPU (0 = not asked yet)
+  int32_t* d_counters = nullptr;       // ring of piece counters (zero between uses)
+  int32_t next_counter = 0;
+  int32_t schedule = 0;                // 0 = automatic, 1 = one wave per piece, 2 = persistent waves
 
   // optional timing of the partial (dominant) kernel with events on the caller's stream
   std::vector<hipEvent_t> prof_ev;     // 2 per record
@@ -67,6 +70,7 @@ struct ellm_pool {
   std::vector<int32_t> n_eff;
   std::vector<ellm::Move> moves;
   std::vector<ellm::BatchArgs> launches;
+  std::vector<int32_t> tiles_tmp;
 };
 
 namespace {
@@ -99,6 +103,8 @@ int ensure_device(ellm_pool* p) {
   HIP_TRY(hipMalloc((void**)&p->d_table, bytes), "hipMalloc(table mirror)");
   HIP_TRY(hipMemcpy(p->d_table, p->core->table().data(), bytes, hipMemcpyHostToDevice), "hipMemcpy(table mirror)");
   (void)p->core->take_dirty();   // the full upload covers everything so far
+  HIP_TRY(hipMalloc((void**)&p->d_counters, ellm::N_WORK_COUNTERS * sizeof(int32_t)), "hipMalloc(counters)");
+  HIP_TRY(hipMemset(p->d_counters, 0, ellm::N_WORK_COUNTERS * sizeof(int32_t)), "hipMemset(counters)");
   HIP_TRY(hipStreamCreateWithFlags(&p->side, hipStreamNonBlocking), "hipStreamCreate(side)");
   HIP_TRY(hipEventCreateWithFlags(&p->ev_compute, hipEventDisableTiming), "hipEventCreate");
   HIP_TRY(hipEventCreateWithFlags(&p->ev_migrate, hipEventDisableTiming), "hipEventCreate");
@@ -196,38 +202,53 @@ int32_t wave_slots(ellm_pool* p) {
   return slots;
 }
 
-// The partition of one launch (at most MAX_LAUNCH_REQ requests). All tiles of all (kv head, request)
-// pairs form one sequence; every wave gets the same number of consecutive tiles, chosen so that the
-// whole launch is resident at once. It depends only on the batch's lengths, the pool geometry and
-// the device's wave capacity, never on physical chunk ids, so the partition, and with it every
-// rounding, is reproducible and invariant under remapping.
+// The partition of one launch (at most MAX_LAUNCH_REQ requests): every (request, kv head) pair is
+// cut into pieces of the same number of tiles, one partial result per piece. The piece size depends
+// only on the batch's lengths, the pool geometry and the device's wave capacity, never on physical
+// chunk ids or on which wave runs which piece, so every rounding is reproducible and invariant
+// under remapping. It aims at one piece per resident wave, so that the whole launch is resident at
+// once: measured on MI355X, smaller pieces lose more to their fixed start-up and wrap-up cost
+// than they gain in balance.
 void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0, int64_t ws_slot0, ellm::BatchArgs& a) {
   const int32_t Tc = p->geom.tokens_per_chunk;
   const int32_t tpc = (Tc + ellm::TILE_TOKENS - 1) / ellm::TILE_TOKENS;
-  a.n_req = n_req;
-  a.q_row0 = q_row0;
-  int64_t prefix = 0;
-  int32_t longest = 0;
+  int64_t total_tiles = 0;
+  std::vector<int32_t>& tiles = p->tiles_tmp;
+  tiles.resize(n_req);
   for (int32_t i = 0; i < n_req; i++) {
     const int64_t len = p->core->tensor(ids[i])->len;
     const int64_t full = len / Tc, rem = len - full * Tc;
-    const int64_t tiles = full * tpc + (rem + ellm::TILE_TOKENS - 1) / ellm::TILE_TOKENS;
+    tiles[i] = (int32_t)(full * tpc + (rem + ellm::TILE_TOKENS - 1) / ellm::TILE_TOKENS);
+    total_tiles += tiles[i];
     a.tensor[i] = ids[i];
     a.len[i] = (int32_t)len;
-    a.tile_prefix[i] = (int32_t)prefix;
-    prefix += tiles;
-    longest = std::max<int32_t>(longest, (int32_t)tiles);
   }
-  a.tile_prefix[n_req] = (int32_t)prefix;
-  a.tiles_per_head = (int32_t)prefix;
-  const int64_t total = prefix * p->geom.n_kv_heads;
-  int64_t per_wave;
-  if (p->split_override > 0) per_wave = std::max<int64_t>(1, p->split_override / ellm::TILE_TOKENS);
-  else per_wave = std::max<int64_t>(1, (total + wave_slots(p) - 1) / wave_slots(p));
-  a.tiles_per_wave = (int32_t)per_wave;
-  a.n_waves = (int32_t)((total + per_wave - 1) / per_wave);
-  a.max_partials = (int32_t)((longest + per_wave - 1) / per_wave) + 1;
+  total_tiles *= p->geom.n_kv_heads;
+  const int32_t slots = wave_slots(p);
+  int64_t per_piece;
+  if (p->split_override > 0) per_piece = std::max<int64_t>(1, p->split_override / ellm::TILE_TOKENS);
+  else per_piece = std::max<int64_t>(1, (total_tiles + slots - 1) / slots);
+  int64_t prefix = 0;
+  int32_t most = 0;
+  for (int32_t i = 0; i < n_req; i++) {
+    const int32_t pieces = (int32_t)((tiles[i] + per_piece - 1) / per_piece);
+    a.piece_prefix[i] = (int32_t)prefix;
+    prefix += pieces;
+    most = std::max(most, pieces);
+  }
+  a.piece_prefix[n_req] = (int32_t)prefix;
+  a.n_req = n_req;
+  a.q_row0 = q_row0;
+  a.pieces_per_head = (int32_t)prefix;
+  a.tiles_per_piece = (int32_t)per_piece;
+  a.n_pieces = (int32_t)(prefix * p->geom.n_kv_heads);
+  a.max_partials = most;
   a.ws_slot0 = (int32_t)ws_slot0;
+  const bool persistent = p->schedule == 2;
+  a.persistent = persistent ? 1 : 0;
+  a.n_waves = persistent ? std::min(a.n_pieces, slots) : a.n_pieces;
+  a.n_counters = ellm::partial_launches_per_decode(p->geom.group);
+  a.counter0 = p->next_counter;
   a.pad = 0;
 }
 
@@ -298,6 +319,7 @@ int ellm_pool_destroy(ellm_pool* p) {
     (void)hipEventDestroy(p->ev_compute);
     (void)hipEventDestroy(p->ev_migrate);
     (void)hipFree(p->d_table);
+    (void)hipFree(p->d_counters);
     for (hipEvent_t e : p->prof_ev) (void)hipEventDestroy(e);
     if (p->d_ws) (void)hipFree(p->d_ws);
   }
@@ -382,17 +404,9 @@ int ellm_decode_plan(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, int
   for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
     const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
     plan_launch(p, ids + b0, nb, b0, 0, a);
-    per_wave = std::max(per_wave, a.tiles_per_wave);
+    per_wave = std::max(per_wave, a.tiles_per_piece);
     if (n_split)
-      for (int32_t i = 0; i < nb; i++) {
-        int32_t most = 0;
-        for (int32_t g = 0; g < p->geom.n_kv_heads; g++) {
-          const int64_t f0 = (int64_t)g * a.tiles_per_head + a.tile_prefix[i];
-          const int64_t f1 = (int64_t)g * a.tiles_per_head + a.tile_prefix[i + 1];
-          most = std::max<int32_t>(most, (int32_t)((f1 - 1) / a.tiles_per_wave - f0 / a.tiles_per_wave + 1));
-        }
-        n_split[b0 + i] = most;
-      }
+      for (int32_t i = 0; i < nb; i++) n_split[b0 + i] = a.piece_prefix[i + 1] - a.piece_prefix[i];
   }
   if (split_tokens) *split_tokens = per_wave * ellm::TILE_TOKENS;
   return ELLM_OK;
@@ -427,7 +441,8 @@ int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch
     launches.emplace_back();
     plan_launch(p, ids + b0, nb, b0, ws_slots, launches.back());
     ws_slots += launch_ws_slots(p, launches.back());
-    if ((int64_t)launches.back().tiles_per_head * p->geom.n_kv_heads > 0x7fffffffll || ws_slots > 0x7fffffffll)
+    p->next_counter = (p->next_counter + launches.back().n_counters) % ellm::N_WORK_COUNTERS;
+    if ((int64_t)launches.back().pieces_per_head * p->geom.n_kv_heads > 0x7fffffffll || ws_slots > 0x7fffffffll)
       return set_err(ELLM_ERR_RANGE, "decode_attention: too much work for one call");
   }
   rc = ensure_workspace(p, ws_slots);
@@ -437,13 +452,13 @@ int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch
   for (const ellm::BatchArgs& a : launches) {
     const bool prof = (size_t)(p->prof_used + 1) * 2 <= p->prof_ev.size();
     if (prof) HIP_TRY(hipEventRecord(p->prof_ev[2 * p->prof_used], stream), "hipEventRecord(profile)");
-    int e = ellm::launch_decode_partial(pv, q, p->d_ws, scale_log2, a, stream);
+    int e = ellm::launch_decode_partial(pv, q, p->d_ws, scale_log2, p->d_counters, a, stream);
     if (e) return hip_err((hipError_t)e, "decode partial launch");
     if (prof) {
       HIP_TRY(hipEventRecord(p->prof_ev[2 * p->prof_used + 1], stream), "hipEventRecord(profile)");
       p->prof_used++;
     }
-    e = ellm::launch_decode_combine(pv, p->d_ws, out, a, stream);
+    e = ellm::launch_decode_combine(pv, p->d_ws, out, p->d_counters, a, stream);
     if (e) return hip_err((hipError_t)e, "decode combine launch");
   }
   return ELLM_OK;
@@ -585,9 +600,17 @@ int ellm_debug_kv_stream_read(ellm_pool* p, const ellm_tensor_id* ids, int32_t b
   for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
     const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
     plan_launch(p, ids + b0, nb, b0, 0, a);
-    int e = ellm::launch_kv_stream(pv, (uint32_t*)sink, a, stream);
+    p->next_counter = (p->next_counter + 1) % ellm::N_WORK_COUNTERS;
+    int e = ellm::launch_kv_stream(pv, (uint32_t*)sink, p->d_counters, a, stream);
+    if (!e) e = ellm::launch_reset_counters(p->d_counters, a.counter0, 1, stream);
     if (e) return hip_err((hipError_t)e, "kv stream launch");
   }
+  return ELLM_OK;
+}
+
+int ellm_debug_set_schedule(ellm_pool* p, int schedule) {
+  if (!p || schedule < 0 || schedule > 2) return set_err(ELLM_ERR_INVALID, "set_schedule: bad argument");
+  p->schedule = schedule;
   return ELLM_OK;
 }
 

@@ -145,20 +145,27 @@ __global__ __launch_bounds__(256) void kv_append_kernel(PoolView pv, const uint4
 // ---------------------------------------------------------------------------------------------
 // work partition shared by the partial pass, the combine pass and the calibration kernel
 // ---------------------------------------------------------------------------------------------
-// request b with tile_prefix[b] <= pos < tile_prefix[b + 1] (wave-uniform result)
+// request b with piece_prefix[b] <= pos < piece_prefix[b + 1] (wave-uniform result)
 __device__ __forceinline__ int find_request(const BatchArgs& a, int pos, int lane) {
   int cnt = 0;
   for (int base = 0; base < a.n_req; base += 64) {
     const int i = base + lane;
-    cnt += __popcll(__ballot(i < a.n_req && a.tile_prefix[i] <= pos));
+    cnt += __popcll(__ballot(i < a.n_req && a.piece_prefix[i] <= pos));
   }
   return __builtin_amdgcn_readfirstlane(cnt - 1);
 }
 
+// number of tiles of a sequence of len tokens (a tile never straddles a chunk)
+__device__ __forceinline__ int32_t tiles_of(int32_t len, int32_t Tc, int32_t tiles_per_chunk) {
+  const int32_t full = len / Tc, rest = len - full * Tc;
+  return full * tiles_per_chunk + (rest + TILE_TOKENS - 1) / TILE_TOKENS;
+}
+
 // ---------------------------------------------------------------------------------------------
-// decode attention, partial pass (split-K): one wave per equal share of the launch's tiles
+// decode attention, partial pass (split-K): one wave per piece of a (request, kv head) pair
 //
-// A tile is up to 64 consecutive rows of one chunk of one (request, kv head). Per tile:
+// A tile is up to 64 consecutive rows of one chunk of one (request, kv head); a piece is a few
+// consecutive tiles. Per tile:
 //   K  64 rows are fetched with coalesced 128-bit loads (LPR = D/8 lanes per row) that write straight
 //      into LDS (no staging registers), then read back transposed: lane t owns token t and reads
 //      its whole row, so a score needs no cross-lane reduction. The query values of the G heads of
@@ -166,7 +173,7 @@ __device__ __forceinline__ int find_request(const BatchArgs& a, int pos, int lan
 //      register; v_dot2_f32_bf16 with a DPP row broadcast multiplies two pairs per lane-op.
 //   softmax  one score per lane and head; the tile maximum is a wave reduction; weights are
 //      rounded to bf16 (the running sum l uses the rounded weights, so they still sum to one)
-//      and handed to the PV layout through LDS.
+//      and handed to the PV layout by cross-lane reads.
 //   V  is consumed straight from registers in the load layout (lane = 8 dims of one row, RPW rows
 //      per wave-wide load): rows of two consecutive loads are interleaved with v_perm_b32 so that
 //      one v_dot2_f32_bf16 adds two tokens' contributions to a dim.
@@ -174,31 +181,21 @@ __device__ __forceinline__ int find_request(const BatchArgs& a, int pos, int lan
 // Scores are kept in log2 units (scale_log2 = scale * log2 e).
 // ---------------------------------------------------------------------------------------------
 template <int D, int G>
-__global__ __launch_bounds__(64) void decode_partial_kernel(PoolView pv, const uint16_t* __restrict__ q,
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_partial_kernel(PoolView pv, const uint16_t* __restrict__ q,
                                                             float* __restrict__ ws, float scale_log2,
-                                                            int32_t g_first, BatchArgs a) {
+                                                            int32_t g_first, int32_t* __restrict__ counter,
+                                                            BatchArgs a) {
   constexpr int LPR = D / 8;             // lanes per row = 16-byte pieces per row
   constexpr int RPW = 64 / LPR;          // rows per wave-wide load
   constexpr int NL = 64 / RPW;           // wave-wide loads per 64-row tile and plane
   constexpr int ROWB = D * 2;            // bytes per row
   constexpr int QR = D / 32;             // registers holding one head's query (16 lanes x 1 pair each)
-  constexpr int K_OFF = 0;               // one LDS buffer: K tile | weights
-  constexpr int P_OFF = 64 * ROWB;
-  __shared__ __attribute__((aligned(16))) char smem[P_OFF + G * 64 * 2];
+  __shared__ __attribute__((aligned(16))) char sm_k[64 * ROWB];      // the K tile being scored
 
   const int lane = threadIdx.x;
   const int sub = lane % LPR, rg = lane / LPR;
-  const int w = blockIdx.x;
   const int32_t Tc = pv.tokens_per_chunk;
-  const int32_t TT = a.tiles_per_head;
   const uint64_t plane = (uint64_t)Tc * ROWB;        // V plane follows the K plane of the same head
-
-  int32_t pos = w * a.tiles_per_wave;                                  // position in the tile sequence
-  const int32_t pos_end = min(TT * pv.n_kv_heads, pos + a.tiles_per_wave);
-  if (pos >= pos_end) return;
-  int32_t g = pos / TT;                                                 // kv head
-  int32_t rem = pos - g * TT;
-  int32_t b = find_request(a, rem, lane);
 
   // Tile loads. Lane (rg, sub) handles piece `sub` of tile rows RPW*u + rg, u = 0 .. NL-1. Rows past
   // nv are replaced by row nv - 1, so every load is in bounds and returns finite data; those
@@ -213,23 +210,100 @@ __global__ __launch_bounds__(64) void decode_partial_kernel(PoolView pv, const u
     const uint32_t off_ = (uint32_t)min(RPW * u + rg, (nvalid) - 1) * ROWB +                        \
                           (uint32_t)((sx ^ ((RPW * u) % LPR)) * 16);                                \
     __builtin_amdgcn_global_load_lds((global_cptr_t)((base) + off_),                                \
-                                     (lds_ptr_t)(smem + K_OFF + u * (RPW * ROWB)), 16, 0, 0);       \
+                                     (lds_ptr_t)(sm_k + u * (RPW * ROWB)), 16, 0, 0);               \
   }
-#define ELLM_LOAD_V_TILE(dst, base, nvalid)                                                         \
+#define ELLM_LOAD_TILE(dst, base, nvalid)                                                           \
   _Pragma("unroll") for (int u = 0; u < NL; u++) {                                                  \
     const uint32_t off_ = (uint32_t)min(RPW * u + rg, (nvalid) - 1) * ROWB + sub * 16;              \
     dst[u] = *reinterpret_cast<const uint4*>((base) + off_);                                        \
   }
+// move the cursor (slot, r) to the next tile and compute its address and valid rows
+#define ELLM_NEXT_TILE()                                                                            \
+  r += TILE_TOKENS;                                                                                 \
+  if (r >= Tc) { r = 0; slot += 1; }                                                                \
+  nv_next = min(TILE_TOKENS, min(Tc - r, len - (slot * Tc + r)));                                   \
+  kb = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + ((uint64_t)(g * 2) * Tc + r) * ROWB;
+// scores of one tile (lane = token) and online softmax: leaves the tile's weights, rounded to bf16,
+// in pu[] (one per head, for this lane's token). Consecutive dot products go to different heads'
+// accumulators, so no instruction waits for the one before it.
+#define ELLM_TILE_SCORES(nvalid)                                                                    \
+  float s[G];                                                                                       \
+  uint32_t pu[G];                                                                                   \
+  {                                                                                                 \
+    _Pragma("unroll") for (int i = 0; i < G; i++) s[i] = 0.f;                                       \
+    static_for<0, LPR>([&](auto jc) {                                                               \
+      constexpr int j = decltype(jc)::value;                                                        \
+      const uint4 kp = *reinterpret_cast<const uint4*>(sm_k + lane * ROWB + ((j ^ kswz) * 16));     \
+      _Pragma("unroll") for (int i = 0; i < G; i++)                                                 \
+        s[i] = dot2_bf16_rowlane<4 * (j % 4) + 0>(qreg[i][j / 4], kp.x, s[i]);                      \
+      _Pragma("unroll") for (int i = 0; i < G; i++)                                                 \
+        s[i] = dot2_bf16_rowlane<4 * (j % 4) + 1>(qreg[i][j / 4], kp.y, s[i]);                      \
+      _Pragma("unroll") for (int i = 0; i < G; i++)                                                 \
+        s[i] = dot2_bf16_rowlane<4 * (j % 4) + 2>(qreg[i][j / 4], kp.z, s[i]);                      \
+      _Pragma("unroll") for (int i = 0; i < G; i++)                                                 \
+        s[i] = dot2_bf16_rowlane<4 * (j % 4) + 3>(qreg[i][j / 4], kp.w, s[i]);                      \
+    });                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < G; i++) settle(s[i]);                                     \
+    _Pragma("unroll") for (int i = 0; i < G; i++) {                                                 \
+      const float sc = lane < (nvalid) ? s[i] * scale_log2 : -INFINITY;                             \
+      const float mn = fmaxf(m[i], wave_max(sc));                                                   \
+      const float alpha = fast_exp2(m[i] - mn);                                                     \
+      m[i] = mn;                                                                                    \
+      pu[i] = __float_as_uint(fast_exp2(sc - mn));                                                  \
+      pu[i] = (pu[i] + 0x7fffu + ((pu[i] >> 16) & 1u)) & 0xffff0000u; /* nearest even */            \
+      l[i] = l[i] * alpha + __uint_as_float(pu[i]);                                                 \
+      _Pragma("unroll") for (int e = 0; e < 8; e++) acc[i][e] *= alpha;                             \
+    }                                                                                               \
+  }
+// weighted V: the PV lane (rg, sub) fetches the weights of its rows RPW*u + rg from the lanes that
+// own those tokens (a cross-lane read, no LDS memory), packs two of them into one register, and
+// adds two tokens per dot2
+#define ELLM_TILE_PV(VR)                                                                            \
+  _Pragma("unroll") for (int i = 0; i < G; i++) {                                                   \
+    uint32_t pp[NL / 2];                                                                            \
+    _Pragma("unroll") for (int v = 0; v < NL / 2; v++) {                                            \
+      const uint32_t pa = __builtin_amdgcn_ds_bpermute((RPW * (2 * v) + rg) * 4, pu[i]);            \
+      const uint32_t pb = __builtin_amdgcn_ds_bpermute((RPW * (2 * v + 1) + rg) * 4, pu[i]);        \
+      pp[v] = __builtin_amdgcn_perm(pb, pa, 0x07060302u);                                           \
+    }                                                                                               \
+    _Pragma("unroll") for (int v = 0; v < NL / 2; v++) {                                            \
+      const uint4 A = VR[2 * v], Bv = VR[2 * v + 1];                                                \
+      acc[i][0] = dot2_bf16(__builtin_amdgcn_perm(Bv.x, A.x, 0x05040100u), pp[v], acc[i][0]);       \
+      acc[i][1] = dot2_bf16(__builtin_amdgcn_perm(Bv.x, A.x, 0x07060302u), pp[v], acc[i][1]);       \
+      acc[i][2] = dot2_bf16(__builtin_amdgcn_perm(Bv.y, A.y, 0x05040100u), pp[v], acc[i][2]);       \
+      acc[i][3] = dot2_bf16(__builtin_amdgcn_perm(Bv.y, A.y, 0x07060302u), pp[v], acc[i][3]);       \
+      acc[i][4] = dot2_bf16(__builtin_amdgcn_perm(Bv.z, A.z, 0x05040100u), pp[v], acc[i][4]);       \
+      acc[i][5] = dot2_bf16(__builtin_amdgcn_perm(Bv.z, A.z, 0x07060302u), pp[v], acc[i][5]);       \
+      acc[i][6] = dot2_bf16(__builtin_amdgcn_perm(Bv.w, A.w, 0x05040100u), pp[v], acc[i][6]);       \
+      acc[i][7] = dot2_bf16(__builtin_amdgcn_perm(Bv.w, A.w, 0x07060302u), pp[v], acc[i][7]);       \
+    }                                                                                               \
+  }
 
-  while (pos < pos_end) {
-    // ---- one piece: tiles [tile0, tile0 + n_tiles) of request b, kv head g ----------------------
-    const int32_t tile0 = rem - a.tile_prefix[b];
-    const int32_t tiles_b = a.tile_prefix[b + 1] - a.tile_prefix[b];
-    const int32_t n_tiles = min(tiles_b - tile0, pos_end - pos);
+  for (int32_t piece = blockIdx.x;;) {
+    // ---- which piece: one per wave, or the next one from the shared counter --------------------
+    if (a.persistent) {
+      int32_t next = 0;
+      if (lane == 0) next = atomicAdd(counter, 1);
+      piece = __builtin_amdgcn_readfirstlane(next);
+    }
+    if (piece >= a.n_pieces) break;
+    const int32_t g = piece / a.pieces_per_head;                       // kv head
+    const int32_t rem = piece - g * a.pieces_per_head;
+    const int32_t b = find_request(a, rem, lane);
+    const int32_t j = rem - a.piece_prefix[b];                         // piece number within the pair
     const int32_t len = a.len[b];
+    const int32_t tile0 = j * a.tiles_per_piece;
+    const int32_t n_tiles = min(a.tiles_per_piece, tiles_of(len, Tc, pv.tiles_per_chunk) - tile0);
     const int hq0 = g * pv.group + g_first;            // first q head handled here
     // the table row is read-only for the kernel's lifetime: uniform (scalar) loads
     const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)a.tensor[b] * pv.max_slots);
+
+    // first tile: cursor -> (slot, first row, valid rows); its K and V are requested at once
+    int32_t slot = tile0 / pv.tiles_per_chunk;
+    int32_t r = (tile0 - slot * pv.tiles_per_chunk) * TILE_TOKENS;
+    int32_t nv = min(TILE_TOKENS, min(Tc - r, len - (slot * Tc + r))), nv_next = nv;
+    const char* kb = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + ((uint64_t)(g * 2) * Tc + r) * ROWB;
+    ELLM_LOAD_K_TILE(kb, nv)
 
     // query: lane keeps pair (16 c + lane % 16) of each head in qreg[.][c]
     uint32_t qreg[G][QR];
@@ -239,10 +313,6 @@ __global__ __launch_bounds__(64) void decode_partial_kernel(PoolView pv, const u
       for (int i = 0; i < G; i++)
 #pragma unroll
         for (int c = 0; c < QR; c++) qreg[i][c] = qsrc[i * (D / 2) + c * 16 + (lane & 15)];
-#pragma unroll
-      for (int i = 0; i < G; i++)
-#pragma unroll
-        for (int c = 0; c < QR; c++) settle(qreg[i][c]);
     }
 
     float m[G], l[G], acc[G][8];
@@ -252,13 +322,7 @@ __global__ __launch_bounds__(64) void decode_partial_kernel(PoolView pv, const u
 #pragma unroll
       for (int e = 0; e < 8; e++) acc[i][e] = 0.f;
     }
-
-    // cursor: tile index -> (slot, first row, valid rows)
-    int32_t slot = tile0 / pv.tiles_per_chunk;
-    int32_t r = (tile0 - slot * pv.tiles_per_chunk) * TILE_TOKENS;
-    int32_t nv = min(TILE_TOKENS, min(Tc - r, len - (slot * Tc + r)));
-    const char* kb = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + ((uint64_t)(g * 2) * Tc + r) * ROWB;
-    ELLM_LOAD_K_TILE(kb, nv)
+    bool q_settled = false;
 
     for (int32_t it = 0; it < n_tiles; it++) {
       // the K tile is the only load outstanding here: wait until it has landed in LDS, then start
@@ -266,74 +330,25 @@ __global__ __launch_bounds__(64) void decode_partial_kernel(PoolView pv, const u
       __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
       __builtin_amdgcn_wave_barrier();
       uint4 vr[NL];
-      ELLM_LOAD_V_TILE(vr, kb + plane, nv)
-
-      // scores: lane = token
-      float s[G];
+      ELLM_LOAD_TILE(vr, kb + plane, nv)
+      if (!q_settled) {
 #pragma unroll
-      for (int i = 0; i < G; i++) s[i] = 0.f;
-      static_for<0, LPR>([&](auto jc) {
-        constexpr int j = decltype(jc)::value;
-        const uint4 kp = *reinterpret_cast<const uint4*>(smem + K_OFF + lane * ROWB + ((j ^ kswz) * 16));
+        for (int i = 0; i < G; i++)
 #pragma unroll
-        for (int i = 0; i < G; i++) {
-          s[i] = dot2_bf16_rowlane<4 * (j % 4) + 0>(qreg[i][j / 4], kp.x, s[i]);
-          s[i] = dot2_bf16_rowlane<4 * (j % 4) + 1>(qreg[i][j / 4], kp.y, s[i]);
-          s[i] = dot2_bf16_rowlane<4 * (j % 4) + 2>(qreg[i][j / 4], kp.z, s[i]);
-          s[i] = dot2_bf16_rowlane<4 * (j % 4) + 3>(qreg[i][j / 4], kp.w, s[i]);
-        }
-      });
-#pragma unroll
-      for (int i = 0; i < G; i++) settle(s[i]);
-      // online softmax over the tile; weights go to LDS as bf16 in the order the PV lanes read them
-      const int pidx = (lane % RPW) * NL + lane / RPW;
-#pragma unroll
-      for (int i = 0; i < G; i++) {
-        const float sc = lane < nv ? s[i] * scale_log2 : -INFINITY;
-        const float mn = fmaxf(m[i], wave_max(sc));
-        const float alpha = fast_exp2(m[i] - mn);
-        m[i] = mn;
-        uint32_t pu = __float_as_uint(fast_exp2(sc - mn));
-        pu = (pu + 0x7fffu + ((pu >> 16) & 1u)) & 0xffff0000u;      // round to bf16, nearest even
-        l[i] = l[i] * alpha + __uint_as_float(pu);
-        *reinterpret_cast<uint16_t*>(smem + P_OFF + (i * 64 + pidx) * 2) = (uint16_t)(pu >> 16);
-#pragma unroll
-        for (int e = 0; e < 8; e++) acc[i][e] *= alpha;
+          for (int c = 0; c < QR; c++) settle(qreg[i][c]);
+        q_settled = true;
       }
-      __builtin_amdgcn_wave_barrier();
-
-      // the K tile has been consumed: fetch the next one while V is multiplied
+      ELLM_TILE_SCORES(nv)
+      // V of this tile must have arrived now (it is the only load outstanding); then the K tile,
+      // which has been consumed, is replaced by the next one while V is multiplied
+      __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
       if (it + 1 < n_tiles) {
-        r += TILE_TOKENS;
-        if (r >= Tc) { r = 0; slot += 1; }
-        nv = min(TILE_TOKENS, min(Tc - r, len - (slot * Tc + r)));
-        kb = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + ((uint64_t)(g * 2) * Tc + r) * ROWB;
+        ELLM_NEXT_TILE()
+        nv = nv_next;
         ELLM_LOAD_K_TILE(kb, nv)
       }
-      __builtin_amdgcn_wave_barrier();
-
-      // weighted V: two tokens per dot2
-#pragma unroll
-      for (int i = 0; i < G; i++) {
-        uint32_t pp[NL / 2];
-#pragma unroll
-        for (int x = 0; x < NL / 8; x++) {
-          const uint4 t4 = *reinterpret_cast<const uint4*>(smem + P_OFF + (i * 64 + rg * NL + x * 8) * 2);
-          pp[x * 4 + 0] = t4.x; pp[x * 4 + 1] = t4.y; pp[x * 4 + 2] = t4.z; pp[x * 4 + 3] = t4.w;
-        }
-#pragma unroll
-        for (int v = 0; v < NL / 2; v++) {
-          const uint4 A = vr[2 * v], Bv = vr[2 * v + 1];
-          acc[i][0] = dot2_bf16(__builtin_amdgcn_perm(Bv.x, A.x, 0x05040100u), pp[v], acc[i][0]);
-          acc[i][1] = dot2_bf16(__builtin_amdgcn_perm(Bv.x, A.x, 0x07060302u), pp[v], acc[i][1]);
-          acc[i][2] = dot2_bf16(__builtin_amdgcn_perm(Bv.y, A.y, 0x05040100u), pp[v], acc[i][2]);
-          acc[i][3] = dot2_bf16(__builtin_amdgcn_perm(Bv.y, A.y, 0x07060302u), pp[v], acc[i][3]);
-          acc[i][4] = dot2_bf16(__builtin_amdgcn_perm(Bv.z, A.z, 0x05040100u), pp[v], acc[i][4]);
-          acc[i][5] = dot2_bf16(__builtin_amdgcn_perm(Bv.z, A.z, 0x07060302u), pp[v], acc[i][5]);
-          acc[i][6] = dot2_bf16(__builtin_amdgcn_perm(Bv.w, A.w, 0x05040100u), pp[v], acc[i][6]);
-          acc[i][7] = dot2_bf16(__builtin_amdgcn_perm(Bv.w, A.w, 0x07060302u), pp[v], acc[i][7]);
-        }
-      }
+      __builtin_amdgcn_sched_barrier(0);
+      ELLM_TILE_PV(vr)
     }
 
     // every row-group holds the same dims for different tokens under one common maximum: add them up
@@ -346,10 +361,9 @@ __global__ __launch_bounds__(64) void decode_partial_kernel(PoolView pv, const u
       }
       l[i] = wave_sum(l[i]);
     }
-    // partial number (w - first wave of this pair) of pair (b, g): [q head][D accumulators, m, l, 2 unused]
-    const int32_t w_first = (g * TT + a.tile_prefix[b]) / a.tiles_per_wave;
-    float* wout = ws + (((int64_t)a.ws_slot0 + (int64_t)(b * pv.n_kv_heads + g) * a.max_partials + (w - w_first)) * pv.group +
-                        g_first) * (D + WS_ROW_PAD);
+    // partial j of pair (b, g): [q head][D accumulators, m, l, 2 unused]
+    float* wout = ws + ((a.ws_slot0 + (int64_t)(b * pv.n_kv_heads + g) * a.max_partials + j) * pv.group + g_first) *
+                           (D + WS_ROW_PAD);
     if (rg == 0) {
 #pragma unroll
       for (int i = 0; i < G; i++) {
@@ -359,16 +373,14 @@ __global__ __launch_bounds__(64) void decode_partial_kernel(PoolView pv, const u
         if (sub == 0) { wout[i * (D + WS_ROW_PAD) + D] = m[i]; wout[i * (D + WS_ROW_PAD) + D + 1] = l[i]; }
       }
     }
-
-    // next piece: same kv head, next request; or next kv head from its first request
-    pos += n_tiles;
-    rem += n_tiles;
-    if (rem == TT) { rem = 0; g += 1; b = 0; }
-    else if (tile0 + n_tiles == tiles_b) b += 1;
+    if (!a.persistent) break;
     __builtin_amdgcn_wave_barrier();
   }
+#undef ELLM_LOAD_TILE
 #undef ELLM_LOAD_K_TILE
-#undef ELLM_LOAD_V_TILE
+#undef ELLM_NEXT_TILE
+#undef ELLM_TILE_SCORES
+#undef ELLM_TILE_PV
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -377,17 +389,17 @@ __global__ __launch_bounds__(64) void decode_partial_kernel(PoolView pv, const u
 template <int D>
 __global__ __launch_bounds__(D) void decode_combine_kernel(const float* __restrict__ ws, uint16_t* __restrict__ out,
                                                            int32_t n_q_heads, int32_t n_kv_heads, int32_t group,
-                                                           BatchArgs a) {
+                                                           int32_t* __restrict__ counters, BatchArgs a) {
   const int b = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
+  // the partial pass is over: put its piece counters back to zero for their next use
+  if (b == 0 && h == 0 && d < a.n_counters) counters[(a.counter0 + d) % N_WORK_COUNTERS] = 0;
   const int g = h / group;
-  const int f0 = g * a.tiles_per_head + a.tile_prefix[b];
-  const int f1 = g * a.tiles_per_head + a.tile_prefix[b + 1];
-  const int w0 = f0 / a.tiles_per_wave, w1 = (f1 - 1) / a.tiles_per_wave;
+  const int n_part = a.piece_prefix[b + 1] - a.piece_prefix[b];
   const float* p = ws + ((a.ws_slot0 + (int64_t)(b * n_kv_heads + g) * a.max_partials) * group + (h - g * group)) *
                             (D + WS_ROW_PAD);
   const int64_t stride = (int64_t)group * (D + WS_ROW_PAD);
   float M = NEG_BIG, L = 0.f, A = 0.f;
-  for (int j = 0; j <= w1 - w0; j++, p += stride) {
+  for (int j = 0; j < n_part; j++, p += stride) {
     const float mj = p[D], lj = p[D + 1], aj = p[d];
     const float mn = fmaxf(M, mj);
     const float c0 = fast_exp2(M - mn), c1 = fast_exp2(mj - mn);
@@ -430,23 +442,27 @@ __global__ __launch_bounds__(256) void read_kernel(const uint4* __restrict__ src
 // the K/V rows a decode over this batch reads, with the same work partition and load shape (one
 // wave per equal share of tiles, 64-row tiles, 128-bit loads), but no arithmetic
 template <int D>
-__global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __restrict__ sink, BatchArgs a) {
+__global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __restrict__ sink,
+                                                       int32_t* __restrict__ counter, BatchArgs a) {
   constexpr int LPR = D / 8, RPW = 64 / LPR, NL = 64 / RPW, ROWB = D * 2;
   const int lane = threadIdx.x;
   const int sub = lane % LPR, rg = lane / LPR;
-  const int w = blockIdx.x;
-  const int32_t Tc = pv.tokens_per_chunk, TT = a.tiles_per_head;
-  int32_t pos = w * a.tiles_per_wave;
-  const int32_t pos_end = min(TT * pv.n_kv_heads, pos + a.tiles_per_wave);
-  if (pos >= pos_end) return;
-  int32_t g = pos / TT, rem = pos - g * TT;
-  int32_t b = find_request(a, rem, lane);
+  const int32_t Tc = pv.tokens_per_chunk;
   uint32_t x = 0;
-  while (pos < pos_end) {
-    const int32_t tile0 = rem - a.tile_prefix[b];
-    const int32_t tiles_b = a.tile_prefix[b + 1] - a.tile_prefix[b];
-    const int32_t n_tiles = min(tiles_b - tile0, pos_end - pos);
+  for (int32_t piece = blockIdx.x;;) {
+    if (a.persistent) {
+      int32_t next = 0;
+      if (lane == 0) next = atomicAdd(counter, 1);
+      piece = __builtin_amdgcn_readfirstlane(next);
+    }
+    if (piece >= a.n_pieces) break;
+    const int32_t g = piece / a.pieces_per_head;
+    const int32_t rem = piece - g * a.pieces_per_head;
+    const int32_t b = find_request(a, rem, lane);
+    const int32_t j = rem - a.piece_prefix[b];
     const int32_t len = a.len[b];
+    const int32_t tile0 = j * a.tiles_per_piece;
+    const int32_t n_tiles = min(a.tiles_per_piece, tiles_of(len, Tc, pv.tiles_per_chunk) - tile0);
     const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)a.tensor[b] * pv.max_slots);
     int32_t slot = tile0 / pv.tiles_per_chunk;
     int32_t r = (tile0 - slot * pv.tiles_per_chunk) * TILE_TOKENS;
@@ -466,10 +482,7 @@ __global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __
       r += TILE_TOKENS;
       if (r >= Tc) { r = 0; slot += 1; }
     }
-    pos += n_tiles;
-    rem += n_tiles;
-    if (rem == TT) { rem = 0; g += 1; b = 0; }
-    else if (tile0 + n_tiles == tiles_b) b += 1;
+    if (!a.persistent) break;
   }
   if (x == 0x9e3779b9u) sink[0] = x;
 }
@@ -531,43 +544,52 @@ int partial_waves_per_cu(int head_dim, int group) {
 
 template <int D, int G>
 static void launch_partial_t(const PoolView& pv, const void* q, float* ws, float scale_log2, int32_t g_first,
-                             const BatchArgs& a, hipStream_t stream) {
+                             int32_t* counter, const BatchArgs& a, hipStream_t stream) {
   hipLaunchKernelGGL((decode_partial_kernel<D, G>), dim3(a.n_waves), dim3(64), 0, stream, pv,
-                     (const uint16_t*)q, ws, scale_log2, g_first, a);
+                     (const uint16_t*)q, ws, scale_log2, g_first, counter, a);
+}
+
+// a group size that is not 8, 4, 2 or 1 is covered by several launches over the same K/V
+int partial_launches_per_decode(int group) {
+  int n = 0;
+  for (int done = 0; done < group; done += group_step(group - done)) n++;
+  return n;
 }
 
 template <int D>
-static int launch_partial_d(const PoolView& pv, const void* q, float* ws, float scale_log2, const BatchArgs& a,
-                            hipStream_t stream) {
-  // a group size that is not 8, 4, 2 or 1 is covered by several launches over the same K/V
-  int done = 0;
+static int launch_partial_d(const PoolView& pv, const void* q, float* ws, float scale_log2, int32_t* counters,
+                            const BatchArgs& a, hipStream_t stream) {
+  int done = 0, k = 0;
   while (done < pv.group) {
     const int step = group_step(pv.group - done);
-    if (step == 8) launch_partial_t<D, 8>(pv, q, ws, scale_log2, done, a, stream);
-    else if (step == 4) launch_partial_t<D, 4>(pv, q, ws, scale_log2, done, a, stream);
-    else if (step == 2) launch_partial_t<D, 2>(pv, q, ws, scale_log2, done, a, stream);
-    else launch_partial_t<D, 1>(pv, q, ws, scale_log2, done, a, stream);
+    int32_t* counter = counters + (a.counter0 + k) % N_WORK_COUNTERS;
+    if (step == 8) launch_partial_t<D, 8>(pv, q, ws, scale_log2, done, counter, a, stream);
+    else if (step == 4) launch_partial_t<D, 4>(pv, q, ws, scale_log2, done, counter, a, stream);
+    else if (step == 2) launch_partial_t<D, 2>(pv, q, ws, scale_log2, done, counter, a, stream);
+    else launch_partial_t<D, 1>(pv, q, ws, scale_log2, done, counter, a, stream);
     ELLM_HIP_CHECK_LAUNCH();
     done += step;
+    k++;
   }
   return 0;
 }
 
-int launch_decode_partial(const PoolView& pv, const void* q, float* ws, float scale_log2, const BatchArgs& a,
-                          hipStream_t stream) {
+int launch_decode_partial(const PoolView& pv, const void* q, float* ws, float scale_log2, int32_t* counters,
+                          const BatchArgs& a, hipStream_t stream) {
   if (a.n_req <= 0 || a.n_waves <= 0) return 0;
-  return pv.head_dim == 128 ? launch_partial_d<128>(pv, q, ws, scale_log2, a, stream)
-                            : launch_partial_d<64>(pv, q, ws, scale_log2, a, stream);
+  return pv.head_dim == 128 ? launch_partial_d<128>(pv, q, ws, scale_log2, counters, a, stream)
+                            : launch_partial_d<64>(pv, q, ws, scale_log2, counters, a, stream);
 }
 
-int launch_decode_combine(const PoolView& pv, const float* ws, void* out, const BatchArgs& a, hipStream_t stream) {
+int launch_decode_combine(const PoolView& pv, const float* ws, void* out, int32_t* counters, const BatchArgs& a,
+                          hipStream_t stream) {
   if (a.n_req <= 0) return 0;
   if (pv.head_dim == 128)
     hipLaunchKernelGGL(decode_combine_kernel<128>, dim3(a.n_req, pv.n_q_heads), dim3(128), 0, stream, ws,
-                       (uint16_t*)out, pv.n_q_heads, pv.n_kv_heads, pv.group, a);
+                       (uint16_t*)out, pv.n_q_heads, pv.n_kv_heads, pv.group, counters, a);
   else
     hipLaunchKernelGGL(decode_combine_kernel<64>, dim3(a.n_req, pv.n_q_heads), dim3(64), 0, stream, ws,
-                       (uint16_t*)out, pv.n_q_heads, pv.n_kv_heads, pv.group, a);
+                       (uint16_t*)out, pv.n_q_heads, pv.n_kv_heads, pv.group, counters, a);
   ELLM_HIP_CHECK_LAUNCH();
   return 0;
 }
@@ -590,12 +612,23 @@ int launch_read(const void* src, int64_t bytes, uint32_t* sink, hipStream_t stre
   return 0;
 }
 
-int launch_kv_stream(const PoolView& pv, uint32_t* sink, const BatchArgs& a, hipStream_t stream) {
+int launch_kv_stream(const PoolView& pv, uint32_t* sink, int32_t* counters, const BatchArgs& a, hipStream_t stream) {
   if (a.n_req <= 0 || a.n_waves <= 0) return 0;
+  int32_t* counter = counters + a.counter0 % N_WORK_COUNTERS;
   if (pv.head_dim == 128)
-    hipLaunchKernelGGL(kv_stream_kernel<128>, dim3(a.n_waves), dim3(64), 0, stream, pv, sink, a);
+    hipLaunchKernelGGL(kv_stream_kernel<128>, dim3(a.n_waves), dim3(64), 0, stream, pv, sink, counter, a);
   else
-    hipLaunchKernelGGL(kv_stream_kernel<64>, dim3(a.n_waves), dim3(64), 0, stream, pv, sink, a);
+    hipLaunchKernelGGL(kv_stream_kernel<64>, dim3(a.n_waves), dim3(64), 0, stream, pv, sink, counter, a);
+  ELLM_HIP_CHECK_LAUNCH();
+  return 0;
+}
+
+// counters[first .. first + n) = 0 (the calibration kernel has no combine pass to do it)
+__global__ void reset_counters_kernel(int32_t* counters, int first, int n) {
+  if ((int)threadIdx.x < n) counters[(first + threadIdx.x) % N_WORK_COUNTERS] = 0;
+}
+int launch_reset_counters(int32_t* counters, int first, int n, hipStream_t stream) {
+  hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, stream, counters, first, n);
   ELLM_HIP_CHECK_LAUNCH();
   return 0;
 }

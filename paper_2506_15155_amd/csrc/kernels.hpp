@@ -23,25 +23,32 @@ struct PoolView {
 };
 
 // One decode launch: requests [q_row0, q_row0 + n_req) of the caller's batch.
-// The tiles of all (kv head, request) pairs are laid out in one sequence, kv head major:
-//   position = g * tiles_per_head + tile_prefix[b] + tile.
-// Wave w of the partial pass handles positions [w * tiles_per_wave, (w + 1) * tiles_per_wave), so every
-// wave gets the same number of tiles whatever the mix of lengths; where its range crosses from one
-// (request, kv head) to the next it writes one partial per piece. The partial of wave w for
-// (b, g) is number w - first_wave(b, g) of that pair.
+// The tiles of every (request, kv head) pair are cut into pieces of tiles_per_piece tiles (the last
+// piece of a request may be shorter). All pieces form one sequence, kv head major:
+//   piece index = g * pieces_per_head + piece_prefix[b] + j.
+// Each piece is handled by one wave and yields one partial result, stored in slot j of its pair.
+// Waves take pieces either one per wave (grid = number of pieces) or, when `persistent` is set, from
+// a shared counter until none is left (grid = resident waves): the cut into pieces is fixed either
+// way, so results do not depend on which wave ran which piece.
 struct BatchArgs {
   int32_t n_req;
   int32_t q_row0;             // row of the first request in q / out
-  int32_t tiles_per_head;     // = tile_prefix[n_req]
-  int32_t tiles_per_wave;
-  int32_t n_waves;            // ceil(tiles_per_head * n_kv_heads / tiles_per_wave)
-  int32_t max_partials;       // partial slots per (request, kv head)
+  int32_t pieces_per_head;    // = piece_prefix[n_req]
+  int32_t tiles_per_piece;
+  int32_t n_pieces;           // pieces_per_head * n_kv_heads
+  int32_t max_partials;       // partial slots per (request, kv head) = most pieces any request has
   int32_t ws_slot0;           // first partial slot of this launch in the workspace
+  int32_t n_waves;            // grid size of the partial pass
+  int32_t persistent;         // waves loop over a shared piece counter
+  int32_t counter0;           // first work counter used by this launch's partial pass(es)
+  int32_t n_counters;         // how many it uses (one per partial-pass launch)
   int32_t pad;
   int32_t tensor[MAX_LAUNCH_REQ];
   int32_t len[MAX_LAUNCH_REQ];
-  int32_t tile_prefix[MAX_LAUNCH_REQ + 1];
+  int32_t piece_prefix[MAX_LAUNCH_REQ + 1];
 };
+
+constexpr int N_WORK_COUNTERS = 256;   // ring of piece counters in device memory
 
 struct AppendArgs {
   int32_t n_req, total_new;
@@ -63,13 +70,16 @@ int partial_waves_per_cu(int head_dim, int group);
 int launch_table_patch(int32_t* table, const PatchArgs& a, hipStream_t stream);
 int launch_kv_append(const PoolView& pv, const void* k_new, const void* v_new, const AppendArgs& a,
                      hipStream_t stream);
-int launch_decode_partial(const PoolView& pv, const void* q, float* ws, float scale_log2, const BatchArgs& a,
+int launch_decode_partial(const PoolView& pv, const void* q, float* ws, float scale_log2, int32_t* counters,
+                          const BatchArgs& a, hipStream_t stream);
+int launch_decode_combine(const PoolView& pv, const float* ws, void* out, int32_t* counters, const BatchArgs& a,
                           hipStream_t stream);
-int launch_decode_combine(const PoolView& pv, const float* ws, void* out, const BatchArgs& a, hipStream_t stream);
+int partial_launches_per_decode(int group);
 
 // calibration (measurement only)
 int launch_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream);
 int launch_read(const void* src, int64_t bytes, uint32_t* sink, hipStream_t stream);
-int launch_kv_stream(const PoolView& pv, uint32_t* sink, const BatchArgs& a, hipStream_t stream);
+int launch_kv_stream(const PoolView& pv, uint32_t* sink, int32_t* counters, const BatchArgs& a, hipStream_t stream);
+int launch_reset_counters(int32_t* counters, int first, int n, hipStream_t stream);
 
 }  // namespace ellm
