@@ -24,6 +24,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, public specification
+COPY_CALIBRATION_BYTES = 1 << 30
 
 
 def parse():
@@ -36,6 +37,7 @@ def parse():
     ap.add_argument("--split", type=int, default=0, help="override tokens per work item (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the measured read ceilings")
     ap.add_argument("--migration", action="store_true", help="also time offload / fetch of 25%% of the requests")
     return ap.parse_args()
 
@@ -173,6 +175,12 @@ def main():
                     "avg_launch_us": round(avg * 1e3, 2), "launches": int(len(kern_ms)),
                     "algorithmic_bytes_per_launch": int(partial_bytes)}
 
+    if roofline is not None and not args.no_ceilings:
+        roofline.update(read_ceilings(E, torch, pool, dev, ids, partial_bytes, ab["kv"]))
+        roofline["frac_of_measured_read_ceiling"] = round(ach / roofline["contiguous_read_GBps"], 4)
+    if roofline is not None and args.config == "llama8b" and n_layers == 32 and not args.split:
+        roofline["traffic"] = committed_traffic()
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(cfg, lens0, oracle_hist, ab, lens)
@@ -203,13 +211,56 @@ def main():
     print(json.dumps(res))
 
 
-def cpu_baseline(cfg, lens0, oracle_hist, ab, lens_now):
-    """The oracle, as it stands, on the host cores: one layer of the same workload (all requests:
-    history append is setup, then one timed append + decode step)."""
+def read_ceilings(E, torch, pool, dev, ids, partial_bytes, kv_bytes):
+    """What plain reads reach on this GPU, for scale: one contiguous read of as many bytes as the
+    partial pass moves, and a read-only kernel that walks the same K/V tiles through the same chunk
+    tables with the same cut into pieces (no arithmetic, nothing written)."""
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+
+    def timed(fn, n):
+        fn(0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    nb = min(int(partial_bytes), dev.numel()) // 16 * 16
+    ms_c = timed(lambda i: E.ellm_debug_stream_read(dev, nb, sink), 40)
+    ms_k = timed(lambda i: E.ellm_debug_kv_stream_read(pool, ids[i % len(ids)], sink), 4 * len(ids))
+    # a plain copy of known size: the yardstick that scales the FETCH_SIZE / WRITE_SIZE counters
+    src = torch.zeros(COPY_CALIBRATION_BYTES, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    timed(lambda i: E.ellm_debug_copy(dst, src, COPY_CALIBRATION_BYTES), 3)
+    return {"contiguous_read_GBps": round(nb / ms_c / 1e6, 1), "kv_pattern_read_GBps": round(kv_bytes / ms_k / 1e6, 1)}
+
+
+def committed_traffic():
+    """HBM bytes per launch of the partial pass from the committed counter runs (rocprofv3 --pmc
+    FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for a copy of known
+    size). The summary file states the commands; None when it is absent."""
+    path = os.path.join(ROOT, "profiles", "decode_partial_llama8b_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":", 1)[1].split()[0]))
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(cfg, lens0, oracle_hist, ab, lens_now, budget_s=15.0):
+    """The oracle, as it stands, on the host cores: one layer of the same workload, all requests.
+    Loading the history is setup; the timed part is consecutive append + decode steps (new K/V/q
+    every step) until about `budget_s` seconds of oracle work are done."""
     import workloads as W
     from oracle.model import OraclePool
     B, Tc = cfg.batch, cfg.tokens_per_chunk
-    slots = [int(-(-(int(l) + 1) // Tc)) for l in lens0]
+    max_steps = 400
+    slots = [int(-(-(int(l) + max_steps) // Tc)) for l in lens0]
     n_chunks = sum(slots)
     orc = OraclePool(n_chunks, cfg.chunk_bytes, 0, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, B,
                      max(slots), None, False)
@@ -223,22 +274,26 @@ def cpu_baseline(cfg, lens0, oracle_hist, ab, lens_now):
         ids.append(t)
     kh, vh = oracle_hist[0]
     assert orc.append(ids, kh, vh, lens0.astype(np.int32)) == 0
-    k1 = W.normal_bf16(rng, (B, cfg.n_kv_heads, cfg.head_dim))
-    v1 = W.normal_bf16(rng, (B, cfg.n_kv_heads, cfg.head_dim))
-    q1 = W.normal_bf16(rng, (B, cfg.n_q_heads, cfg.head_dim))
     cores = os.cpu_count() or 1
     cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
-    t0 = time.perf_counter()
-    assert orc.append(ids, k1, v1) == 0
-    rc, _ = orc.decode(ids, q1, threads=cores)
-    t1 = time.perf_counter()
-    assert rc == 0
-    nbytes = W.algorithmic_bytes(cfg, lens0 + 1, 0)["total"]
+    spent, nbytes, n_steps, lens = 0.0, 0, 0, lens0.copy()
+    while spent < budget_s and n_steps < max_steps:
+        k1 = W.normal_bf16(rng, (B, cfg.n_kv_heads, cfg.head_dim))
+        v1 = W.normal_bf16(rng, (B, cfg.n_kv_heads, cfg.head_dim))
+        q1 = W.normal_bf16(rng, (B, cfg.n_q_heads, cfg.head_dim))
+        t0 = time.perf_counter()
+        rc = orc.append(ids, k1, v1)
+        rc2, _ = orc.decode(ids, q1, threads=cores)
+        spent += time.perf_counter() - t0
+        assert rc == 0 and rc2 == 0
+        lens += 1
+        n_steps += 1
+        nbytes += W.algorithmic_bytes(cfg, lens, 0)["total"]
     orc.close()
-    return {"value": round(nbytes / (t1 - t0) / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": f"1 of the layers, all {B} requests, one append + decode step "
-                      f"({int((lens0 + 1).sum())} cached tokens), fp64 C oracle with pthreads",
-            "seconds": round(t1 - t0, 3), "tokens_per_s_per_layer": round(B / (t1 - t0), 2)}
+    return {"value": round(nbytes / spent / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"1 of the layers, all {B} requests, {n_steps} consecutive append + decode steps "
+                      f"({int(lens.sum())} cached tokens at the end), fp64 C oracle with pthreads",
+            "seconds": round(spent, 3), "tokens_per_s_per_layer": round(B * n_steps / spent, 2)}
 
 
 def time_migration(E, torch, pool, ids, lens, Tc, cfg, B):
