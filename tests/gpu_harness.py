@@ -19,6 +19,8 @@ def dev_bits(a: np.ndarray) -> torch.Tensor:
 
 
 def host_bits(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        t = t.view(torch.int16)
     return t.detach().cpu().numpy().view(np.uint16)
 
 
