@@ -160,7 +160,7 @@ def main():
 
     # algorithmic bytes: lengths at the middle of the timed region
     lens_mid = lens - (K + 1) // 2
-    n_items = int(sum(-(-int(x) // S) for x in lens_mid))
+    n_items = int(np.sum(n_split_now))          # partial results per kv-head group, from the library's plan
     ab = W.algorithmic_bytes(cfg, lens_mid, n_items)
     step_bytes = ab["total"] * n_layers
     value = step_bytes / (ms_per_step * 1e-3) / 1e9

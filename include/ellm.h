@@ -246,10 +246,11 @@ int ellm_debug_copy(void* dst, const void* src, uint64_t bytes, void* stream);
 int ellm_debug_stream_read(const void* src, uint64_t bytes, void* sink, void* stream);
 int ellm_debug_kv_stream_read(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, void* sink, void* stream);
 
-/* How the partial pass hands pieces to waves, for A/B measurements: 0 = automatic, 1 = one wave
- * per piece, 2 = resident waves that take pieces from a shared counter. The cut into pieces, and
- * with it every result bit, is the same in all three. */
-int ellm_debug_set_schedule(ellm_pool* pool, int schedule);
+/* Parameters of the automatic cut into pieces, for measurements: tail_percent (0..90) of every
+ * request's tiles are kept back for small pieces of small_tiles (>= 1) 64-token tiles each. The
+ * defaults are what the library was tuned to on MI355X. Results stay within the stated tolerance
+ * for every setting; bits may differ between settings. */
+int ellm_debug_set_partition(ellm_pool* pool, int32_t tail_percent, int32_t small_tiles);
 
 /* O(n) consistency scan of the host state (tables, chunk records, free lists, host slots agree;
  * no chunk backs two slots). Returns 0 when consistent, else a positive rule number. */

@@ -58,9 +58,8 @@ struct ellm_pool {
   bool have_last_stream = false;
   int32_t split_override = 0;
   int32_t wave_slots = 0;              // resident partial-pass waves on the whole GPU (0 = not asked yet)
-  int32_t* d_counters = nullptr;       // ring of piece counters (zero between uses)
-  int32_t next_counter = 0;
-  int32_t schedule = 0;                // 0 = automatic, 1 = one wave per piece, 2 = persistent waves
+  int32_t tail_percent = 10;           // share of every request's tiles kept for small pieces (automatic cut)
+  int32_t small_tiles = 1;             // tiles per small piece (automatic cut)
 
   // optional timing of the partial (dominant) kernel with events on the caller's stream
   std::vector<hipEvent_t> prof_ev;     // 2 per record
@@ -103,8 +102,6 @@ int ensure_device(ellm_pool* p) {
   HIP_TRY(hipMalloc((void**)&p->d_table, bytes), "hipMalloc(table mirror)");
   HIP_TRY(hipMemcpy(p->d_table, p->core->table().data(), bytes, hipMemcpyHostToDevice), "hipMemcpy(table mirror)");
   (void)p->core->take_dirty();   // the full upload covers everything so far
-  HIP_TRY(hipMalloc((void**)&p->d_counters, ellm::N_WORK_COUNTERS * sizeof(int32_t)), "hipMalloc(counters)");
-  HIP_TRY(hipMemset(p->d_counters, 0, ellm::N_WORK_COUNTERS * sizeof(int32_t)), "hipMemset(counters)");
   HIP_TRY(hipStreamCreateWithFlags(&p->side, hipStreamNonBlocking), "hipStreamCreate(side)");
   HIP_TRY(hipEventCreateWithFlags(&p->ev_compute, hipEventDisableTiming), "hipEventCreate");
   HIP_TRY(hipEventCreateWithFlags(&p->ev_migrate, hipEventDisableTiming), "hipEventCreate");
@@ -202,13 +199,15 @@ int32_t wave_slots(ellm_pool* p) {
   return slots;
 }
 
-// The partition of one launch (at most MAX_LAUNCH_REQ requests): every (request, kv head) pair is
-// cut into pieces of the same number of tiles, one partial result per piece. The piece size depends
-// only on the batch's lengths, the pool geometry and the device's wave capacity, never on physical
-// chunk ids or on which wave runs which piece, so every rounding is reproducible and invariant
-// under remapping. It aims at one piece per resident wave, so that the whole launch is resident at
-// once: measured on MI355X, smaller pieces lose more to their fixed start-up and wrap-up cost
-// than they gain in balance.
+// The partition of one launch (at most MAX_LAUNCH_REQ requests). Every (request, kv head) pair is cut
+// into big pieces followed by small ones, one wave and one partial result per piece. The big pieces
+// are sized so that there is about one per resident wave: they fill the GPU once. The last
+// tail_percent of every request's tiles (and whatever does not fill a big piece) become small
+// pieces, which the dispatcher hands out as waves finish, so that faster waves and compute units
+// take more of them. The cut depends only on the batch's lengths, the pool geometry and the
+// device's wave capacity, never on physical chunk ids or on which wave runs which piece: every
+// rounding is reproducible and invariant under remapping.
+// With an override (tests) all pieces have the given size and only the remainder is "small".
 void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0, int64_t ws_slot0, ellm::BatchArgs& a) {
   const int32_t Tc = p->geom.tokens_per_chunk;
   const int32_t tpc = (Tc + ellm::TILE_TOKENS - 1) / ellm::TILE_TOKENS;
@@ -225,31 +224,36 @@ void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0
   }
   total_tiles *= p->geom.n_kv_heads;
   const int32_t slots = wave_slots(p);
-  int64_t per_piece;
-  if (p->split_override > 0) per_piece = std::max<int64_t>(1, p->split_override / ellm::TILE_TOKENS);
-  else per_piece = std::max<int64_t>(1, (total_tiles + slots - 1) / slots);
-  int64_t prefix = 0;
+  int64_t big, small, keep_percent;
+  if (p->split_override > 0) {
+    big = small = std::max<int64_t>(1, p->split_override / ellm::TILE_TOKENS);
+    keep_percent = 100;
+  } else {
+    keep_percent = 100 - p->tail_percent;
+    big = std::max<int64_t>(1, (total_tiles * keep_percent / 100 + slots - 1) / slots);
+    small = std::min<int64_t>(big, p->small_tiles);
+  }
+  int64_t big_prefix = 0, small_prefix = 0;
   int32_t most = 0;
   for (int32_t i = 0; i < n_req; i++) {
-    const int32_t pieces = (int32_t)((tiles[i] + per_piece - 1) / per_piece);
-    a.piece_prefix[i] = (int32_t)prefix;
-    prefix += pieces;
-    most = std::max(most, pieces);
+    const int64_t n_big = (int64_t)tiles[i] * keep_percent / 100 / big;
+    const int64_t n_small = (tiles[i] - n_big * big + small - 1) / small;
+    a.big_prefix[i] = (int32_t)big_prefix;
+    a.small_prefix[i] = (int32_t)small_prefix;
+    big_prefix += n_big;
+    small_prefix += n_small;
+    most = std::max<int32_t>(most, (int32_t)(n_big + n_small));
   }
-  a.piece_prefix[n_req] = (int32_t)prefix;
+  a.big_prefix[n_req] = (int32_t)big_prefix;
+  a.small_prefix[n_req] = (int32_t)small_prefix;
   a.n_req = n_req;
   a.q_row0 = q_row0;
-  a.pieces_per_head = (int32_t)prefix;
-  a.tiles_per_piece = (int32_t)per_piece;
-  a.n_pieces = (int32_t)(prefix * p->geom.n_kv_heads);
+  a.big_per_head = (int32_t)big_prefix;
+  a.small_per_head = (int32_t)small_prefix;
+  a.tiles_big = (int32_t)big;
+  a.tiles_small = (int32_t)small;
   a.max_partials = most;
   a.ws_slot0 = (int32_t)ws_slot0;
-  const bool persistent = p->schedule == 2;
-  a.persistent = persistent ? 1 : 0;
-  a.n_waves = persistent ? std::min(a.n_pieces, slots) : a.n_pieces;
-  a.n_counters = ellm::partial_launches_per_decode(p->geom.group);
-  a.counter0 = p->next_counter;
-  a.pad = 0;
 }
 
 int64_t launch_ws_slots(const ellm_pool* p, const ellm::BatchArgs& a) {
@@ -319,7 +323,6 @@ int ellm_pool_destroy(ellm_pool* p) {
     (void)hipEventDestroy(p->ev_compute);
     (void)hipEventDestroy(p->ev_migrate);
     (void)hipFree(p->d_table);
-    (void)hipFree(p->d_counters);
     for (hipEvent_t e : p->prof_ev) (void)hipEventDestroy(e);
     if (p->d_ws) (void)hipFree(p->d_ws);
   }
@@ -404,9 +407,10 @@ int ellm_decode_plan(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, int
   for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
     const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
     plan_launch(p, ids + b0, nb, b0, 0, a);
-    per_wave = std::max(per_wave, a.tiles_per_piece);
+    per_wave = std::max(per_wave, a.tiles_big);
     if (n_split)
-      for (int32_t i = 0; i < nb; i++) n_split[b0 + i] = a.piece_prefix[i + 1] - a.piece_prefix[i];
+      for (int32_t i = 0; i < nb; i++)
+        n_split[b0 + i] = a.big_prefix[i + 1] - a.big_prefix[i] + a.small_prefix[i + 1] - a.small_prefix[i];
   }
   if (split_tokens) *split_tokens = per_wave * ellm::TILE_TOKENS;
   return ELLM_OK;
@@ -441,8 +445,8 @@ int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch
     launches.emplace_back();
     plan_launch(p, ids + b0, nb, b0, ws_slots, launches.back());
     ws_slots += launch_ws_slots(p, launches.back());
-    p->next_counter = (p->next_counter + launches.back().n_counters) % ellm::N_WORK_COUNTERS;
-    if ((int64_t)launches.back().pieces_per_head * p->geom.n_kv_heads > 0x7fffffffll || ws_slots > 0x7fffffffll)
+    const ellm::BatchArgs& la = launches.back();
+    if (((int64_t)la.big_per_head + la.small_per_head) * p->geom.n_kv_heads > 0x7fffffffll || ws_slots > 0x7fffffffll)
       return set_err(ELLM_ERR_RANGE, "decode_attention: too much work for one call");
   }
   rc = ensure_workspace(p, ws_slots);
@@ -452,13 +456,13 @@ int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch
   for (const ellm::BatchArgs& a : launches) {
     const bool prof = (size_t)(p->prof_used + 1) * 2 <= p->prof_ev.size();
     if (prof) HIP_TRY(hipEventRecord(p->prof_ev[2 * p->prof_used], stream), "hipEventRecord(profile)");
-    int e = ellm::launch_decode_partial(pv, q, p->d_ws, scale_log2, p->d_counters, a, stream);
+    int e = ellm::launch_decode_partial(pv, q, p->d_ws, scale_log2, a, stream);
     if (e) return hip_err((hipError_t)e, "decode partial launch");
     if (prof) {
       HIP_TRY(hipEventRecord(p->prof_ev[2 * p->prof_used + 1], stream), "hipEventRecord(profile)");
       p->prof_used++;
     }
-    e = ellm::launch_decode_combine(pv, p->d_ws, out, p->d_counters, a, stream);
+    e = ellm::launch_decode_combine(pv, p->d_ws, out, a, stream);
     if (e) return hip_err((hipError_t)e, "decode combine launch");
   }
   return ELLM_OK;
@@ -600,17 +604,17 @@ int ellm_debug_kv_stream_read(ellm_pool* p, const ellm_tensor_id* ids, int32_t b
   for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
     const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
     plan_launch(p, ids + b0, nb, b0, 0, a);
-    p->next_counter = (p->next_counter + 1) % ellm::N_WORK_COUNTERS;
-    int e = ellm::launch_kv_stream(pv, (uint32_t*)sink, p->d_counters, a, stream);
-    if (!e) e = ellm::launch_reset_counters(p->d_counters, a.counter0, 1, stream);
+    int e = ellm::launch_kv_stream(pv, (uint32_t*)sink, a, stream);
     if (e) return hip_err((hipError_t)e, "kv stream launch");
   }
   return ELLM_OK;
 }
 
-int ellm_debug_set_schedule(ellm_pool* p, int schedule) {
-  if (!p || schedule < 0 || schedule > 2) return set_err(ELLM_ERR_INVALID, "set_schedule: bad argument");
-  p->schedule = schedule;
+int ellm_debug_set_partition(ellm_pool* p, int32_t tail_percent, int32_t small_tiles) {
+  if (!p || tail_percent < 0 || tail_percent > 90 || small_tiles < 1)
+    return set_err(ELLM_ERR_INVALID, "set_partition: bad argument");
+  p->tail_percent = tail_percent;
+  p->small_tiles = small_tiles;
   return ELLM_OK;
 }
 

@@ -145,20 +145,41 @@ __global__ __launch_bounds__(256) void kv_append_kernel(PoolView pv, const uint4
 // ---------------------------------------------------------------------------------------------
 // work partition shared by the partial pass, the combine pass and the calibration kernel
 // ---------------------------------------------------------------------------------------------
-// request b with piece_prefix[b] <= pos < piece_prefix[b + 1] (wave-uniform result)
-__device__ __forceinline__ int find_request(const BatchArgs& a, int pos, int lane) {
-  int cnt = 0;
-  for (int base = 0; base < a.n_req; base += 64) {
-    const int i = base + lane;
-    cnt += __popcll(__ballot(i < a.n_req && a.piece_prefix[i] <= pos));
-  }
-  return __builtin_amdgcn_readfirstlane(cnt - 1);
-}
-
 // number of tiles of a sequence of len tokens (a tile never straddles a chunk)
 __device__ __forceinline__ int32_t tiles_of(int32_t len, int32_t Tc, int32_t tiles_per_chunk) {
   const int32_t full = len / Tc, rest = len - full * Tc;
   return full * tiles_per_chunk + (rest + TILE_TOKENS - 1) / TILE_TOKENS;
+}
+
+// request b with prefix[b] <= pos < prefix[b + 1] (wave-uniform result)
+__device__ __forceinline__ int find_request(const int32_t* prefix, int n_req, int pos, int lane) {
+  int cnt = 0;
+  for (int base = 0; base < n_req; base += 64) {
+    const int i = base + lane;
+    cnt += __popcll(__ballot(i < n_req && prefix[i] <= pos));
+  }
+  return __builtin_amdgcn_readfirstlane(cnt - 1);
+}
+
+// which piece a workgroup handles: kv head, request, partial slot, first tile, number of tiles
+struct Piece { int32_t g, b, j, tile0, n_tiles; };
+__device__ __forceinline__ Piece locate_piece(const PoolView& pv, const BatchArgs& a, int32_t index, int lane) {
+  const int32_t n_big_total = a.big_per_head * pv.n_kv_heads;
+  const bool small = index >= n_big_total;
+  const int32_t idx = small ? index - n_big_total : index;
+  const int32_t per_head = small ? a.small_per_head : a.big_per_head;
+  Piece p;
+  p.g = idx / per_head;
+  const int32_t rem = idx - p.g * per_head;
+  const int32_t* prefix = small ? a.small_prefix : a.big_prefix;
+  p.b = find_request(prefix, a.n_req, rem, lane);
+  const int32_t j = rem - prefix[p.b];
+  const int32_t n_big = a.big_prefix[p.b + 1] - a.big_prefix[p.b];
+  const int32_t tiles = tiles_of(a.len[p.b], pv.tokens_per_chunk, pv.tiles_per_chunk);
+  p.tile0 = small ? n_big * a.tiles_big + j * a.tiles_small : j * a.tiles_big;
+  p.n_tiles = small ? min(a.tiles_small, tiles - p.tile0) : a.tiles_big;
+  p.j = small ? n_big + j : j;
+  return p;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -183,8 +204,7 @@ __device__ __forceinline__ int32_t tiles_of(int32_t len, int32_t Tc, int32_t til
 template <int D, int G>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_partial_kernel(PoolView pv, const uint16_t* __restrict__ q,
                                                             float* __restrict__ ws, float scale_log2,
-                                                            int32_t g_first, int32_t* __restrict__ counter,
-                                                            BatchArgs a) {
+                                                            int32_t g_first, BatchArgs a) {
   constexpr int LPR = D / 8;             // lanes per row = 16-byte pieces per row
   constexpr int RPW = 64 / LPR;          // rows per wave-wide load
   constexpr int NL = 64 / RPW;           // wave-wide loads per 64-row tile and plane
@@ -279,21 +299,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     }                                                                                               \
   }
 
-  for (int32_t piece = blockIdx.x;;) {
-    // ---- which piece: one per wave, or the next one from the shared counter --------------------
-    if (a.persistent) {
-      int32_t next = 0;
-      if (lane == 0) next = atomicAdd(counter, 1);
-      piece = __builtin_amdgcn_readfirstlane(next);
-    }
-    if (piece >= a.n_pieces) break;
-    const int32_t g = piece / a.pieces_per_head;                       // kv head
-    const int32_t rem = piece - g * a.pieces_per_head;
-    const int32_t b = find_request(a, rem, lane);
-    const int32_t j = rem - a.piece_prefix[b];                         // piece number within the pair
+  {
+    const Piece pc = locate_piece(pv, a, blockIdx.x, lane);
+    const int32_t g = pc.g, b = pc.b, j = pc.j, tile0 = pc.tile0, n_tiles = pc.n_tiles;
     const int32_t len = a.len[b];
-    const int32_t tile0 = j * a.tiles_per_piece;
-    const int32_t n_tiles = min(a.tiles_per_piece, tiles_of(len, Tc, pv.tiles_per_chunk) - tile0);
     const int hq0 = g * pv.group + g_first;            // first q head handled here
     // the table row is read-only for the kernel's lifetime: uniform (scalar) loads
     const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)a.tensor[b] * pv.max_slots);
@@ -373,8 +382,6 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
         if (sub == 0) { wout[i * (D + WS_ROW_PAD) + D] = m[i]; wout[i * (D + WS_ROW_PAD) + D + 1] = l[i]; }
       }
     }
-    if (!a.persistent) break;
-    __builtin_amdgcn_wave_barrier();
   }
 #undef ELLM_LOAD_TILE
 #undef ELLM_LOAD_K_TILE
@@ -384,30 +391,64 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
 }
 
 // ---------------------------------------------------------------------------------------------
-// combine pass: merge the partials of every (request, q head) in wave order, normalise, round
+// combine pass: one wave per (request, q head). First the common maximum and the normaliser from
+// the (m, l) pairs of all partials, one partial per lane; then the weighted sum of the
+// accumulators, whose loads do not depend on one another.
 // ---------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(D) void decode_combine_kernel(const float* __restrict__ ws, uint16_t* __restrict__ out,
-                                                           int32_t n_q_heads, int32_t n_kv_heads, int32_t group,
-                                                           int32_t* __restrict__ counters, BatchArgs a) {
-  const int b = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
-  // the partial pass is over: put its piece counters back to zero for their next use
-  if (b == 0 && h == 0 && d < a.n_counters) counters[(a.counter0 + d) % N_WORK_COUNTERS] = 0;
+__global__ __launch_bounds__(64) void decode_combine_kernel(const float* __restrict__ ws, uint16_t* __restrict__ out,
+                                                            int32_t n_q_heads, int32_t n_kv_heads, int32_t group,
+                                                            BatchArgs a) {
+  constexpr int DPL = D / 64;        // output dims per lane
+  const int b = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
   const int g = h / group;
-  const int n_part = a.piece_prefix[b + 1] - a.piece_prefix[b];
-  const float* p = ws + ((a.ws_slot0 + (int64_t)(b * n_kv_heads + g) * a.max_partials) * group + (h - g * group)) *
-                            (D + WS_ROW_PAD);
+  const int n_part = a.big_prefix[b + 1] - a.big_prefix[b] + a.small_prefix[b + 1] - a.small_prefix[b];
+  const float* p0 = ws + ((a.ws_slot0 + (int64_t)(b * n_kv_heads + g) * a.max_partials) * group + (h - g * group)) *
+                             (D + WS_ROW_PAD);
   const int64_t stride = (int64_t)group * (D + WS_ROW_PAD);
-  float M = NEG_BIG, L = 0.f, A = 0.f;
-  for (int j = 0; j < n_part; j++, p += stride) {
-    const float mj = p[D], lj = p[D + 1], aj = p[d];
-    const float mn = fmaxf(M, mj);
-    const float c0 = fast_exp2(M - mn), c1 = fast_exp2(mj - mn);
-    L = L * c0 + lj * c1;
-    A = A * c0 + aj * c1;
-    M = mn;
+  float M = NEG_BIG;
+  for (int j = lane; j < n_part; j += 64) M = fmaxf(M, p0[j * stride + D]);
+  M = wave_max(M);
+  float L = 0.f, A[DPL];
+#pragma unroll
+  for (int e = 0; e < DPL; e++) A[e] = 0.f;
+  for (int j0 = 0; j0 < n_part; j0 += 64) {
+    // weight of partial j0 + lane, then every lane walks the block's partials in order
+    const int jl = j0 + lane;
+    float c = 0.f;
+    if (jl < n_part) {
+      c = fast_exp2(p0[jl * stride + D] - M);
+      L += p0[jl * stride + D + 1] * c;
+    }
+    const int nb = min(64, n_part - j0);
+    const float* p = p0 + j0 * stride + lane * DPL;
+    int j = 0;
+    for (; j + 4 <= nb; j += 4) {
+      float v[4][DPL];
+#pragma unroll
+      for (int u = 0; u < 4; u++)
+#pragma unroll
+        for (int e = 0; e < DPL; e++) v[u][e] = p[(j + u) * stride + e];
+#pragma unroll
+      for (int u = 0; u < 4; u++) {
+        const float cu = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(c), j + u));
+#pragma unroll
+        for (int e = 0; e < DPL; e++) A[e] += v[u][e] * cu;
+      }
+    }
+    for (; j < nb; j++) {
+      const float cu = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(c), j));
+#pragma unroll
+      for (int e = 0; e < DPL; e++) A[e] += p[j * stride + e] * cu;
+    }
   }
-  out[((int64_t)(a.q_row0 + b) * n_q_heads + h) * D + d] = (uint16_t)f32_to_bf16_bits(A / L);
+  L = wave_sum(L);
+  uint16_t* o = out + ((int64_t)(a.q_row0 + b) * n_q_heads + h) * D + lane * DPL;
+  if (DPL == 2) {
+    *reinterpret_cast<uint32_t*>(o) = f32_to_bf16_bits(A[0] / L) | (f32_to_bf16_bits(A[DPL - 1] / L) << 16);
+  } else {
+    o[0] = (uint16_t)f32_to_bf16_bits(A[0] / L);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -442,27 +483,16 @@ __global__ __launch_bounds__(256) void read_kernel(const uint4* __restrict__ src
 // the K/V rows a decode over this batch reads, with the same work partition and load shape (one
 // wave per equal share of tiles, 64-row tiles, 128-bit loads), but no arithmetic
 template <int D>
-__global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __restrict__ sink,
-                                                       int32_t* __restrict__ counter, BatchArgs a) {
+__global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __restrict__ sink, BatchArgs a) {
   constexpr int LPR = D / 8, RPW = 64 / LPR, NL = 64 / RPW, ROWB = D * 2;
   const int lane = threadIdx.x;
   const int sub = lane % LPR, rg = lane / LPR;
   const int32_t Tc = pv.tokens_per_chunk;
   uint32_t x = 0;
-  for (int32_t piece = blockIdx.x;;) {
-    if (a.persistent) {
-      int32_t next = 0;
-      if (lane == 0) next = atomicAdd(counter, 1);
-      piece = __builtin_amdgcn_readfirstlane(next);
-    }
-    if (piece >= a.n_pieces) break;
-    const int32_t g = piece / a.pieces_per_head;
-    const int32_t rem = piece - g * a.pieces_per_head;
-    const int32_t b = find_request(a, rem, lane);
-    const int32_t j = rem - a.piece_prefix[b];
+  {
+    const Piece pc = locate_piece(pv, a, blockIdx.x, lane);
+    const int32_t g = pc.g, b = pc.b, tile0 = pc.tile0, n_tiles = pc.n_tiles;
     const int32_t len = a.len[b];
-    const int32_t tile0 = j * a.tiles_per_piece;
-    const int32_t n_tiles = min(a.tiles_per_piece, tiles_of(len, Tc, pv.tiles_per_chunk) - tile0);
     const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)a.tensor[b] * pv.max_slots);
     int32_t slot = tile0 / pv.tiles_per_chunk;
     int32_t r = (tile0 - slot * pv.tiles_per_chunk) * TILE_TOKENS;
@@ -482,7 +512,6 @@ __global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __
       r += TILE_TOKENS;
       if (r >= Tc) { r = 0; slot += 1; }
     }
-    if (!a.persistent) break;
   }
   if (x == 0x9e3779b9u) sink[0] = x;
 }
@@ -544,52 +573,44 @@ int partial_waves_per_cu(int head_dim, int group) {
 
 template <int D, int G>
 static void launch_partial_t(const PoolView& pv, const void* q, float* ws, float scale_log2, int32_t g_first,
-                             int32_t* counter, const BatchArgs& a, hipStream_t stream) {
-  hipLaunchKernelGGL((decode_partial_kernel<D, G>), dim3(a.n_waves), dim3(64), 0, stream, pv,
-                     (const uint16_t*)q, ws, scale_log2, g_first, counter, a);
+                             const BatchArgs& a, hipStream_t stream) {
+  const unsigned grid = (unsigned)((a.big_per_head + a.small_per_head) * pv.n_kv_heads);
+  hipLaunchKernelGGL((decode_partial_kernel<D, G>), dim3(grid), dim3(64), 0, stream, pv,
+                     (const uint16_t*)q, ws, scale_log2, g_first, a);
 }
 
 // a group size that is not 8, 4, 2 or 1 is covered by several launches over the same K/V
-int partial_launches_per_decode(int group) {
-  int n = 0;
-  for (int done = 0; done < group; done += group_step(group - done)) n++;
-  return n;
-}
-
 template <int D>
-static int launch_partial_d(const PoolView& pv, const void* q, float* ws, float scale_log2, int32_t* counters,
-                            const BatchArgs& a, hipStream_t stream) {
-  int done = 0, k = 0;
+static int launch_partial_d(const PoolView& pv, const void* q, float* ws, float scale_log2, const BatchArgs& a,
+                            hipStream_t stream) {
+  int done = 0;
   while (done < pv.group) {
     const int step = group_step(pv.group - done);
-    int32_t* counter = counters + (a.counter0 + k) % N_WORK_COUNTERS;
-    if (step == 8) launch_partial_t<D, 8>(pv, q, ws, scale_log2, done, counter, a, stream);
-    else if (step == 4) launch_partial_t<D, 4>(pv, q, ws, scale_log2, done, counter, a, stream);
-    else if (step == 2) launch_partial_t<D, 2>(pv, q, ws, scale_log2, done, counter, a, stream);
-    else launch_partial_t<D, 1>(pv, q, ws, scale_log2, done, counter, a, stream);
+    if (step == 8) launch_partial_t<D, 8>(pv, q, ws, scale_log2, done, a, stream);
+    else if (step == 4) launch_partial_t<D, 4>(pv, q, ws, scale_log2, done, a, stream);
+    else if (step == 2) launch_partial_t<D, 2>(pv, q, ws, scale_log2, done, a, stream);
+    else launch_partial_t<D, 1>(pv, q, ws, scale_log2, done, a, stream);
     ELLM_HIP_CHECK_LAUNCH();
     done += step;
-    k++;
   }
   return 0;
 }
 
-int launch_decode_partial(const PoolView& pv, const void* q, float* ws, float scale_log2, int32_t* counters,
-                          const BatchArgs& a, hipStream_t stream) {
-  if (a.n_req <= 0 || a.n_waves <= 0) return 0;
-  return pv.head_dim == 128 ? launch_partial_d<128>(pv, q, ws, scale_log2, counters, a, stream)
-                            : launch_partial_d<64>(pv, q, ws, scale_log2, counters, a, stream);
+int launch_decode_partial(const PoolView& pv, const void* q, float* ws, float scale_log2, const BatchArgs& a,
+                          hipStream_t stream) {
+  if (a.n_req <= 0 || a.big_per_head + a.small_per_head <= 0) return 0;
+  return pv.head_dim == 128 ? launch_partial_d<128>(pv, q, ws, scale_log2, a, stream)
+                            : launch_partial_d<64>(pv, q, ws, scale_log2, a, stream);
 }
 
-int launch_decode_combine(const PoolView& pv, const float* ws, void* out, int32_t* counters, const BatchArgs& a,
-                          hipStream_t stream) {
+int launch_decode_combine(const PoolView& pv, const float* ws, void* out, const BatchArgs& a, hipStream_t stream) {
   if (a.n_req <= 0) return 0;
   if (pv.head_dim == 128)
-    hipLaunchKernelGGL(decode_combine_kernel<128>, dim3(a.n_req, pv.n_q_heads), dim3(128), 0, stream, ws,
-                       (uint16_t*)out, pv.n_q_heads, pv.n_kv_heads, pv.group, counters, a);
+    hipLaunchKernelGGL(decode_combine_kernel<128>, dim3(a.n_req, pv.n_q_heads), dim3(64), 0, stream, ws,
+                       (uint16_t*)out, pv.n_q_heads, pv.n_kv_heads, pv.group, a);
   else
     hipLaunchKernelGGL(decode_combine_kernel<64>, dim3(a.n_req, pv.n_q_heads), dim3(64), 0, stream, ws,
-                       (uint16_t*)out, pv.n_q_heads, pv.n_kv_heads, pv.group, counters, a);
+                       (uint16_t*)out, pv.n_q_heads, pv.n_kv_heads, pv.group, a);
   ELLM_HIP_CHECK_LAUNCH();
   return 0;
 }
@@ -612,23 +633,13 @@ int launch_read(const void* src, int64_t bytes, uint32_t* sink, hipStream_t stre
   return 0;
 }
 
-int launch_kv_stream(const PoolView& pv, uint32_t* sink, int32_t* counters, const BatchArgs& a, hipStream_t stream) {
-  if (a.n_req <= 0 || a.n_waves <= 0) return 0;
-  int32_t* counter = counters + a.counter0 % N_WORK_COUNTERS;
+int launch_kv_stream(const PoolView& pv, uint32_t* sink, const BatchArgs& a, hipStream_t stream) {
+  const unsigned grid = (unsigned)((a.big_per_head + a.small_per_head) * pv.n_kv_heads);
+  if (a.n_req <= 0 || grid == 0) return 0;
   if (pv.head_dim == 128)
-    hipLaunchKernelGGL(kv_stream_kernel<128>, dim3(a.n_waves), dim3(64), 0, stream, pv, sink, counter, a);
+    hipLaunchKernelGGL(kv_stream_kernel<128>, dim3(grid), dim3(64), 0, stream, pv, sink, a);
   else
-    hipLaunchKernelGGL(kv_stream_kernel<64>, dim3(a.n_waves), dim3(64), 0, stream, pv, sink, counter, a);
-  ELLM_HIP_CHECK_LAUNCH();
-  return 0;
-}
-
-// counters[first .. first + n) = 0 (the calibration kernel has no combine pass to do it)
-__global__ void reset_counters_kernel(int32_t* counters, int first, int n) {
-  if ((int)threadIdx.x < n) counters[(first + threadIdx.x) % N_WORK_COUNTERS] = 0;
-}
-int launch_reset_counters(int32_t* counters, int first, int n, hipStream_t stream) {
-  hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, stream, counters, first, n);
+    hipLaunchKernelGGL(kv_stream_kernel<64>, dim3(grid), dim3(64), 0, stream, pv, sink, a);
   ELLM_HIP_CHECK_LAUNCH();
   return 0;
 }

@@ -6,7 +6,7 @@
 
 namespace ellm {
 
-constexpr int MAX_LAUNCH_REQ = 256;   // requests described by one launch's kernel arguments
+constexpr int MAX_LAUNCH_REQ = 192;   // requests described by one launch's kernel arguments (4 KB in all)
 constexpr int MAX_PATCH = 448;        // table entries patched by one launch
 constexpr int TILE_TOKENS = 64;       // rows of K (and V) one wave handles at a time
 constexpr int WS_ROW_PAD = 4;         // a partial row is head_dim accumulators, m, l and 2 unused floats
@@ -23,32 +23,27 @@ struct PoolView {
 };
 
 // One decode launch: requests [q_row0, q_row0 + n_req) of the caller's batch.
-// The tiles of every (request, kv head) pair are cut into pieces of tiles_per_piece tiles (the last
-// piece of a request may be shorter). All pieces form one sequence, kv head major:
-//   piece index = g * pieces_per_head + piece_prefix[b] + j.
-// Each piece is handled by one wave and yields one partial result, stored in slot j of its pair.
-// Waves take pieces either one per wave (grid = number of pieces) or, when `persistent` is set, from
-// a shared counter until none is left (grid = resident waves): the cut into pieces is fixed either
-// way, so results do not depend on which wave ran which piece.
+// The tiles of every (request, kv head) pair are cut into pieces, one wave and one partial result
+// each: first n_big "big" pieces of tiles_big tiles, then the remaining tiles in "small" pieces of
+// tiles_small tiles (the last one may be shorter). The grid runs all big pieces first, kv head
+// major (index g * big_per_head + big_prefix[b] + j), then all small pieces in the same order: the
+// big pieces fill the GPU once, and the small ones are handed out by the hardware dispatcher as
+// waves finish, which evens out waves and compute units that run at different speeds. Partial j of
+// a pair is big piece j, or small piece j - n_big; the cut is fixed by the plan, so results do not
+// depend on which wave ran when.
 struct BatchArgs {
   int32_t n_req;
   int32_t q_row0;             // row of the first request in q / out
-  int32_t pieces_per_head;    // = piece_prefix[n_req]
-  int32_t tiles_per_piece;
-  int32_t n_pieces;           // pieces_per_head * n_kv_heads
+  int32_t big_per_head;       // = big_prefix[n_req]
+  int32_t small_per_head;     // = small_prefix[n_req]
+  int32_t tiles_big, tiles_small;
   int32_t max_partials;       // partial slots per (request, kv head) = most pieces any request has
   int32_t ws_slot0;           // first partial slot of this launch in the workspace
-  int32_t n_waves;            // grid size of the partial pass
-  int32_t persistent;         // waves loop over a shared piece counter
-  int32_t counter0;           // first work counter used by this launch's partial pass(es)
-  int32_t n_counters;         // how many it uses (one per partial-pass launch)
-  int32_t pad;
   int32_t tensor[MAX_LAUNCH_REQ];
   int32_t len[MAX_LAUNCH_REQ];
-  int32_t piece_prefix[MAX_LAUNCH_REQ + 1];
+  int32_t big_prefix[MAX_LAUNCH_REQ + 1];
+  int32_t small_prefix[MAX_LAUNCH_REQ + 1];
 };
-
-constexpr int N_WORK_COUNTERS = 256;   // ring of piece counters in device memory
 
 struct AppendArgs {
   int32_t n_req, total_new;
@@ -70,16 +65,13 @@ int partial_waves_per_cu(int head_dim, int group);
 int launch_table_patch(int32_t* table, const PatchArgs& a, hipStream_t stream);
 int launch_kv_append(const PoolView& pv, const void* k_new, const void* v_new, const AppendArgs& a,
                      hipStream_t stream);
-int launch_decode_partial(const PoolView& pv, const void* q, float* ws, float scale_log2, int32_t* counters,
-                          const BatchArgs& a, hipStream_t stream);
-int launch_decode_combine(const PoolView& pv, const float* ws, void* out, int32_t* counters, const BatchArgs& a,
+int launch_decode_partial(const PoolView& pv, const void* q, float* ws, float scale_log2, const BatchArgs& a,
                           hipStream_t stream);
-int partial_launches_per_decode(int group);
+int launch_decode_combine(const PoolView& pv, const float* ws, void* out, const BatchArgs& a, hipStream_t stream);
 
 // calibration (measurement only)
 int launch_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream);
 int launch_read(const void* src, int64_t bytes, uint32_t* sink, hipStream_t stream);
-int launch_kv_stream(const PoolView& pv, uint32_t* sink, int32_t* counters, const BatchArgs& a, hipStream_t stream);
-int launch_reset_counters(int32_t* counters, int first, int n, hipStream_t stream);
+int launch_kv_stream(const PoolView& pv, uint32_t* sink, const BatchArgs& a, hipStream_t stream);
 
 }  // namespace ellm
