@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the measured read ceilings")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="ellm_kv_append then ellm_decode_attention instead of the fused ellm_kv_append_decode")
     ap.add_argument("--migration", action="store_true", help="also time offload / fetch of 25%% of the requests")
     return ap.parse_args()
 
@@ -126,7 +128,8 @@ def main():
     c_q = [C.c_void_p(t.data_ptr()) for t in q]
     c_o = [C.c_void_p(t.data_ptr()) for t in out]
     c_scale = C.c_float(0.0)
-    f_append, f_decode = E.lib.ellm_kv_append, E.lib.ellm_decode_attention
+    f_append, f_decode, f_fused = E.lib.ellm_kv_append, E.lib.ellm_decode_attention, E.lib.ellm_kv_append_decode
+    fused = not args.separate_calls
 
     def step():
         # a3: requests whose next token opens a new chunk get one mapped (inflating if needed)
@@ -134,8 +137,11 @@ def main():
             for l in range(n_layers):
                 E.ellm_tensor_map_chunks(pool, int(ids[l][b]), int(lens[b]) // Tc, 1, None, E.ELLM_MAP_ALLOW_INFLATE)
         for l in range(n_layers):
-            rc = f_append(c_pool, c_ids[l], B, None, c_k[l], c_v[l], c_stream)
-            rc |= f_decode(c_pool, c_ids[l], B, c_q[l], c_o[l], c_scale, c_stream)
+            if fused:
+                rc = f_fused(c_pool, c_ids[l], B, c_k[l], c_v[l], c_q[l], c_o[l], c_scale, c_stream)
+            else:
+                rc = f_append(c_pool, c_ids[l], B, None, c_k[l], c_v[l], c_stream)
+                rc |= f_decode(c_pool, c_ids[l], B, c_q[l], c_o[l], c_scale, c_stream)
             if rc:
                 raise E.EllmError(rc, E.ellm_last_error())
         lens[:] += 1
@@ -164,8 +170,9 @@ def main():
     ab = W.algorithmic_bytes(cfg, lens_mid, n_items)
     step_bytes = ab["total"] * n_layers
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
-    # dominant kernel: the partial pass reads K/V, q and table entries and writes the partials
-    partial_bytes = ab["kv"] + ab["q_out"] // 2 + ab["table"] + ab["partials"] // 2
+    # dominant kernel: the partial pass reads K/V, q and table entries and writes the partials; fused, it
+    # also reads the new token's K/V rows and writes them into their chunks
+    partial_bytes = ab["kv"] + ab["q_out"] // 2 + ab["table"] + ab["partials"] // 2 + (ab["append"] if fused else 0)
     roofline = None
     if use_events and len(kern_ms):
         avg = float(np.mean(kern_ms))
@@ -200,7 +207,8 @@ def main():
         "config": {"workload": f"{args.config}: {Hq}q/{Hkv}kv heads, head_dim {D}, batch {B}, {n_layers} layers, "
                                f"lengths {cfg.length_dist} {cfg.len_lo}..{cfg.len_hi} (mean {float(lens_mid.mean()):.0f}), "
                                f"{cfg.chunk_bytes >> 10} KiB chunks shuffled in one pool of {n_chunks}, "
-                               "step = per layer map-ahead + append 1 token/request + decode",
+                               "step = per layer map-ahead + append 1 token/request + decode"
+                               + (" (one fused call)" if fused else " (two calls)"),
                    "global_batch": B, "layers": n_layers, "split_tokens": int(S), "work_items_per_layer": n_items,
                    "algorithmic_bytes_per_step": int(step_bytes)},
         "roofline": roofline, "cpu_baseline": cpu,

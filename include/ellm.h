@@ -183,6 +183,19 @@ int ellm_kv_append(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, co
 int ellm_decode_attention(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, const void* q,
                           void* out, float scale, void* stream);
 
+/* One decode iteration in a single pass (Sec. 3.1: every sequence writes one token, then attends
+ * over its whole context): the same tables, lengths, chunk bytes and output bits as
+ * ellm_kv_append(pool, ids, batch, NULL, k_new, v_new, stream) followed by
+ * ellm_decode_attention(pool, ids, batch, q, out, scale, stream), but the new K/V rows are taken
+ * from k_new / v_new by the attention kernel itself, which also writes them into their chunks, so
+ * no separate append kernel runs.
+ *   k_new, v_new (device): [batch][n_kv_heads][head_dim] bf16; q, out (device): [batch][n_q_heads][head_dim].
+ * Checks: batch < 0, NULL q / out, non-finite scale -> INVALID; then the checks of ellm_kv_append
+ * with one token per request; NULL k_new / v_new with batch > 0 -> INVALID; then the checks of
+ * ellm_decode_attention on the lengths after the append. A call that fails has changed nothing. */
+int ellm_kv_append_decode(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, const void* k_new,
+                          const void* v_new, const void* q, void* out, float scale, void* stream);
+
 /* Offload (Sec. 2.2.2): copy the chunks of slots [first_slot, first_slot + n_slots) to host
  * slots (lowest free host slot first, slots in ascending order), free the device chunks (owner
  * stays KV), entry := host code. Copies run on the library's side stream after everything

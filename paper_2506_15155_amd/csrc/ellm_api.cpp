@@ -208,14 +208,15 @@ int32_t wave_slots(ellm_pool* p) {
 // device's wave capacity, never on physical chunk ids or on which wave runs which piece: every
 // rounding is reproducible and invariant under remapping.
 // With an override (tests) all pieces have the given size and only the remainder is "small".
-void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0, int64_t ws_slot0, ellm::BatchArgs& a) {
+void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0, int64_t ws_slot0, ellm::BatchArgs& a,
+                 int32_t extra = 0) {
   const int32_t Tc = p->geom.tokens_per_chunk;
   const int32_t tpc = (Tc + ellm::TILE_TOKENS - 1) / ellm::TILE_TOKENS;
   int64_t total_tiles = 0;
   std::vector<int32_t>& tiles = p->tiles_tmp;
   tiles.resize(n_req);
   for (int32_t i = 0; i < n_req; i++) {
-    const int64_t len = p->core->tensor(ids[i])->len;
+    const int64_t len = p->core->tensor(ids[i])->len + extra;   // extra: tokens of a fused append
     const int64_t full = len / Tc, rem = len - full * Tc;
     tiles[i] = (int32_t)(full * tpc + (rem + ellm::TILE_TOKENS - 1) / ellm::TILE_TOKENS);
     total_tiles += tiles[i];
@@ -422,16 +423,11 @@ int ellm_pool_set_split_tokens(ellm_pool* p, int32_t split_tokens) {
   return ELLM_OK;
 }
 
-int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const void* q, void* out,
-                          float scale, void* stream_) {
-  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
-  if (batch < 0 || !q || !out || !std::isfinite(scale)) return set_err(ELLM_ERR_INVALID, "decode_attention: bad argument");
-  int rc = core_err(p, p->core->decode_check(ids, batch));
-  if (rc) return rc;
-  if (batch == 0) return ELLM_OK;
-  if (p->metadata_only) return set_err(ELLM_ERR_NO_DEVICE, "decode_attention: pool has no device");
-  hipStream_t stream = (hipStream_t)stream_;
-  rc = enter_compute(p, stream);
+// decode over `ids`; with k_new / v_new the one-token append is fused into the same launches
+static int decode_impl(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const void* q, const void* k_new,
+                       const void* v_new, void* out, float scale, hipStream_t stream) {
+  const int32_t extra = k_new ? 1 : 0;
+  int rc = enter_compute(p, stream);
   if (rc) return rc;
   if (scale == 0.f) scale = 1.0f / std::sqrt((float)p->geom.head_dim);
   const float scale_log2 = scale * 1.4426950408889634f;
@@ -443,7 +439,7 @@ int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch
   for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
     const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
     launches.emplace_back();
-    plan_launch(p, ids + b0, nb, b0, ws_slots, launches.back());
+    plan_launch(p, ids + b0, nb, b0, ws_slots, launches.back(), extra);
     ws_slots += launch_ws_slots(p, launches.back());
     const ellm::BatchArgs& la = launches.back();
     if (((int64_t)la.big_per_head + la.small_per_head) * p->geom.n_kv_heads > 0x7fffffffll || ws_slots > 0x7fffffffll)
@@ -456,7 +452,7 @@ int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch
   for (const ellm::BatchArgs& a : launches) {
     const bool prof = (size_t)(p->prof_used + 1) * 2 <= p->prof_ev.size();
     if (prof) HIP_TRY(hipEventRecord(p->prof_ev[2 * p->prof_used], stream), "hipEventRecord(profile)");
-    int e = ellm::launch_decode_partial(pv, q, p->d_ws, scale_log2, a, stream);
+    int e = ellm::launch_decode_partial(pv, q, k_new, v_new, p->d_ws, scale_log2, a, stream);
     if (e) return hip_err((hipError_t)e, "decode partial launch");
     if (prof) {
       HIP_TRY(hipEventRecord(p->prof_ev[2 * p->prof_used + 1], stream), "hipEventRecord(profile)");
@@ -465,6 +461,34 @@ int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch
     e = ellm::launch_decode_combine(pv, p->d_ws, out, a, stream);
     if (e) return hip_err((hipError_t)e, "decode combine launch");
   }
+  return ELLM_OK;
+}
+
+int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const void* q, void* out,
+                          float scale, void* stream_) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  if (batch < 0 || !q || !out || !std::isfinite(scale)) return set_err(ELLM_ERR_INVALID, "decode_attention: bad argument");
+  int rc = core_err(p, p->core->decode_check(ids, batch));
+  if (rc) return rc;
+  if (batch == 0) return ELLM_OK;
+  if (p->metadata_only) return set_err(ELLM_ERR_NO_DEVICE, "decode_attention: pool has no device");
+  return decode_impl(p, ids, batch, q, nullptr, nullptr, out, scale, (hipStream_t)stream_);
+}
+
+int ellm_kv_append_decode(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const void* k_new, const void* v_new,
+                          const void* q, void* out, float scale, void* stream_) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  if (batch < 0 || !q || !out || !std::isfinite(scale)) return set_err(ELLM_ERR_INVALID, "kv_append_decode: bad argument");
+  int rc = core_err(p, p->core->append_check(ids, batch, nullptr, p->n_eff, nullptr));
+  if (rc) return rc;
+  if (batch > 0 && (!k_new || !v_new)) return set_err(ELLM_ERR_INVALID, "kv_append_decode: NULL k_new / v_new");
+  rc = core_err(p, p->core->decode_check(ids, batch, 1));
+  if (rc) return rc;
+  if (batch == 0) return ELLM_OK;
+  if (p->metadata_only) return set_err(ELLM_ERR_NO_DEVICE, "kv_append_decode: pool has no device");
+  rc = decode_impl(p, ids, batch, q, k_new, v_new, out, scale, (hipStream_t)stream_);
+  if (rc) return rc;
+  p->core->append_commit(ids, batch, p->n_eff);
   return ELLM_OK;
 }
 

@@ -201,8 +201,9 @@ __device__ __forceinline__ Piece locate_piece(const PoolView& pv, const BatchArg
 // V of the tile is in flight while its scores are computed, K of the next tile while V is multiplied.
 // Scores are kept in log2 units (scale_log2 = scale * log2 e).
 // ---------------------------------------------------------------------------------------------
-template <int D, int G>
+template <int D, int G, bool APPEND>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_partial_kernel(PoolView pv, const uint16_t* __restrict__ q,
+                                                            const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
                                                             float* __restrict__ ws, float scale_log2,
                                                             int32_t g_first, BatchArgs a) {
   constexpr int LPR = D / 8;             // lanes per row = 16-byte pieces per row
@@ -324,6 +325,20 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
         for (int c = 0; c < QR; c++) qreg[i][c] = qsrc[i * (D / 2) + c * 16 + (lane & 15)];
     }
 
+    // Fused append: a.len counts the new token already, but its K/V row is still in k_new / v_new.
+    // The wave whose piece ends the sequence fetches that row (lane's 16-byte piece `sub` of each),
+    // puts it where the last tile's loads would have found it, and writes it to the chunk.
+    bool appends = false;
+    uint4 kn, vn;
+    if (APPEND) {
+      appends = tile0 + n_tiles == tiles_of(len, Tc, pv.tiles_per_chunk);
+      if (appends) {
+        const int64_t row16 = ((int64_t)(a.q_row0 + b) * pv.n_kv_heads + g) * LPR + sub;
+        kn = k_new[row16];
+        vn = v_new[row16];
+      }
+    }
+
     float m[G], l[G], acc[G][8];
 #pragma unroll
     for (int i = 0; i < G; i++) {
@@ -340,6 +355,18 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
       __builtin_amdgcn_wave_barrier();
       uint4 vr[NL];
       ELLM_LOAD_TILE(vr, kb + plane, nv)
+      if (APPEND && appends && it + 1 == n_tiles) {
+        // the new token is row nv - 1 of this tile: K goes into the LDS tile (same swizzle as the
+        // loads) and both rows go to the chunk; V replaces what the loads fetched for that row once
+        // they have arrived
+        const int rl = nv - 1;
+        if (rg == 0) {
+          *reinterpret_cast<uint4*>(sm_k + rl * ROWB + ((sub ^ (rl % LPR)) * 16)) = kn;
+          char* dst = const_cast<char*>(kb) + (uint32_t)rl * ROWB + sub * 16;
+          *reinterpret_cast<uint4*>(dst) = kn;
+          *reinterpret_cast<uint4*>(dst + plane) = vn;
+        }
+      }
       if (!q_settled) {
 #pragma unroll
         for (int i = 0; i < G; i++)
@@ -351,6 +378,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
       // V of this tile must have arrived now (it is the only load outstanding); then the K tile,
       // which has been consumed, is replaced by the next one while V is multiplied
       __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+      if (APPEND && appends && it + 1 == n_tiles) {
+#pragma unroll
+        for (int u = 0; u < NL; u++)
+          if (RPW * u + rg >= nv - 1) vr[u] = vn;
+      }
       if (it + 1 < n_tiles) {
         ELLM_NEXT_TILE()
         nv = nv_next;
@@ -555,10 +587,10 @@ static int group_step(int left) { return left >= 8 ? 8 : left >= 4 ? 4 : left >=
 template <int D>
 static const void* partial_kernel_ptr(int step) {
   switch (step) {
-    case 8: return (const void*)decode_partial_kernel<D, 8>;
-    case 4: return (const void*)decode_partial_kernel<D, 4>;
-    case 2: return (const void*)decode_partial_kernel<D, 2>;
-    default: return (const void*)decode_partial_kernel<D, 1>;
+    case 8: return (const void*)decode_partial_kernel<D, 8, true>;
+    case 4: return (const void*)decode_partial_kernel<D, 4, true>;
+    case 2: return (const void*)decode_partial_kernel<D, 2, true>;
+    default: return (const void*)decode_partial_kernel<D, 1, true>;
   }
 }
 
@@ -572,35 +604,39 @@ int partial_waves_per_cu(int head_dim, int group) {
 }
 
 template <int D, int G>
-static void launch_partial_t(const PoolView& pv, const void* q, float* ws, float scale_log2, int32_t g_first,
-                             const BatchArgs& a, hipStream_t stream) {
+static void launch_partial_t(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
+                             float scale_log2, int32_t g_first, const BatchArgs& a, hipStream_t stream) {
   const unsigned grid = (unsigned)((a.big_per_head + a.small_per_head) * pv.n_kv_heads);
-  hipLaunchKernelGGL((decode_partial_kernel<D, G>), dim3(grid), dim3(64), 0, stream, pv,
-                     (const uint16_t*)q, ws, scale_log2, g_first, a);
+  if (k_new)
+    hipLaunchKernelGGL((decode_partial_kernel<D, G, true>), dim3(grid), dim3(64), 0, stream, pv, (const uint16_t*)q,
+                       (const uint4*)k_new, (const uint4*)v_new, ws, scale_log2, g_first, a);
+  else
+    hipLaunchKernelGGL((decode_partial_kernel<D, G, false>), dim3(grid), dim3(64), 0, stream, pv, (const uint16_t*)q,
+                       nullptr, nullptr, ws, scale_log2, g_first, a);
 }
 
 // a group size that is not 8, 4, 2 or 1 is covered by several launches over the same K/V
 template <int D>
-static int launch_partial_d(const PoolView& pv, const void* q, float* ws, float scale_log2, const BatchArgs& a,
-                            hipStream_t stream) {
+static int launch_partial_d(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
+                            float scale_log2, const BatchArgs& a, hipStream_t stream) {
   int done = 0;
   while (done < pv.group) {
     const int step = group_step(pv.group - done);
-    if (step == 8) launch_partial_t<D, 8>(pv, q, ws, scale_log2, done, a, stream);
-    else if (step == 4) launch_partial_t<D, 4>(pv, q, ws, scale_log2, done, a, stream);
-    else if (step == 2) launch_partial_t<D, 2>(pv, q, ws, scale_log2, done, a, stream);
-    else launch_partial_t<D, 1>(pv, q, ws, scale_log2, done, a, stream);
+    if (step == 8) launch_partial_t<D, 8>(pv, q, k_new, v_new, ws, scale_log2, done, a, stream);
+    else if (step == 4) launch_partial_t<D, 4>(pv, q, k_new, v_new, ws, scale_log2, done, a, stream);
+    else if (step == 2) launch_partial_t<D, 2>(pv, q, k_new, v_new, ws, scale_log2, done, a, stream);
+    else launch_partial_t<D, 1>(pv, q, k_new, v_new, ws, scale_log2, done, a, stream);
     ELLM_HIP_CHECK_LAUNCH();
     done += step;
   }
   return 0;
 }
 
-int launch_decode_partial(const PoolView& pv, const void* q, float* ws, float scale_log2, const BatchArgs& a,
-                          hipStream_t stream) {
+int launch_decode_partial(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
+                          float scale_log2, const BatchArgs& a, hipStream_t stream) {
   if (a.n_req <= 0 || a.big_per_head + a.small_per_head <= 0) return 0;
-  return pv.head_dim == 128 ? launch_partial_d<128>(pv, q, ws, scale_log2, a, stream)
-                            : launch_partial_d<64>(pv, q, ws, scale_log2, a, stream);
+  return pv.head_dim == 128 ? launch_partial_d<128>(pv, q, k_new, v_new, ws, scale_log2, a, stream)
+                            : launch_partial_d<64>(pv, q, k_new, v_new, ws, scale_log2, a, stream);
 }
 
 int launch_decode_combine(const PoolView& pv, const float* ws, void* out, const BatchArgs& a, hipStream_t stream) {

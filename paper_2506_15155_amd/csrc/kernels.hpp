@@ -65,8 +65,11 @@ int partial_waves_per_cu(int head_dim, int group);
 int launch_table_patch(int32_t* table, const PatchArgs& a, hipStream_t stream);
 int launch_kv_append(const PoolView& pv, const void* k_new, const void* v_new, const AppendArgs& a,
                      hipStream_t stream);
-int launch_decode_partial(const PoolView& pv, const void* q, float* ws, float scale_log2, const BatchArgs& a,
-                          hipStream_t stream);
+// k_new / v_new non-NULL: fused append. a.len then counts one token per request whose K/V row
+// ([request][kv head][dim], rows q_row0 .. of the caller's batch) is still in k_new / v_new; the
+// kernel uses it from there and writes it into the chunk.
+int launch_decode_partial(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
+                          float scale_log2, const BatchArgs& a, hipStream_t stream);
 int launch_decode_combine(const PoolView& pv, const float* ws, void* out, const BatchArgs& a, hipStream_t stream);
 
 // calibration (measurement only)

@@ -218,15 +218,15 @@ void PoolCore::append_commit(const int32_t* ids, int32_t batch, const std::vecto
   for (int32_t b = 0; b < batch; b++) t_[ids[b]].len += n_eff[b];
 }
 
-int PoolCore::decode_check(const int32_t* ids, int32_t batch) {
+int PoolCore::decode_check(const int32_t* ids, int32_t batch, int32_t extra) {
   if (batch < 0 || (batch > 0 && !ids)) return fail(ERR_INVALID, "decode_attention: bad batch");
   const int64_t Tc = g_.tokens_per_chunk;
   for (int32_t b = 0; b < batch; b++) {
     const TensorRec* t = tensor(ids[b]);
     if (!t) return fail(ERR_INVALID, "decode_attention: bad tensor handle");
-    if (t->len == 0) return fail(ERR_EMPTY, "decode_attention: tensor holds no token");
+    if (t->len + extra == 0) return fail(ERR_EMPTY, "decode_attention: tensor holds no token");
     const int32_t* r = row(ids[b]);
-    for (int64_t s = 0; s <= (t->len - 1) / Tc; s++) {
+    for (int64_t s = 0; s <= (t->len + extra - 1) / Tc; s++) {
       if (r[s] == ENTRY_UNMAPPED) return fail(ERR_UNMAPPED, "decode_attention: slot has no chunk");
       if (r[s] <= -2) return fail(ERR_NOT_RESIDENT, "decode_attention: slot is in host memory");
     }

@@ -63,7 +63,8 @@ class PoolCore {
   int append_check(const int32_t* ids, int32_t batch, const int32_t* n_new, std::vector<int32_t>& n_eff,
                    int64_t* total);
   void append_commit(const int32_t* ids, int32_t batch, const std::vector<int32_t>& n_eff);
-  int decode_check(const int32_t* ids, int32_t batch);
+  // extra: tokens a not yet committed append adds to every request (0 or 1)
+  int decode_check(const int32_t* ids, int32_t batch, int32_t extra = 0);
 
   // offload / fetch: plan lists the moves in slot order; commit applies them
   int offload_plan(int32_t id, int32_t first, int32_t n, std::vector<Move>& moves);

@@ -91,6 +91,20 @@ class Both:
         torch.cuda.synchronize()
         return rc, out
 
+    def append_decode(self, ids, k_bits, v_bits, q_bits, scale=0.0):
+        """The fused call on the library; append then decode on the oracle (return codes must agree
+        when both steps succeed). Returns (rc, out_device, oracle_out)."""
+        kd, vd, qd = dev_bits(k_bits), dev_bits(v_bits), dev_bits(q_bits)
+        out = torch.empty_like(qd)
+        rc = E.ellm_kv_append_decode(self.pool, ids, kd, vd, qd, out, scale, check=False)
+        torch.cuda.synchronize()
+        ref = None
+        if self.orc is not None and rc == 0:
+            assert self.orc.append(ids, k_bits, v_bits) == 0
+            rco, ref = self.orc.decode(ids, q_bits, scale)
+            assert rco == 0
+        return rc, out, ref
+
     def offload(self, tid, first, n):
         return self.both("offload", lambda: E.ellm_chunk_deflate_to_host(self.pool, tid, first, n, check=False),
                          lambda: self.orc.offload(tid, first, n))

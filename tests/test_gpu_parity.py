@@ -184,6 +184,75 @@ def test_offload_fetch_remap_invariance_and_bytes():
     B.close()
 
 
+FUSED_CASES = {
+    "tiny": W.CONFIGS["tiny"],
+    **REDUCED,
+    "g3": W.Config("g3", 9, 5, 12, 4, 128, 24 * (2 * 4 * 128 * 2), 64, 24 * 12, "uniform", 1, 24 * 12),
+    "g5_d64": W.Config("g5", 9, 6, 10, 2, 64, 40 * (2 * 2 * 64 * 2), 64, 40 * 8, "uniform", 1, 40 * 8),
+}
+
+
+@pytest.mark.parametrize("name", sorted(FUSED_CASES))
+def test_fused_append_decode_equals_separate_calls(name):
+    """ellm_kv_append_decode against ellm_kv_append + ellm_decode_attention on a twin pool: same
+    output bits, same tables and lengths, same chunk bytes; and against the oracle."""
+    cfg = FUSED_CASES[name]
+    st = W.draw_step(cfg, seed=31)
+    owner = st.placement.owner if cfg.act_fraction > 0 else None
+    F = H.Both(cfg, owner=owner)
+    S = H.Both(cfg, owner=owner, oracle=False)
+    ids = H.load_step(F, st)
+    ids_s = H.load_step(S, st)
+    assert ids == ids_s
+    rc, out, ref = F.append_decode(ids, st.k_new, st.v_new, st.q)
+    assert rc == 0
+    assert S.append(ids, st.k_new, st.v_new) == 0
+    rc, sep = S.decode(ids, st.q)
+    assert rc == 0
+    assert torch.equal(out, sep), "fused and separate calls disagree"
+    H.check_close(out, ref, f"fused {name}")
+    F.compare_state()
+    for b, t in enumerate(ids):
+        tab, ln = E.ellm_tensor_get_table(F.pool, t)
+        assert ln == int(st.lens[b])
+        for c in tab[tab >= 0]:
+            assert np.array_equal(F.chunk_bytes_dev(int(c)), S.chunk_bytes_dev(int(c))), (b, int(c))
+    # a second fused step on top (the row written by the first must be read back from the chunk)
+    rng = np.random.default_rng(5)
+    room = [b for b in range(cfg.batch) if int(st.lens[b]) % cfg.tokens_per_chunk != 0]
+    sel = [ids[b] for b in room]
+    if sel:
+        k2 = W.normal_bf16(rng, (len(sel), cfg.n_kv_heads, cfg.head_dim))
+        v2 = W.normal_bf16(rng, (len(sel), cfg.n_kv_heads, cfg.head_dim))
+        q2 = W.normal_bf16(rng, (len(sel), cfg.n_q_heads, cfg.head_dim))
+        rc, out2, ref2 = F.append_decode(sel, k2, v2, q2)
+        assert rc == 0
+        H.check_close(out2, ref2, f"fused {name}, second step")
+        F.compare_state()
+    F.close()
+    S.close()
+
+
+def test_fused_append_decode_errors_change_nothing():
+    cfg = W.scaled(W.CONFIGS["tiny"], batch=2)
+    B = H.Both(cfg, max_tensors=4)
+    t = B.create(64)
+    u = B.create(64)
+    assert B.map(t, 0, 1) == 0
+    one = np.zeros((2, 8, 64), np.uint16)
+    k, q = H.dev_bits(one), H.dev_bits(one)
+    out = torch.full_like(q, 123)
+    # second request has no chunk: nothing may change for the first one either
+    assert E.ellm_kv_append_decode(B.pool, [t, u], k, k, q, out, check=False) == E.ERR.UNMAPPED
+    assert E.ellm_kv_append_decode(B.pool, [t, t], k, k, q, out, check=False) == E.ERR.INVALID
+    assert E.ellm_kv_append_decode(B.pool, [t], None, k, q, out, check=False) == E.ERR.INVALID
+    torch.cuda.synchronize()
+    assert (out == 123).all()
+    assert E.ellm_tensor_get_table(B.pool, t)[1] == 0
+    B.compare_state()
+    B.close()
+
+
 def test_error_paths_launch_nothing():
     cfg = W.scaled(W.CONFIGS["tiny"], batch=2, host_slots=4)
     B = H.Both(cfg)

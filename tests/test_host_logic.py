@@ -197,6 +197,45 @@ def test_failed_calls_change_nothing():
     P.close()
 
 
+def test_fused_append_decode_checks_on_host():
+    """The fused call validates like an append of one token each, then like a decode over the
+    lengths after it; when it fails, or has no device to run on, nothing has changed. Each code is
+    the one the oracle's pool gives for append-then-decode on the same state."""
+    P = Pair(n_chunks=8, n_host=2, max_tensors=3, max_slots=2)
+    t = E.ellm_tensor_create(P.lib, 32)
+    u = E.ellm_tensor_create(P.lib, 16)
+    P.orc.tensor_create(32)
+    P.orc.tensor_create(16)
+
+    def fused(ids, k=DUMMY, q=DUMMY):
+        return E.ellm_kv_append_decode(P.lib, ids, k, k, q, DUMMY, stream=0, check=False)
+
+    one = np.zeros((1, P.Hkv, P.D), np.uint16)
+    assert fused([t]) == E.ERR.UNMAPPED == P.orc.append([t], one, one)
+    assert E.ellm_tensor_map_chunks(P.lib, t, 0, 1, None, check=False) == 0 == P.orc.map_chunks(t, 0, 1, None, 0)
+    assert fused([t, u]) == E.ERR.UNMAPPED                 # the second request has no chunk
+    assert fused([t, t]) == E.ERR.INVALID
+    assert fused([t], k=None) == E.ERR.INVALID
+    assert fused([t], q=None) == E.ERR.INVALID
+    assert fused([7]) == E.ERR.INVALID
+    assert fused([]) == 0                                   # empty batch: nothing to do
+    assert fused([t]) == E.ERR.NO_DEVICE                    # all checks passed; no device to run on
+    assert E.ellm_tensor_get_table(P.lib, t)[1] == 0        # and the length was not advanced
+    # a slot below the new token that is on the host: the decode half of the checks catches it
+    assert E.ellm_tensor_map_chunks(P.lib, t, 1, 1, None, check=False) == 0 == P.orc.map_chunks(t, 1, 1, None, 0)
+    toks = np.zeros((16, P.Hkv, P.D), np.uint16)
+    assert E.ellm_kv_append(P.lib, [t], DUMMY, DUMMY, [16], stream=0, check=False) == 0 == P.orc.append([t], toks, toks, [16])
+    assert E.ellm_chunk_deflate_to_host(P.lib, t, 0, 1, check=False) == 0 == P.orc.offload(t, 0, 1)
+    assert fused([t]) == E.ERR.NOT_RESIDENT
+    assert P.orc.append([t], one, one) == 0 and P.orc.decode([t], np.zeros((1, 8, P.D), np.uint16))[0] == E.ERR.NOT_RESIDENT
+    assert E.ellm_tensor_get_table(P.lib, t)[1] == 16
+    # range: a tensor that is full
+    assert E.ellm_tensor_map_chunks(P.lib, u, 0, 1, None, check=False) == 0
+    assert E.ellm_kv_append(P.lib, [u], DUMMY, DUMMY, [16], stream=0, check=False) == 0
+    assert fused([u]) == E.ERR.RANGE
+    P.close()
+
+
 def test_pool_create_rejects_bad_geometry():
     ok = dict(device_buf=None, host_buf=None, chunk_bytes=32768, n_q_heads=8, n_kv_heads=8, head_dim=64,
               max_tensors=4, max_slots_per_tensor=4, flags=1, device_bytes=4 * 32768)
