@@ -255,6 +255,18 @@ void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0
   a.tiles_small = (int32_t)small;
   a.max_partials = most;
   a.ws_slot0 = (int32_t)ws_slot0;
+  a.pad = 0;
+  a.use_piece_req = big_prefix + small_prefix <= ellm::MAX_PIECE_REQ ? 1 : 0;
+  if (a.use_piece_req) {
+    std::memset(a.piece_req, 0, sizeof(a.piece_req));
+    for (int32_t i = 0; i < n_req; i++) {
+      for (int32_t k = a.big_prefix[i]; k < a.big_prefix[i + 1]; k++) a.piece_req[k >> 2] |= (uint32_t)i << ((k & 3) * 8);
+      for (int32_t k = a.small_prefix[i]; k < a.small_prefix[i + 1]; k++) {
+        const int32_t t = (int32_t)big_prefix + k;
+        a.piece_req[t >> 2] |= (uint32_t)i << ((t & 3) * 8);
+      }
+    }
+  }
 }
 
 int64_t launch_ws_slots(const ellm_pool* p, const ellm::BatchArgs& a) {

@@ -172,7 +172,12 @@ __device__ __forceinline__ Piece locate_piece(const PoolView& pv, const BatchArg
   p.g = idx / per_head;
   const int32_t rem = idx - p.g * per_head;
   const int32_t* prefix = small ? a.small_prefix : a.big_prefix;
-  p.b = find_request(prefix, a.n_req, rem, lane);
+  if (a.use_piece_req) {
+    const int32_t i = small ? a.big_per_head + rem : rem;
+    p.b = (a.piece_req[i >> 2] >> ((i & 3) * 8)) & 0xff;
+  } else {
+    p.b = find_request(prefix, a.n_req, rem, lane);
+  }
   const int32_t j = rem - prefix[p.b];
   const int32_t n_big = a.big_prefix[p.b + 1] - a.big_prefix[p.b];
   const int32_t tiles = tiles_of(a.len[p.b], pv.tokens_per_chunk, pv.tiles_per_chunk);

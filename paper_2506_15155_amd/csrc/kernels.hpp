@@ -7,6 +7,7 @@
 namespace ellm {
 
 constexpr int MAX_LAUNCH_REQ = 192;   // requests described by one launch's kernel arguments (4 KB in all)
+constexpr int MAX_PIECE_REQ = 512;    // pieces per kv head that the request lookup table covers
 constexpr int MAX_PATCH = 448;        // table entries patched by one launch
 constexpr int TILE_TOKENS = 64;       // rows of K (and V) one wave handles at a time
 constexpr int WS_ROW_PAD = 4;         // a partial row is head_dim accumulators, m, l and 2 unused floats
@@ -39,6 +40,11 @@ struct BatchArgs {
   int32_t tiles_big, tiles_small;
   int32_t max_partials;       // partial slots per (request, kv head) = most pieces any request has
   int32_t ws_slot0;           // first partial slot of this launch in the workspace
+  int32_t use_piece_req;      // piece_req is filled in (big_per_head + small_per_head <= MAX_PIECE_REQ)
+  int32_t pad;
+  // request of piece i of a kv head (big pieces first, then small ones), one byte each: lets a wave
+  // find its request with one scalar load instead of a search through the prefix arrays
+  uint32_t piece_req[MAX_PIECE_REQ / 4];
   int32_t tensor[MAX_LAUNCH_REQ];
   int32_t len[MAX_LAUNCH_REQ];
   int32_t big_prefix[MAX_LAUNCH_REQ + 1];
