@@ -40,7 +40,11 @@ def parse():
     ap.add_argument("--no-ceilings", action="store_true", help="skip the measured read ceilings")
     ap.add_argument("--separate-calls", action="store_true",
                     help="ellm_kv_append then ellm_decode_attention instead of the fused ellm_kv_append_decode")
-    ap.add_argument("--migration", action="store_true", help="also time offload / fetch of 25%% of the requests")
+    ap.add_argument("--migration", action="store_true",
+                    help="also time the elastic step: 25%% of the requests parked in pinned host memory, fetched and "
+                         "offloaded every step, all at once and layer by layer under the attention")
+    ap.add_argument("--prefill-append", type=int, default=0, metavar="N",
+                    help="also time a multi-token append of N tokens per request and layer")
     return ap.parse_args()
 
 
@@ -74,6 +78,10 @@ def main():
     slots_now = [int(-(-int(l) // Tc)) for l in lens0]
     need = n_layers * sum(slots_now)
     n_chunks = int(need * 1.15) + 64
+    if args.prefill_append:
+        n_chunks += n_layers * B * -(-args.prefill_append // Tc)
+    if args.migration:
+        n_chunks += 512        # room for the chunks of two layers' parked requests to be resident at once
     owner = np.zeros(n_chunks, np.uint8)
     owner[rng.random(n_chunks) < 0.125] = 1
     kv_ids = np.flatnonzero(owner == 0).astype(np.int32)
@@ -83,9 +91,10 @@ def main():
     n_host = 0
     host = None
     if args.migration:
-        n_host = 2 * max(slots_now) * (B // 4 + 1)
+        n_host = n_layers * sum(-(-(int(lens_final[b]) + 64) // Tc) for b in range(0, B, 4))
         host = torch.empty(n_host * cfg.chunk_bytes, dtype=torch.uint8, pin_memory=True)
-    pool = E.ellm_pool_create(dev, host, cfg.chunk_bytes, Hq, Hkv, D, n_layers * B, -(-max_tokens // Tc), owner)
+    pool = E.ellm_pool_create(dev, host, cfg.chunk_bytes, Hq, Hkv, D,
+                              n_layers * B * (2 if args.prefill_append else 1), -(-max_tokens // Tc), owner)
     if args.split:
         E.ellm_pool_set_split_tokens(pool, args.split)
 
@@ -131,19 +140,25 @@ def main():
     f_append, f_decode, f_fused = E.lib.ellm_kv_append, E.lib.ellm_decode_attention, E.lib.ellm_kv_append_decode
     fused = not args.separate_calls
 
-    def step():
+    def map_ahead():
         # a3: requests whose next token opens a new chunk get one mapped (inflating if needed)
         for b in np.flatnonzero(lens % Tc == 0):
             for l in range(n_layers):
                 E.ellm_tensor_map_chunks(pool, int(ids[l][b]), int(lens[b]) // Tc, 1, None, E.ELLM_MAP_ALLOW_INFLATE)
+
+    def layer_call(l):
+        if fused:
+            rc = f_fused(c_pool, c_ids[l], B, c_k[l], c_v[l], c_q[l], c_o[l], c_scale, c_stream)
+        else:
+            rc = f_append(c_pool, c_ids[l], B, None, c_k[l], c_v[l], c_stream)
+            rc |= f_decode(c_pool, c_ids[l], B, c_q[l], c_o[l], c_scale, c_stream)
+        if rc:
+            raise E.EllmError(rc, E.ellm_last_error())
+
+    def step():
+        map_ahead()
         for l in range(n_layers):
-            if fused:
-                rc = f_fused(c_pool, c_ids[l], B, c_k[l], c_v[l], c_q[l], c_o[l], c_scale, c_stream)
-            else:
-                rc = f_append(c_pool, c_ids[l], B, None, c_k[l], c_v[l], c_stream)
-                rc |= f_decode(c_pool, c_ids[l], B, c_q[l], c_o[l], c_scale, c_stream)
-            if rc:
-                raise E.EllmError(rc, E.ellm_last_error())
+            layer_call(l)
         lens[:] += 1
 
     for _ in range(Wm):
@@ -194,7 +209,10 @@ def main():
 
     mig = None
     if args.migration:
-        mig = time_migration(E, torch, pool, ids, lens, Tc, cfg, B)
+        mig = time_migration(E, torch, pool, ids, lens, Tc, cfg, B, n_layers, map_ahead, layer_call)
+    pre = None
+    if args.prefill_append:
+        pre = time_prefill_append(E, torch, pool, ids, lens, cfg, n_layers, args.prefill_append, max_tokens)
 
     res = {
         "metric": "decode-attention achieved HBM GB/s (% of peak) + tokens/s, chunk-backed KV, 1 GPU",
@@ -215,6 +233,8 @@ def main():
     }
     if mig:
         res["migration"] = mig
+    if pre:
+        res["prefill_append"] = pre
     E.ellm_pool_destroy(pool)
     print(json.dumps(res))
 
@@ -304,23 +324,136 @@ def cpu_baseline(cfg, lens0, oracle_hist, ab, lens_now, budget_s=15.0):
             "seconds": round(spent, 3), "tokens_per_s_per_layer": round(B * n_steps / spent, 2)}
 
 
-def time_migration(E, torch, pool, ids, lens, Tc, cfg, B):
-    """Offload then fetch all chunks of 25% of the requests of layer 0; GB/s each way."""
-    sel = list(range(0, B, 4))
-    slots = [int(-(-int(lens[b]) // Tc)) for b in sel]
-    nbytes = sum(slots) * cfg.chunk_bytes
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for b, s in zip(sel, slots):
-        E.ellm_chunk_deflate_to_host(pool, int(ids[0][b]), 0, s)
-    E.ellm_pool_sync(pool)
-    t1 = time.perf_counter()
-    for b, s in zip(sel, slots):
-        E.ellm_chunk_inflate_from_host(pool, int(ids[0][b]), 0, s)
-    E.ellm_pool_sync(pool)
-    t2 = time.perf_counter()
-    return {"requests": len(sel), "chunks": int(sum(slots)), "bytes": int(nbytes),
-            "offload_GBps": round(nbytes / (t1 - t0) / 1e9, 2), "fetch_GBps": round(nbytes / (t2 - t1) / 1e9, 2)}
+def time_migration(E, torch, pool, ids, lens, Tc, cfg, B, n_layers, map_ahead, layer_call):
+    """Two cases: every 4th request parked (the elastic configuration; the copies take far longer than
+    the step), and one request of median length parked (copies of the order of the step)."""
+    order = np.argsort(lens)
+    return {"quarter_of_requests": _time_migration(E, torch, pool, ids, lens, Tc, cfg, n_layers, map_ahead, layer_call,
+                                                   list(range(0, B, 4)), 3),
+            "one_median_request": _time_migration(E, torch, pool, ids, lens, Tc, cfg, n_layers, map_ahead, layer_call,
+                                                  [int(order[B // 2])], 10)}
+
+
+def _time_migration(E, torch, pool, ids, lens, Tc, cfg, n_layers, map_ahead, layer_call, sel, steps):
+    """The elastic step over all layers with every 4th request parked in pinned host memory between
+    steps: (a) no migration, (b) fetch everything, wait, run the step, offload everything, (c) layer by
+    layer: the fetch of layer l+1 is issued before layer l's attention and the offload of layer l
+    right after it, so the copies run on the side stream under the kernels."""
+
+    def slots(b, extra=0):
+        return int(-(-(int(lens[b]) + extra) // Tc))
+
+    def offload_layer(l, extra=0):
+        for b in sel:
+            E.ellm_chunk_deflate_to_host(pool, int(ids[l][b]), 0, slots(b, extra))
+
+    def fetch_layer(l):
+        for b in sel:
+            E.ellm_chunk_inflate_from_host(pool, int(ids[l][b]), 0, slots(b))
+
+    def sync():
+        E.ellm_pool_sync(pool)
+        torch.cuda.synchronize()
+
+    def timed(fn):
+        sync()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        sync()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    def plain():
+        map_ahead()
+        for l in range(n_layers):
+            layer_call(l)
+        lens[:] += 1
+
+    def copies_only():
+        for l in range(n_layers):
+            fetch_layer(l)
+        for l in range(n_layers):
+            offload_layer(l)
+
+    def blocking():
+        for l in range(n_layers):
+            fetch_layer(l)
+        E.ellm_pool_sync(pool)
+        map_ahead()
+        for l in range(n_layers):
+            layer_call(l)
+        torch.cuda.synchronize()
+        for l in range(n_layers):
+            offload_layer(l, 1)
+        lens[:] += 1
+
+    def layerwise():
+        map_ahead()
+        fetch_layer(0)
+        for l in range(n_layers):
+            if l + 1 < n_layers:
+                fetch_layer(l + 1)
+            layer_call(l)
+            offload_layer(l, 1)
+        lens[:] += 1
+
+    t_plain = timed(plain)
+    for l in range(n_layers):          # park the selected requests
+        offload_layer(l)
+    sync()
+    nbytes = sum(slots(b) for b in sel) * cfg.chunk_bytes * n_layers
+    t_copy = timed(copies_only)
+    t_block = timed(blocking)
+    t_layer = timed(layerwise)
+    for l in range(n_layers):          # leave everything resident
+        fetch_layer(l)
+    sync()
+    return {"parked_requests": len(sel), "bytes_each_way_per_step": int(nbytes),
+            "ms_step_no_migration": round(t_plain, 3), "ms_copies_only": round(t_copy, 3),
+            "ms_step_fetch_all_then_compute": round(t_block, 3), "ms_step_layerwise": round(t_layer, 3),
+            "pcie_GBps_both_ways_avg": round(2 * nbytes / (t_copy * 1e-3) / 1e9, 2),
+            "ms_hidden_by_layerwise": round(t_block - t_layer, 3)}
+
+
+def time_prefill_append(E, torch, pool, ids, lens, cfg, n_layers, n_tok, max_tokens):
+    """Multi-token append (the prefill-side write): n_tok tokens per request into fresh tensors of every
+    layer; GB/s counts the new K/V rows read and written."""
+    B, Tc = cfg.batch, cfg.tokens_per_chunk
+    n_tok = min(n_tok, max_tokens)
+    need = -(-n_tok // Tc)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(cfg.seed + 9)
+    k = torch.randn((B * n_tok, cfg.n_kv_heads, cfg.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+    v = torch.randn((B * n_tok, cfg.n_kv_heads, cfg.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+    counts = np.full(B, n_tok, np.int32)
+    times = []
+    for rep in range(3):
+        fresh = []
+        try:
+            for l in range(n_layers):
+                row = []
+                for b in range(B):
+                    t = E.ellm_tensor_create(pool, max_tokens)
+                    row.append(t)
+                    E.ellm_tensor_map_chunks(pool, t, 0, need, None, E.ELLM_MAP_ALLOW_INFLATE)
+                fresh.append(np.array(row, np.int32))
+        except E.EllmError as e:
+            for row in fresh:
+                for t in row:
+                    E.ellm_tensor_destroy(pool, int(t))
+            return {"skipped": f"pool has no room for the extra tensors ({e})"}
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for l in range(n_layers):
+            E.ellm_kv_append(pool, fresh[l], k, v, counts)
+        torch.cuda.synchronize()
+        times.append(time.perf_counter() - t0)
+        for row in fresh:
+            for t in row:
+                E.ellm_tensor_destroy(pool, int(t))
+    nbytes = 2 * 2 * B * n_tok * cfg.n_kv_heads * cfg.head_dim * 2 * n_layers
+    best = min(times)
+    return {"tokens_per_request": n_tok, "ms_all_layers": round(best * 1e3, 3), "GBps": round(nbytes / best / 1e9, 1)}
 
 
 if __name__ == "__main__":

@@ -198,9 +198,13 @@ int ellm_kv_append_decode(ellm_pool* pool, const ellm_tensor_id* ids, int32_t ba
 
 /* Offload (Sec. 2.2.2): copy the chunks of slots [first_slot, first_slot + n_slots) to host
  * slots (lowest free host slot first, slots in ascending order), free the device chunks (owner
- * stays KV), entry := host code. Copies run on the library's side stream after everything
- * enqueued so far on the last stream passed to append / decode; later append / decode calls wait
- * for them on their stream.
+ * stays KV), entry := host code. The copies run on a side stream of the library (offloads and
+ * fetches have one each, so the two directions overlap). Ordering is kept per chunk and per host
+ * slot: a copy waits for the append / decode calls already enqueued that touch its chunks (not
+ * for others: a copy for one tensor runs under the attention of another), and for earlier copies
+ * in the other direction through the same chunk or host slot; a later append / decode call waits,
+ * on its own stream, for the copies that touched its tensors' chunks. All append / decode calls
+ * of a pool are expected on one stream, or on streams the caller orders.
  * Checks: bad handle, n_slots < 0 -> INVALID; range -> RANGE; slots ascending: empty -> UNMAPPED,
  * already on host -> NOT_RESIDENT; fewer than n_slots free host slots -> HOST_FULL. */
 int ellm_chunk_deflate_to_host(ellm_pool* pool, ellm_tensor_id id, int32_t first_slot, int32_t n_slots);

@@ -50,12 +50,30 @@ struct ellm_pool {
   int32_t* d_table = nullptr;
   float* d_ws = nullptr;
   size_t ws_bytes = 0;
-  hipStream_t side = nullptr;          // migrations
-  hipEvent_t ev_compute = nullptr;     // "everything enqueued so far on the compute stream"
-  hipEvent_t ev_migrate = nullptr;     // "everything enqueued so far on the side stream"
-  bool migrate_pending = false;        // compute streams must wait for ev_migrate
+  hipStream_t side_in = nullptr;       // fetches (host -> device)
+  hipStream_t side_out = nullptr;      // offloads (device -> host): a stream of its own, so that the two
+                                       // directions use their own copy engines and run at the same time
   hipStream_t last_stream = nullptr;   // last stream given to append / decode
   bool have_last_stream = false;
+
+  // Ordering between the compute stream and the two side streams is kept per chunk and per host
+  // slot, so that a copy waits only for the kernels and copies that touched its chunks and a
+  // kernel only for the copies of its chunks: a fetch for the next layer runs under this layer's
+  // attention. Every compute call, fetch call and offload call gets a sequence number of its kind
+  // and records an event from that kind's ring after its work; a chunk (host slot) remembers the
+  // last call of each kind that touched it. Pools without host slots never migrate and skip it.
+  static constexpr int EV_RING = 256;
+  struct Ring {
+    std::vector<hipEvent_t> ev;
+    int64_t seq = 0;                   // calls of this kind so far = seq of the newest event
+  };
+  Ring r_compute, r_in, r_out;
+  std::vector<int64_t> chunk_compute, chunk_in, chunk_out;   // per chunk: seq of the last call of a kind, 0 = none
+  std::vector<int64_t> host_in, host_out;                    // per host slot: last fetch that read it, last offload that wrote it
+  // what each waiting stream already waits for, per ring (a stream is in order, so waiting for seq n covers all before)
+  int64_t compute_waits_in = 0, compute_waits_out = 0;
+  int64_t in_waits_compute = 0, in_waits_out = 0;
+  int64_t out_waits_compute = 0, out_waits_in = 0;
   int32_t split_override = 0;
   int32_t wave_slots = 0;              // resident partial-pass waves on the whole GPU (0 = not asked yet)
   int32_t tail_percent = 10;           // share of every request's tiles kept for small pieces (automatic cut)
@@ -102,9 +120,21 @@ int ensure_device(ellm_pool* p) {
   HIP_TRY(hipMalloc((void**)&p->d_table, bytes), "hipMalloc(table mirror)");
   HIP_TRY(hipMemcpy(p->d_table, p->core->table().data(), bytes, hipMemcpyHostToDevice), "hipMemcpy(table mirror)");
   (void)p->core->take_dirty();   // the full upload covers everything so far
-  HIP_TRY(hipStreamCreateWithFlags(&p->side, hipStreamNonBlocking), "hipStreamCreate(side)");
-  HIP_TRY(hipEventCreateWithFlags(&p->ev_compute, hipEventDisableTiming), "hipEventCreate");
-  HIP_TRY(hipEventCreateWithFlags(&p->ev_migrate, hipEventDisableTiming), "hipEventCreate");
+  HIP_TRY(hipStreamCreateWithFlags(&p->side_in, hipStreamNonBlocking), "hipStreamCreate(side)");
+  HIP_TRY(hipStreamCreateWithFlags(&p->side_out, hipStreamNonBlocking), "hipStreamCreate(side)");
+  if (p->geom.n_host_slots > 0) {
+    p->chunk_compute.assign(p->geom.n_chunks, 0);
+    p->chunk_in.assign(p->geom.n_chunks, 0);
+    p->chunk_out.assign(p->geom.n_chunks, 0);
+    p->host_in.assign(p->geom.n_host_slots, 0);
+    p->host_out.assign(p->geom.n_host_slots, 0);
+    for (ellm_pool::Ring* r : {&p->r_compute, &p->r_in, &p->r_out})
+      for (int i = 0; i < ellm_pool::EV_RING; i++) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming), "hipEventCreate");
+        r->ev.push_back(e);
+      }
+  }
   p->dev_ready = true;
   return ELLM_OK;
 }
@@ -135,13 +165,44 @@ int flush_table(ellm_pool* p, hipStream_t stream) {
   return ELLM_OK;
 }
 
-// things every compute call does before launching on `stream`
-int enter_compute(ellm_pool* p, hipStream_t stream) {
+bool tracks_chunks(const ellm_pool* p) { return p->geom.n_host_slots > 0; }
+
+// `waiter` waits for call `need` of ring r unless it already waits for that much. A seq the ring
+// no longer holds an event for is covered by the newest event of the same (in-order) stream.
+int wait_for(hipStream_t waiter, const ellm_pool::Ring& r, int64_t need, int64_t& waited) {
+  if (need <= waited) return ELLM_OK;
+  if (need <= r.seq - ellm_pool::EV_RING) need = r.seq;
+  HIP_TRY(hipStreamWaitEvent(waiter, r.ev[need % ellm_pool::EV_RING], 0), "hipStreamWaitEvent");
+  waited = need;
+  return ELLM_OK;
+}
+
+// a call of ring r's kind has enqueued its work on `stream`: number it and mark its end
+int record_on(ellm_pool::Ring& r, hipStream_t stream, int64_t* seq) {
+  *seq = ++r.seq;
+  HIP_TRY(hipEventRecord(r.ev[*seq % ellm_pool::EV_RING], stream), "hipEventRecord");
+  return ELLM_OK;
+}
+
+// Things every compute call does before launching on `stream`: wait for the copies that touched
+// the chunks of the tensors it works on, bring the device table up to date.
+int enter_compute(ellm_pool* p, hipStream_t stream, const int32_t* ids, int32_t batch) {
   int rc = ensure_device(p);
   if (rc) return rc;
-  if (p->migrate_pending) {
-    HIP_TRY(hipStreamWaitEvent(stream, p->ev_migrate, 0), "hipStreamWaitEvent(migration)");
-    p->migrate_pending = false;
+  if (p->have_last_stream && stream != p->last_stream) p->compute_waits_in = p->compute_waits_out = 0;
+  if (tracks_chunks(p) && (p->r_in.seq > p->compute_waits_in || p->r_out.seq > p->compute_waits_out)) {
+    int64_t need_in = 0, need_out = 0;
+    for (int32_t b = 0; b < batch; b++) {
+      const ellm::TensorRec* t = p->core->tensor(ids[b]);
+      const int32_t* r = p->core->row(ids[b]);
+      for (int32_t s = 0; s < t->n_slots; s++)
+        if (r[s] >= 0) {
+          need_in = std::max(need_in, p->chunk_in[r[s]]);
+          need_out = std::max(need_out, p->chunk_out[r[s]]);
+        }
+    }
+    if ((rc = wait_for(stream, p->r_in, need_in, p->compute_waits_in))) return rc;
+    if ((rc = wait_for(stream, p->r_out, need_out, p->compute_waits_out))) return rc;
   }
   rc = flush_table(p, stream);
   if (rc) return rc;
@@ -150,20 +211,50 @@ int enter_compute(ellm_pool* p, hipStream_t stream) {
   return ELLM_OK;
 }
 
-// side stream waits for everything enqueued so far on the last compute stream
-int enter_migration(ellm_pool* p) {
-  int rc = ensure_device(p);
+// after a compute call's launches: remember which chunks it touches and mark its end on the stream
+int leave_compute(ellm_pool* p, hipStream_t stream, const int32_t* ids, int32_t batch) {
+  if (!tracks_chunks(p)) return ELLM_OK;
+  int64_t seq;
+  int rc = record_on(p->r_compute, stream, &seq);
   if (rc) return rc;
-  if (p->have_last_stream) {
-    HIP_TRY(hipEventRecord(p->ev_compute, p->last_stream), "hipEventRecord(compute)");
-    HIP_TRY(hipStreamWaitEvent(p->side, p->ev_compute, 0), "hipStreamWaitEvent(compute)");
+  for (int32_t b = 0; b < batch; b++) {
+    const ellm::TensorRec* t = p->core->tensor(ids[b]);
+    const int32_t* r = p->core->row(ids[b]);
+    for (int32_t s = 0; s < t->n_slots; s++)
+      if (r[s] >= 0) p->chunk_compute[r[s]] = seq;
   }
   return ELLM_OK;
 }
 
-int leave_migration(ellm_pool* p) {
-  HIP_TRY(hipEventRecord(p->ev_migrate, p->side), "hipEventRecord(migration)");
-  p->migrate_pending = true;
+// An offload reads device chunks and writes host slots; a fetch reads host slots and overwrites
+// device chunks. Its stream waits for the kernels that touched those chunks (the last reader of
+// a chunk about to be overwritten may still run) and for the copies of the other direction that
+// touched the same chunks or host slots.
+int enter_migration(ellm_pool* p, const std::vector<ellm::Move>& moves, bool fetch) {
+  int rc = ensure_device(p);
+  if (rc) return rc;
+  int64_t need_compute = 0, need_other = 0;
+  for (const ellm::Move& m : moves) {
+    need_compute = std::max(need_compute, p->chunk_compute[m.chunk]);
+    if (fetch) need_other = std::max({need_other, p->chunk_out[m.chunk], p->host_out[m.host_slot]});
+    else need_other = std::max({need_other, p->chunk_in[m.chunk], p->host_in[m.host_slot]});
+  }
+  if (fetch) {
+    if ((rc = wait_for(p->side_in, p->r_compute, need_compute, p->in_waits_compute))) return rc;
+    return wait_for(p->side_in, p->r_out, need_other, p->in_waits_out);
+  }
+  if ((rc = wait_for(p->side_out, p->r_compute, need_compute, p->out_waits_compute))) return rc;
+  return wait_for(p->side_out, p->r_in, need_other, p->out_waits_in);
+}
+
+int leave_migration(ellm_pool* p, const std::vector<ellm::Move>& moves, bool fetch) {
+  int64_t seq;
+  int rc = fetch ? record_on(p->r_in, p->side_in, &seq) : record_on(p->r_out, p->side_out, &seq);
+  if (rc) return rc;
+  for (const ellm::Move& m : moves) {
+    (fetch ? p->chunk_in : p->chunk_out)[m.chunk] = seq;
+    (fetch ? p->host_in : p->host_out)[m.host_slot] = seq;
+  }
   return ELLM_OK;
 }
 
@@ -330,11 +421,13 @@ int ellm_pool_destroy(ellm_pool* p) {
   if (!p) return set_err(ELLM_ERR_INVALID, "pool_destroy: NULL pool");
   int rc = ELLM_OK;
   if (p->dev_ready) {
-    if (hipStreamSynchronize(p->side) != hipSuccess) rc = ELLM_ERR_HIP;
+    if (hipStreamSynchronize(p->side_in) != hipSuccess) rc = ELLM_ERR_HIP;
+    if (hipStreamSynchronize(p->side_out) != hipSuccess) rc = ELLM_ERR_HIP;
     if (p->have_last_stream && hipStreamSynchronize(p->last_stream) != hipSuccess) rc = ELLM_ERR_HIP;
-    (void)hipStreamDestroy(p->side);
-    (void)hipEventDestroy(p->ev_compute);
-    (void)hipEventDestroy(p->ev_migrate);
+    (void)hipStreamDestroy(p->side_in);
+    (void)hipStreamDestroy(p->side_out);
+    for (ellm_pool::Ring* r : {&p->r_compute, &p->r_in, &p->r_out})
+      for (hipEvent_t e : r->ev) (void)hipEventDestroy(e);
     (void)hipFree(p->d_table);
     for (hipEvent_t e : p->prof_ev) (void)hipEventDestroy(e);
     if (p->d_ws) (void)hipFree(p->d_ws);
@@ -384,7 +477,7 @@ int ellm_kv_append(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const
   if (total > 0x7fffffffll / (2 * p->geom.n_kv_heads)) return set_err(ELLM_ERR_RANGE, "kv_append: too many tokens in one call");
   if (total > 0 && !p->metadata_only) {
     hipStream_t stream = (hipStream_t)stream_;
-    rc = enter_compute(p, stream);
+    rc = enter_compute(p, stream, ids, batch);
     if (rc) return rc;
     const ellm::PoolView pv = view_of(p);
     const size_t tok_bytes = (size_t)p->geom.n_kv_heads * p->geom.head_dim * 2;
@@ -406,6 +499,8 @@ int ellm_kv_append(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const
       if (e) return hip_err((hipError_t)e, "kv_append launch");
       row0 += t;
     }
+    rc = leave_compute(p, stream, ids, batch);
+    if (rc) return rc;
   }
   p->core->append_commit(ids, batch, p->n_eff);
   return ELLM_OK;
@@ -439,7 +534,7 @@ int ellm_pool_set_split_tokens(ellm_pool* p, int32_t split_tokens) {
 static int decode_impl(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const void* q, const void* k_new,
                        const void* v_new, void* out, float scale, hipStream_t stream) {
   const int32_t extra = k_new ? 1 : 0;
-  int rc = enter_compute(p, stream);
+  int rc = enter_compute(p, stream, ids, batch);
   if (rc) return rc;
   if (scale == 0.f) scale = 1.0f / std::sqrt((float)p->geom.head_dim);
   const float scale_log2 = scale * 1.4426950408889634f;
@@ -473,7 +568,7 @@ static int decode_impl(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, c
     e = ellm::launch_decode_combine(pv, p->d_ws, out, a, stream);
     if (e) return hip_err((hipError_t)e, "decode combine launch");
   }
-  return ELLM_OK;
+  return leave_compute(p, stream, ids, batch);
 }
 
 int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const void* q, void* out,
@@ -509,13 +604,13 @@ int ellm_chunk_deflate_to_host(ellm_pool* p, ellm_tensor_id id, int32_t first_sl
   int rc = core_err(p, p->core->offload_plan(id, first_slot, n_slots, p->moves));
   if (rc) return rc;
   if (!p->moves.empty() && !p->metadata_only) {
-    rc = enter_migration(p);
+    rc = enter_migration(p, p->moves, false);
     if (rc) return rc;
     const size_t cb = p->geom.chunk_bytes;
     for (const ellm::Move& m : p->moves)
       HIP_TRY(hipMemcpyAsync(p->host_base + (size_t)m.host_slot * cb, p->device_base + (size_t)m.chunk * cb, cb,
-                             hipMemcpyDeviceToHost, p->side), "hipMemcpyAsync(offload)");
-    rc = leave_migration(p);
+                             hipMemcpyDeviceToHost, p->side_out), "hipMemcpyAsync(offload)");
+    rc = leave_migration(p, p->moves, false);
     if (rc) return rc;
   }
   p->core->offload_commit(id, p->moves);
@@ -528,13 +623,13 @@ int ellm_chunk_inflate_from_host(ellm_pool* p, ellm_tensor_id id, int32_t first_
   int rc = core_err(p, p->core->fetch_plan(id, first_slot, n_slots, chunk_ids, p->moves));
   if (rc) return rc;
   if (!p->moves.empty() && !p->metadata_only) {
-    rc = enter_migration(p);
+    rc = enter_migration(p, p->moves, true);
     if (rc) return rc;
     const size_t cb = p->geom.chunk_bytes;
     for (const ellm::Move& m : p->moves)
       HIP_TRY(hipMemcpyAsync(p->device_base + (size_t)m.chunk * cb, p->host_base + (size_t)m.host_slot * cb, cb,
-                             hipMemcpyHostToDevice, p->side), "hipMemcpyAsync(fetch)");
-    rc = leave_migration(p);
+                             hipMemcpyHostToDevice, p->side_in), "hipMemcpyAsync(fetch)");
+    rc = leave_migration(p, p->moves, true);
     if (rc) return rc;
   }
   p->core->fetch_commit(id, p->moves);
@@ -544,7 +639,8 @@ int ellm_chunk_inflate_from_host(ellm_pool* p, ellm_tensor_id id, int32_t first_
 int ellm_pool_sync(ellm_pool* p) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
   if (!p->dev_ready) return ELLM_OK;
-  HIP_TRY(hipStreamSynchronize(p->side), "hipStreamSynchronize(side)");
+  HIP_TRY(hipStreamSynchronize(p->side_in), "hipStreamSynchronize(side)");
+  HIP_TRY(hipStreamSynchronize(p->side_out), "hipStreamSynchronize(side)");
   return ELLM_OK;
 }
 
@@ -633,7 +729,7 @@ int ellm_debug_kv_stream_read(ellm_pool* p, const ellm_tensor_id* ids, int32_t b
   if (batch == 0) return ELLM_OK;
   if (p->metadata_only) return set_err(ELLM_ERR_NO_DEVICE, "debug_kv_stream_read: pool has no device");
   hipStream_t stream = (hipStream_t)stream_;
-  rc = enter_compute(p, stream);
+  rc = enter_compute(p, stream, ids, batch);
   if (rc) return rc;
   const ellm::PoolView pv = view_of(p);
   ellm::BatchArgs a;
@@ -643,7 +739,7 @@ int ellm_debug_kv_stream_read(ellm_pool* p, const ellm_tensor_id* ids, int32_t b
     int e = ellm::launch_kv_stream(pv, (uint32_t*)sink, a, stream);
     if (e) return hip_err((hipError_t)e, "kv stream launch");
   }
-  return ELLM_OK;
+  return leave_compute(p, stream, ids, batch);
 }
 
 int ellm_debug_set_partition(ellm_pool* p, int32_t tail_percent, int32_t small_tiles) {

@@ -253,6 +253,88 @@ def test_fused_append_decode_errors_change_nothing():
     B.close()
 
 
+def test_layerwise_fetch_under_attention():
+    """Several layers in one pool, a third of the requests parked in host memory. Per step and layer:
+    the fetch of the next layer's chunks is issued before this layer's attention, the offload of this
+    layer's chunks right after it, and the freed chunks are reused at once by a scratch tensor. The
+    side stream and the compute stream are ordered per chunk only, so any missing wait shows up as
+    poison or stale rows. Checked against a twin pool that never migrates (same bits), the oracle
+    (tolerance, tables, host bytes)."""
+    n_layers = 3
+    base = W.scaled(W.CONFIGS["llama8b"], batch=9, n_chunks=160, len_lo=300, len_hi=1400, lognormal_median=700,
+                    host_slots=40)
+    st = W.draw_step(base, seed=41, extra_slots=0)
+    Bq, Tc = base.batch, base.tokens_per_chunk
+    M = H.Both(base, max_tensors=n_layers * Bq + 1)
+    T = H.Both(base, oracle=False, max_tensors=n_layers * Bq + 1)
+    rng = np.random.default_rng(43)
+    free = list(rng.permutation(base.n_chunks).astype(np.int32))
+    ids = []
+    for l in range(n_layers):
+        row = []
+        for b in range(Bq):
+            n = -(-int(st.lens[b]) // Tc)
+            cid = np.array([free.pop() for _ in range(n)], np.int32)
+            tm, tt = M.create(base.max_tokens), T.create(base.max_tokens)
+            assert tm == tt
+            assert M.map(tm, 0, n, cid) == 0 and T.map(tt, 0, n, cid) == 0
+            k = W.normal_bf16(rng, (int(st.lens[b]) - 1, base.n_kv_heads, base.head_dim))
+            v = W.normal_bf16(rng, (int(st.lens[b]) - 1, base.n_kv_heads, base.head_dim))
+            assert M.append([tm], k, v, [int(st.lens[b]) - 1]) == 0 and T.append([tt], k, v, [int(st.lens[b]) - 1]) == 0
+            row.append(tm)
+        ids.append(row)
+    scratch = M.create(Tc)
+    T.create(Tc)
+    parked = [0, 4, 7]
+    lens = st.lens.copy() - 1
+    n_slots = lambda b: -(-int(lens[b]) // Tc)
+    for l in range(n_layers):
+        for b in parked:
+            assert M.offload(ids[l][b], 0, n_slots(b)) == 0
+    M.compare_state()
+    shape = (Bq, base.n_kv_heads, base.head_dim)
+    for step in range(3):
+        for b in parked:
+            assert M.fetch(ids[0][b], 0, n_slots(b)) == 0
+        for l in range(n_layers):
+            if l + 1 < n_layers:
+                for b in parked:                       # next layer's chunks start moving now
+                    assert M.fetch(ids[l + 1][b], 0, n_slots(b)) == 0
+            k1, v1 = W.normal_bf16(rng, shape), W.normal_bf16(rng, shape)
+            q = W.normal_bf16(rng, (Bq, base.n_q_heads, base.head_dim))
+            rc, out, ref = M.append_decode(ids[l], k1, v1, q)
+            assert rc == 0
+            rct, twin, _ = T.append_decode(ids[l], k1, v1, q)
+            assert rct == 0
+            assert torch.equal(out, twin), f"step {step} layer {l}: migrating pool differs from the twin"
+            H.check_close(out, ref, f"step {step} layer {l}")
+            for b in parked:                           # and this layer's go back to the host
+                assert M.offload(ids[l][b], 0, -(-(int(lens[b]) + 1) // Tc)) == 0
+            # reuse a chunk the offload has just freed: the copy must have read it before the append writes
+            assert M.map(scratch, 0, 1) == 0
+            junk = W.normal_bf16(rng, (5, base.n_kv_heads, base.head_dim))
+            assert M.append([scratch], junk, junk, [5]) == 0
+            assert E.ellm_tensor_destroy(M.pool, scratch, check=False) == 0 == M.orc.tensor_destroy(scratch)
+            M.ids.remove(scratch)
+            assert M.create(Tc) == scratch
+        lens += 1
+        E.ellm_pool_sync(M.pool)
+        torch.cuda.synchronize()
+        M.compare_state()
+        th, sh = E.ellm_pool_get_host_slots(M.pool)
+        for hs in np.flatnonzero(th >= 0)[:6]:          # parked bytes equal the oracle's image of them
+            got, want = M.host_slot_bytes(int(hs)), M.orc.host_slot_bytes(int(hs))
+            used = 2 * base.n_kv_heads * Tc * base.head_dim * 2
+            t_id, t_slot = int(th[hs]), int(sh[hs])
+            b = ids[t_id // Bq].index(t_id) if t_id in ids[t_id // Bq] else None
+            rows = min(Tc, int(lens[b]) - t_slot * Tc)
+            g = got[:used].reshape(base.n_kv_heads * 2, Tc, base.head_dim * 2)
+            w = want[:used].reshape(base.n_kv_heads * 2, Tc, base.head_dim * 2)
+            assert np.array_equal(g[:, :rows], w[:, :rows])
+    M.close()
+    T.close()
+
+
 def test_error_paths_launch_nothing():
     cfg = W.scaled(W.CONFIGS["tiny"], batch=2, host_slots=4)
     B = H.Both(cfg)
