@@ -115,31 +115,33 @@ __global__ void table_patch_kernel(int32_t* table, PatchArgs a) {
 template <int D>
 __global__ __launch_bounds__(256) void kv_append_kernel(PoolView pv, const uint4* __restrict__ k_new,
                                                         const uint4* __restrict__ v_new, AppendArgs a) {
-  constexpr int LPR = D * 2 / 16;            // lanes per row (16 bytes each)
-  constexpr int ROWS = 256 / LPR;            // rows per block
-  const int sub = threadIdx.x % LPR;
-  const int64_t row = (int64_t)blockIdx.x * ROWS + threadIdx.x / LPR;
-  const int64_t total_rows = (int64_t)a.total_new * pv.n_kv_heads * 2;
-  if (row >= total_rows) return;
-  const int per_tok = pv.n_kv_heads * 2;
-  const int32_t tau = (int32_t)(row / per_tok);       // index of the new token in the launch
-  const int rem = (int)(row - (int64_t)tau * per_tok);
-  const int h = rem >> 1, plane = rem & 1;
-  // request that owns token tau: largest b with tok0[b] <= tau
-  int lo = 0, hi = a.n_req - 1;
+  // One workgroup per new token: which request it belongs to, its position and its chunk are the
+  // same for every lane, so they are found once with scalar loads. The lanes then copy the token's
+  // 2 * n_kv_heads rows (K and V of every head), 16 bytes each per turn.
+  constexpr int LPR = D * 2 / 16;            // 16-byte pieces per row
+  const int32_t tau = blockIdx.x;            // index of the new token in the launch
+  int lo = 0, hi = a.n_req - 1;              // request that owns it: largest b with tok0[b] <= tau
   while (lo < hi) {
-    int mid = (lo + hi + 1) >> 1;
+    const int mid = (lo + hi + 1) >> 1;
     if (a.tok0[mid] <= tau) lo = mid; else hi = mid - 1;
   }
   const int b = lo;
   const int64_t pos = (int64_t)a.len_before[b] + (tau - a.tok0[b]);
   const int32_t slot = (int32_t)(pos / pv.tokens_per_chunk);
   const int32_t r = (int32_t)(pos - (int64_t)slot * pv.tokens_per_chunk);
-  const int32_t chunk = pv.table[(int64_t)a.tensor[b] * pv.max_slots + slot];
-  const uint4* src = (plane ? v_new : k_new) + ((int64_t)tau * pv.n_kv_heads + h) * LPR + sub;
-  char* dst = pv.base + (uint64_t)chunk * pv.chunk_bytes +
-              ((uint64_t)(h * 2 + plane) * pv.tokens_per_chunk + r) * (D * 2) + sub * 16;
-  *reinterpret_cast<uint4*>(dst) = *src;
+  const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)a.tensor[b] * pv.max_slots);
+  char* chunk = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + (uint64_t)r * (D * 2);
+  const uint64_t plane_bytes = (uint64_t)pv.tokens_per_chunk * (D * 2);
+  const int n16 = pv.n_kv_heads * LPR;       // 16-byte pieces of the token's K (and of its V)
+  const uint4* ks = k_new + (int64_t)tau * n16;
+  const uint4* vs = v_new + (int64_t)tau * n16;
+  for (int i = threadIdx.x; i < n16; i += 256) {
+    const int h = i / LPR, sub = i - h * LPR;
+    char* dst = chunk + (uint64_t)(h * 2) * plane_bytes + sub * 16;
+    const uint4 kv = ks[i], vv = vs[i];
+    *reinterpret_cast<uint4*>(dst) = kv;
+    *reinterpret_cast<uint4*>(dst + plane_bytes) = vv;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -572,16 +574,12 @@ int launch_table_patch(int32_t* table, const PatchArgs& a, hipStream_t stream) {
 int launch_kv_append(const PoolView& pv, const void* k_new, const void* v_new, const AppendArgs& a,
                      hipStream_t stream) {
   if (a.total_new <= 0) return 0;
-  const int64_t total_rows = (int64_t)a.total_new * pv.n_kv_heads * 2;
-  if (pv.head_dim == 128) {
-    const int64_t blocks = (total_rows + 15) / 16;
-    hipLaunchKernelGGL(kv_append_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, stream, pv,
+  if (pv.head_dim == 128)
+    hipLaunchKernelGGL(kv_append_kernel<128>, dim3((unsigned)a.total_new), dim3(256), 0, stream, pv,
                        (const uint4*)k_new, (const uint4*)v_new, a);
-  } else {
-    const int64_t blocks = (total_rows + 31) / 32;
-    hipLaunchKernelGGL(kv_append_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, stream, pv,
+  else
+    hipLaunchKernelGGL(kv_append_kernel<64>, dim3((unsigned)a.total_new), dim3(256), 0, stream, pv,
                        (const uint4*)k_new, (const uint4*)v_new, a);
-  }
   ELLM_HIP_CHECK_LAUNCH();
   return 0;
 }
