@@ -143,6 +143,48 @@ int ellm_tensor_map_chunks(ellm_pool* pool, ellm_tensor_id id, int32_t first_slo
  * -> INVALID; an empty slot -> UNMAPPED. */
 int ellm_tensor_unmap_chunks(ellm_pool* pool, ellm_tensor_id id, int32_t first_slot, int32_t n_slots);
 
+/* ---- request turnover (Sec. 2.1.2 "Memory Management Strategy"; Sec. 3.1 pre-mapping) --------- */
+
+/* The request is over (Sec. 2.1.2): the tensor is not unmapped but becomes "mapped and available".
+ * Its length drops to 0; its leading run of slots that have a device chunk stays mapped (that run,
+ * times T_c, is its mapped size); whatever lies behind the first slot without a device chunk (host
+ * copies, stray mappings) is given back. A released tensor takes no call except
+ * ellm_tensor_acquire (as a candidate), ellm_tensor_destroy, ellm_tensor_get_table and
+ * ellm_tensor_is_released; every other call on it -> INVALID.
+ * Checks: bad or already released handle -> INVALID. */
+int ellm_tensor_release(ellm_pool* pool, ellm_tensor_id id);
+
+/* A new request that needs room for need_tokens now and max_tokens at most. Best fit (the arg min
+ * of Sec. 2.1.2): of the released tensors whose max_tokens is at least the one asked for and whose
+ * mapped size is at least need_tokens, the one with the smallest mapped size; equal sizes: the
+ * lowest handle. It becomes live again with length 0 and its own max_tokens; no mapping changes,
+ * nothing to do on the device. Without such a tensor, on-demand mapping: a fresh tensor (lowest
+ * free handle) gets ceil(need_tokens / T_c) chunks in slots 0.., taken in this order: FREE KV
+ * chunks ascending; then chunks taken back from released tensors (smallest mapped size first,
+ * equal sizes lowest handle first, each from its last mapped slot downwards); then, with
+ * ELLM_MAP_ALLOW_INFLATE, FREE ACT chunks ascending. All or nothing.
+ * Checks: need_tokens < 0, max_tokens < 1, need_tokens > max_tokens, unknown flag -> INVALID;
+ * max_tokens needs more than max_slots_per_tensor slots -> RANGE; on-demand: no free handle, or
+ * too few chunks -> OOM. */
+int ellm_tensor_acquire(ellm_pool* pool, int64_t need_tokens, int64_t max_tokens, uint32_t flags,
+                        ellm_tensor_id* out);
+
+/* 1 if the tensor is released, 0 if it is live; bad handle -> INVALID. */
+int ellm_tensor_is_released(ellm_pool* pool, ellm_tensor_id id);
+
+/* Speculative pre-mapping (Sec. 3.1): every sequence is assumed to produce one more token, so each
+ * listed tensor whose next token would open a slot that has no chunk (len < max_tokens,
+ * len % T_c == 0, slot len / T_c empty) gets one mapped now, pool-chosen as in
+ * ellm_tensor_map_chunks, in batch order. All or nothing; *n_mapped (may be NULL) = chunks mapped.
+ * Checks: batch < 0, bad / released / repeated handle, unknown flag -> INVALID; too few chunks -> OOM. */
+int ellm_kv_premap_next(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, uint32_t flags,
+                        int32_t* n_mapped);
+
+/* Push the table changes made so far to the device mirror now, ordered on `stream`, instead of at
+ * the start of the next append / decode call: with ellm_kv_premap_next this moves the mapping
+ * work of the next step out of its way (Sec. 3.1). No-op on a metadata-only pool. */
+int ellm_pool_flush_tables(ellm_pool* pool, void* stream);
+
 /* Ownership transfer of FREE chunks between the two sides of the pool (Sec. 2.2.1 step 3 for
  * new_owner = KV, "deflation" for new_owner = ACT). A chunk that already has new_owner is left
  * as it is. Checks: n < 0 or bad owner -> INVALID; per id in order: outside pool -> RANGE,

@@ -55,6 +55,7 @@ enum { ST_FREE = 0, ST_MAPPED = 1, ST_BUSY = 2 };
 
 typedef struct {
   int used;
+  int released;        /* mapped and available: waits for a new request (Sec. 2.1.2) */
   int64_t max_tokens, len;
   int32_t n_slots;
   int32_t* table;      /* n_slots entries                                     */
@@ -145,9 +146,16 @@ void orc_pool_destroy(orc_pool* p) {
 
 int32_t orc_tokens_per_chunk(const orc_pool* p) { return p->tokens_per_chunk; }
 
-static orc_tensor* tensor_of(orc_pool* p, int32_t id) {
+/* any tensor record in use, released or not */
+static orc_tensor* tensor_any(orc_pool* p, int32_t id) {
   if (id < 0 || id >= p->max_tensors || !p->t[id].used) return NULL;
   return &p->t[id];
+}
+
+/* a tensor that belongs to a request: released ones take no call but acquire / destroy / read-out */
+static orc_tensor* tensor_of(orc_pool* p, int32_t id) {
+  orc_tensor* t = tensor_any(p, id);
+  return (t && !t->released) ? t : NULL;
 }
 
 /* reserve a virtual range; lowest unused handle */
@@ -178,7 +186,7 @@ static void release_entry(orc_pool* p, int32_t e) {
 }
 
 int orc_tensor_destroy(orc_pool* p, int32_t id) {
-  orc_tensor* t = tensor_of(p, id);
+  orc_tensor* t = tensor_any(p, id);
   if (!t) return ORC_INVALID;
   for (int32_t s = 0; s < t->n_slots; s++) release_entry(p, t->table[s]);
   free(t->table); free(t->twin_k); free(t->twin_v);
@@ -244,6 +252,147 @@ int orc_tensor_unmap_chunks(orc_pool* p, int32_t id, int32_t first, int32_t n) {
   if (first < live) return ORC_INVALID;
   for (int32_t i = 0; i < n; i++) if (t->table[first + i] == ENTRY_NONE) return ORC_UNMAPPED;
   for (int32_t i = 0; i < n; i++) { release_entry(p, t->table[first + i]); t->table[first + i] = ENTRY_NONE; }
+  return ORC_OK;
+}
+
+/* ---- request turnover (Sec. 2.1.2 "Memory Management Strategy", Sec. 3.1 pre-mapping) -------- */
+
+/* tokens a tensor can take without any new mapping: its leading run of device-resident slots */
+static int32_t mapped_run(const orc_tensor* t) {
+  int32_t run = 0;
+  while (run < t->n_slots && t->table[run] >= 0) run++;
+  return run;
+}
+
+/* The request is over: the tensor keeps its leading mapped slots and becomes available. What lies
+ * behind the first slot without a device chunk (host copies, stray mappings) is given back. */
+int orc_tensor_release(orc_pool* p, int32_t id) {
+  orc_tensor* t = tensor_of(p, id);
+  if (!t) return ORC_INVALID;
+  int32_t keep = mapped_run(t);
+#if ORC_MUTANT == 12
+  keep = 0;                                                                /* nothing retained */
+#endif
+  for (int32_t s = keep; s < t->n_slots; s++) {
+    release_entry(p, t->table[s]);
+    t->table[s] = ENTRY_NONE;
+  }
+  t->len = 0;
+  t->released = 1;
+  return ORC_OK;
+}
+
+int orc_tensor_is_released(orc_pool* p, int32_t id) {
+  orc_tensor* t = tensor_any(p, id);
+  return t ? t->released : ORC_INVALID;
+}
+
+/* A new request that needs room for `need` tokens now and `max_tokens` at most. Best fit: of the
+ * available tensors whose virtual range suffices and whose mapped size is at least `need`, the one
+ * with the smallest mapped size (the paper's arg min); equal sizes: the lowest handle. Without
+ * one, a fresh tensor (lowest unused handle) is mapped on demand: free KV chunks in ascending
+ * order, then chunks taken back from available tensors (smallest mapped size first, equal sizes
+ * lowest handle first, from its last mapped slot downwards), then, if allowed, free activation
+ * chunks in ascending order. All or nothing. */
+int orc_tensor_acquire(orc_pool* p, int64_t need, int64_t max_tokens, uint32_t flags, int32_t* out) {
+  const int64_t Tc = p->tokens_per_chunk;
+  if (need < 0 || max_tokens < 1 || need > max_tokens) return ORC_INVALID;
+  if ((max_tokens + Tc - 1) / Tc > p->max_slots) return ORC_RANGE;
+  int32_t best = -1;
+  int64_t best_size = 0;
+  for (int32_t i = 0; i < p->max_tensors; i++) {
+    orc_tensor* t = &p->t[i];
+    if (!t->used || !t->released || t->max_tokens < max_tokens) continue;
+    int64_t size = (int64_t)mapped_run(t) * Tc;
+    if (size < need) continue;
+#if ORC_MUTANT == 11
+    if (best < 0 || size > best_size) { best = i; best_size = size; }   /* worst fit */
+    continue;
+#endif
+    if (best < 0 || size < best_size) { best = i; best_size = size; }
+  }
+  if (best >= 0) {
+    p->t[best].released = 0;
+    p->t[best].len = 0;
+    *out = best;
+    return ORC_OK;
+  }
+  /* on-demand mapping */
+  int32_t n = (int32_t)((need + Tc - 1) / Tc), k = 0, handle = -1;
+  for (int32_t i = 0; i < p->max_tensors && handle < 0; i++) if (!p->t[i].used) handle = i;
+  if (handle < 0) return ORC_OOM;
+  int32_t* pick = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n + 1));
+  int32_t* taken = (int32_t*)calloc((size_t)p->max_tensors, sizeof(int32_t));   /* slots taken back per tensor */
+  for (int32_t c = 0; c < p->n_chunks && k < n; c++)
+    if (p->owner[c] == OWNER_KV && p->state[c] == ST_FREE) pick[k++] = c;
+  while (k < n) {
+    int32_t donor = -1, donor_left = 0;
+    for (int32_t i = 0; i < p->max_tensors; i++) {
+      orc_tensor* t = &p->t[i];
+      if (!t->used || !t->released) continue;
+      int32_t left = mapped_run(t) - taken[i];
+      if (left > 0 && (donor < 0 || left < donor_left)) { donor = i; donor_left = left; }
+    }
+    if (donor < 0) break;
+    while (k < n && donor_left > 0) {
+      pick[k++] = p->t[donor].table[donor_left - 1];
+      donor_left--;
+      taken[donor]++;
+    }
+  }
+  if (k < n && (flags & 1u))
+    for (int32_t c = 0; c < p->n_chunks && k < n; c++)
+      if (p->owner[c] == OWNER_ACT && p->state[c] == ST_FREE) pick[k++] = c;
+  if (k < n) { free(pick); free(taken); return ORC_OOM; }
+  for (int32_t i = 0; i < p->max_tensors; i++) {
+    if (!taken[i]) continue;
+    orc_tensor* t = &p->t[i];
+    int32_t run = mapped_run(t);
+    for (int32_t s = run - taken[i]; s < run; s++) { release_entry(p, t->table[s]); t->table[s] = ENTRY_NONE; }
+  }
+  free(taken);
+  int32_t id = -1;
+  int rc = orc_tensor_create(p, max_tokens, &id);
+  if (rc || id != handle) { free(pick); return rc ? rc : ORC_INVALID; }
+  orc_tensor* t = &p->t[id];
+  for (int32_t i = 0; i < n; i++) {
+    int32_t c = pick[i];
+    p->owner[c] = OWNER_KV; p->state[c] = ST_MAPPED;
+    p->map_tensor[c] = id; p->map_slot[c] = i;
+    t->table[i] = c;
+  }
+  free(pick);
+  *out = id;
+  return ORC_OK;
+}
+
+/* Speculative pre-mapping (Sec. 3.1): every sequence is assumed to produce one more token, so a
+ * request whose next token opens a slot that has no chunk gets one mapped now (pool-chosen, as in
+ * map). All or nothing; *n_mapped counts the chunks. */
+int orc_kv_premap_next(orc_pool* p, const int32_t* ids, int32_t batch, uint32_t flags, int32_t* n_mapped) {
+  if (batch < 0) return ORC_INVALID;
+  const int64_t Tc = p->tokens_per_chunk;
+  int32_t need = 0;
+  for (int32_t b = 0; b < batch; b++) {
+    orc_tensor* t = tensor_of(p, ids[b]);
+    if (!t) return ORC_INVALID;
+    for (int32_t j = 0; j < b; j++) if (ids[j] == ids[b]) return ORC_INVALID;
+    if (t->len < t->max_tokens && t->len % Tc == 0 && t->table[t->len / Tc] == ENTRY_NONE) need++;
+  }
+  int32_t* pick = (int32_t*)malloc(sizeof(int32_t) * (size_t)(need + 1));
+  int rc = choose_chunks(p, need, (flags & 1u) != 0, pick);
+  if (rc) { free(pick); return rc; }
+  int32_t k = 0;
+  for (int32_t b = 0; b < batch; b++) {
+    orc_tensor* t = tensor_of(p, ids[b]);
+    if (!(t->len < t->max_tokens && t->len % Tc == 0 && t->table[t->len / Tc] == ENTRY_NONE)) continue;
+    int32_t c = pick[k++], s = (int32_t)(t->len / Tc);
+    p->owner[c] = OWNER_KV; p->state[c] = ST_MAPPED;
+    p->map_tensor[c] = ids[b]; p->map_slot[c] = s;
+    t->table[s] = c;
+  }
+  free(pick);
+  if (n_mapped) *n_mapped = need;
   return ORC_OK;
 }
 
@@ -380,7 +529,7 @@ int orc_chunk_fetch(orc_pool* p, int32_t id, int32_t first, int32_t n, const int
 
 /* ---- state read-out -------------------------------------------------------------------------- */
 int orc_tensor_get_table(orc_pool* p, int32_t id, int32_t* out, int32_t cap, int32_t* n_slots, int64_t* len) {
-  orc_tensor* t = tensor_of(p, id);
+  orc_tensor* t = tensor_any(p, id);
   if (!t) return ORC_INVALID;
   int32_t n = t->n_slots < cap ? t->n_slots : cap;
   if (out && n > 0) memcpy(out, t->table, sizeof(int32_t) * (size_t)n);

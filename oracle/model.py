@@ -33,6 +33,10 @@ def load(path: str | None = None) -> C.CDLL:
     lib.orc_tokens_per_chunk.argtypes = [C.c_void_p]
     lib.orc_tensor_create.argtypes = [C.c_void_p, C.c_int64, _i32p]
     lib.orc_tensor_destroy.argtypes = [C.c_void_p, C.c_int32]
+    lib.orc_tensor_release.argtypes = [C.c_void_p, C.c_int32]
+    lib.orc_tensor_acquire.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_uint32, _i32p]
+    lib.orc_tensor_is_released.argtypes = [C.c_void_p, C.c_int32]
+    lib.orc_kv_premap_next.argtypes = [C.c_void_p, _i32p, C.c_int32, C.c_uint32, _i32p]
     lib.orc_tensor_map_chunks.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _i32p, C.c_uint32]
     lib.orc_tensor_unmap_chunks.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
     lib.orc_pool_transfer.argtypes = [C.c_void_p, _i32p, C.c_int32, C.c_int]
@@ -108,6 +112,23 @@ class OraclePool:
 
     def tensor_destroy(self, tid):
         return self.lib.orc_tensor_destroy(self.h, tid)
+
+    def release(self, tid):
+        return self.lib.orc_tensor_release(self.h, tid)
+
+    def acquire(self, need_tokens, max_tokens, flags=0):
+        out = C.c_int32(-1)
+        rc = self.lib.orc_tensor_acquire(self.h, int(need_tokens), int(max_tokens), int(flags), C.byref(out))
+        return rc, out.value
+
+    def is_released(self, tid):
+        return self.lib.orc_tensor_is_released(self.h, tid)
+
+    def premap_next(self, ids, flags=0):
+        a, p = _i32(ids)
+        out = C.c_int32(0)
+        rc = self.lib.orc_kv_premap_next(self.h, p, a.size, int(flags), C.byref(out))
+        return rc, out.value
 
     def map_chunks(self, tid, first, n, chunk_ids=None, flags=0):
         _, p = _i32(chunk_ids)

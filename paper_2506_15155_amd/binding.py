@@ -56,6 +56,11 @@ _sigs = {
     "ellm_pool_destroy": [_vp],
     "ellm_tensor_create": [_vp, C.c_int64, _i32p],
     "ellm_tensor_destroy": [_vp, C.c_int32],
+    "ellm_tensor_release": [_vp, C.c_int32],
+    "ellm_tensor_acquire": [_vp, C.c_int64, C.c_int64, C.c_uint32, _i32p],
+    "ellm_tensor_is_released": [_vp, C.c_int32],
+    "ellm_kv_premap_next": [_vp, _i32p, C.c_int32, C.c_uint32, _i32p],
+    "ellm_pool_flush_tables": [_vp, _vp],
     "ellm_tensor_map_chunks": [_vp, C.c_int32, C.c_int32, C.c_int32, _i32p, C.c_uint32],
     "ellm_tensor_unmap_chunks": [_vp, C.c_int32, C.c_int32, C.c_int32],
     "ellm_pool_transfer": [_vp, _i32p, C.c_int32, C.c_int],
@@ -172,6 +177,39 @@ def ellm_tensor_create(pool, max_tokens, check=True):
 
 def ellm_tensor_destroy(pool, tid, check=True):
     return _ret(lib.ellm_tensor_destroy(pool, tid), check)
+
+
+def ellm_tensor_release(pool, tid, check=True):
+    return _ret(lib.ellm_tensor_release(pool, tid), check)
+
+
+def ellm_tensor_acquire(pool, need_tokens, max_tokens, flags=0, check=True):
+    """Returns the handle (check=True) or (rc, handle)."""
+    out = C.c_int32(-1)
+    rc = lib.ellm_tensor_acquire(pool, int(need_tokens), int(max_tokens), int(flags), C.byref(out))
+    if check:
+        _ret(rc, True)
+        return out.value
+    return rc, out.value
+
+
+def ellm_tensor_is_released(pool, tid):
+    return lib.ellm_tensor_is_released(pool, tid)
+
+
+def ellm_kv_premap_next(pool, ids, flags=0, check=True):
+    """Returns the number of chunks mapped (check=True) or (rc, n)."""
+    _, p, n = _i32(ids)
+    out = C.c_int32(0)
+    rc = lib.ellm_kv_premap_next(pool, p, n, int(flags), C.byref(out))
+    if check:
+        _ret(rc, True)
+        return out.value
+    return rc, out.value
+
+
+def ellm_pool_flush_tables(pool, stream=None, check=True):
+    return _ret(lib.ellm_pool_flush_tables(pool, _stream(stream)), check)
 
 
 def ellm_tensor_map_chunks(pool, tid, first_slot, n_slots, chunk_ids=None, flags=0, check=True):

@@ -506,6 +506,38 @@ int ellm_kv_append(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const
   return ELLM_OK;
 }
 
+int ellm_tensor_release(ellm_pool* p, ellm_tensor_id id) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  return core_err(p, p->core->tensor_release(id));
+}
+
+int ellm_tensor_acquire(ellm_pool* p, int64_t need_tokens, int64_t max_tokens, uint32_t flags, ellm_tensor_id* out) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  if (flags & ~ELLM_MAP_ALLOW_INFLATE) return set_err(ELLM_ERR_INVALID, "tensor_acquire: unknown flags");
+  return core_err(p, p->core->tensor_acquire(need_tokens, max_tokens, flags, out));
+}
+
+int ellm_tensor_is_released(ellm_pool* p, ellm_tensor_id id) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  const ellm::TensorRec* t = p->core->tensor_any(id);
+  if (!t) return set_err(ELLM_ERR_INVALID, "is_released: bad tensor handle");
+  return t->released ? 1 : 0;
+}
+
+int ellm_kv_premap_next(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, uint32_t flags, int32_t* n_mapped) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  if (flags & ~ELLM_MAP_ALLOW_INFLATE) return set_err(ELLM_ERR_INVALID, "premap_next: unknown flags");
+  return core_err(p, p->core->premap_next(ids, batch, flags, n_mapped));
+}
+
+int ellm_pool_flush_tables(ellm_pool* p, void* stream) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  if (p->metadata_only) return ELLM_OK;
+  int rc = ensure_device(p);
+  if (rc) return rc;
+  return flush_table(p, (hipStream_t)stream);
+}
+
 int ellm_decode_plan(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, int32_t* n_split, int32_t* split_tokens) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
   int rc = core_err(p, p->core->decode_check(ids, batch));
@@ -656,7 +688,7 @@ int ellm_pool_get_geometry(ellm_pool* p, int32_t* n_chunks, int32_t* tokens_per_
 
 int ellm_tensor_get_table(ellm_pool* p, ellm_tensor_id id, int32_t* out, int32_t cap, int32_t* n_slots, int64_t* len) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
-  const ellm::TensorRec* t = p->core->tensor(id);
+  const ellm::TensorRec* t = p->core->tensor_any(id);
   if (!t) return set_err(ELLM_ERR_INVALID, "get_table: bad tensor handle");
   if (out && cap > 0) std::memcpy(out, p->core->row(id), sizeof(int32_t) * (size_t)std::min(cap, t->n_slots));
   if (n_slots) *n_slots = t->n_slots;

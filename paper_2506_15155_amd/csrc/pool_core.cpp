@@ -80,14 +80,116 @@ int PoolCore::tensor_create(int64_t max_tokens, int32_t* out) {
 }
 
 int PoolCore::tensor_destroy(int32_t id) {
-  if (!tensor(id)) return fail(ERR_INVALID, "tensor_destroy: bad tensor handle");
+  if (!tensor_any(id)) return fail(ERR_INVALID, "tensor_destroy: bad tensor handle");
   TensorRec& t = t_[id];
+  if (t.released) released_.erase({t.run, id});
   for (int32_t s = 0; s < t.n_slots; s++) {
     release_entry(row(id)[s]);
     set_entry(id, s, ENTRY_UNMAPPED);
   }
   t = TensorRec();
   free_ids_.insert(id);
+  return OK;
+}
+
+int PoolCore::tensor_release(int32_t id) {
+  if (!tensor(id)) return fail(ERR_INVALID, "tensor_release: bad or already released tensor handle");
+  TensorRec& t = t_[id];
+  int32_t run = 0;
+  while (run < t.n_slots && row(id)[run] >= 0) run++;
+  for (int32_t s = run; s < t.n_slots; s++) {
+    if (row(id)[s] == ENTRY_UNMAPPED) continue;
+    release_entry(row(id)[s]);
+    set_entry(id, s, ENTRY_UNMAPPED);
+  }
+  t.len = 0;
+  t.released = true;
+  t.run = run;
+  released_.insert({run, id});
+  return OK;
+}
+
+int PoolCore::tensor_acquire(int64_t need, int64_t max_tokens, uint32_t flags, int32_t* out) {
+  const int64_t Tc = g_.tokens_per_chunk;
+  if (!out || need < 0 || max_tokens < 1 || need > max_tokens)
+    return fail(ERR_INVALID, "tensor_acquire: need_tokens must be in 0 .. max_tokens, max_tokens >= 1");
+  if ((max_tokens + Tc - 1) / Tc > g_.max_slots)
+    return fail(ERR_RANGE, "tensor_acquire: max_tokens needs more slots than max_slots_per_tensor");
+  const int32_t n = (int32_t)((need + Tc - 1) / Tc);
+  // best fit: released_ is ordered by (mapped slots, handle), so the first entry at or above n whose
+  // virtual range suffices has the smallest sufficient size and, among equals, the lowest handle
+  for (auto it = released_.lower_bound({n, -1}); it != released_.end(); ++it) {
+    TensorRec& t = t_[it->second];
+    if (t.max_tokens < max_tokens) continue;
+    *out = it->second;
+    released_.erase(it);
+    t.released = false;
+    t.run = 0;
+    t.len = 0;
+    return OK;
+  }
+  // on-demand mapping of a fresh tensor: plan first, change nothing on failure
+  if (free_ids_.empty()) return fail(ERR_OOM, "tensor_acquire: no fitting available tensor and no free tensor handle");
+  std::vector<int32_t> pick;
+  pick.reserve(n);
+  for (auto it = free_kv_.begin(); it != free_kv_.end() && (int32_t)pick.size() < n; ++it) pick.push_back(*it);
+  std::vector<std::pair<int32_t, int32_t>> donors;   // (handle, slots taken back from its tail)
+  for (auto it = released_.begin(); it != released_.end() && (int32_t)pick.size() < n; ++it) {
+    if (it->first == 0) continue;
+    int32_t left = it->first, took = 0;
+    while ((int32_t)pick.size() < n && left > 0) {
+      pick.push_back(row(it->second)[left - 1]);
+      left--;
+      took++;
+    }
+    donors.push_back({it->second, took});
+  }
+  if ((int32_t)pick.size() < n && (flags & 1u))
+    for (auto it = free_act_.begin(); it != free_act_.end() && (int32_t)pick.size() < n; ++it) pick.push_back(*it);
+  if ((int32_t)pick.size() < n) return fail(ERR_OOM, "tensor_acquire: not enough chunks for on-demand mapping");
+  for (const auto& d : donors) {
+    TensorRec& t = t_[d.first];
+    released_.erase({t.run, d.first});
+    for (int32_t s = t.run - d.second; s < t.run; s++) {
+      release_entry(row(d.first)[s]);
+      set_entry(d.first, s, ENTRY_UNMAPPED);
+    }
+    t.run -= d.second;
+    released_.insert({t.run, d.first});
+  }
+  int32_t id = -1;
+  int rc = tensor_create(max_tokens, &id);
+  if (rc) return rc;
+  for (int32_t i = 0; i < n; i++) take_chunk(pick[i], id, i);
+  *out = id;
+  return OK;
+}
+
+int PoolCore::premap_next(const int32_t* ids, int32_t batch, uint32_t flags, int32_t* n_mapped) {
+  if (batch < 0 || (batch > 0 && !ids)) return fail(ERR_INVALID, "premap_next: bad batch");
+  const int64_t Tc = g_.tokens_per_chunk;
+  ++stamp_now_;
+  int32_t need = 0;
+  auto opens_slot = [&](int32_t id) {
+    const TensorRec& t = t_[id];
+    return t.len < t.max_tokens && t.len % Tc == 0 && row(id)[t.len / Tc] == ENTRY_UNMAPPED;
+  };
+  for (int32_t b = 0; b < batch; b++) {
+    if (!tensor(ids[b])) return fail(ERR_INVALID, "premap_next: bad tensor handle");
+    if (stamp_[ids[b]] == stamp_now_) return fail(ERR_INVALID, "premap_next: tensor handle given twice");
+    stamp_[ids[b]] = stamp_now_;
+    if (opens_slot(ids[b])) need++;
+  }
+  std::vector<int32_t> pick;
+  int rc = pick_chunks(need, nullptr, (flags & 1u) != 0, pick);
+  if (rc) return rc;
+  int32_t k = 0;
+  for (int32_t b = 0; b < batch; b++)
+    if (opens_slot(ids[b])) {
+      take_chunk(pick[k], ids[b], (int32_t)(t_[ids[b]].len / Tc));
+      k++;
+    }
+  if (n_mapped) *n_mapped = need;
   return OK;
 }
 
@@ -321,6 +423,17 @@ int PoolCore::self_check() const {
     if (is_free != (host_tensor_[s] < 0)) return 10;
     if (!is_free && !hseen[s]) return 11;
   }
+  // released tensors: empty, mapped only in a leading run, and listed under that run
+  size_t n_released = 0;
+  for (int32_t id = 0; id < g_.max_tensors; id++) {
+    const TensorRec& t = t_[id];
+    if (!t.used || !t.released) continue;
+    n_released++;
+    if (t.len != 0 || !released_.count({t.run, id})) return 12;
+    for (int32_t s = 0; s < t.n_slots; s++)
+      if ((s < t.run) != (row(id)[s] >= 0) || (s >= t.run && row(id)[s] != ENTRY_UNMAPPED)) return 13;
+  }
+  if (n_released != released_.size()) return 14;
   return 0;
 }
 

@@ -38,6 +38,8 @@ struct Geometry {
 
 struct TensorRec {
   bool used = false;
+  bool released = false;   // mapped and available: waits for a new request (Sec. 2.1.2)
+  int32_t run = 0;         // while released: leading slots that still have a device chunk
   int64_t max_tokens = 0, len = 0;
   int32_t n_slots = 0;
 };
@@ -54,6 +56,12 @@ class PoolCore {
 
   int tensor_create(int64_t max_tokens, int32_t* out);
   int tensor_destroy(int32_t id);
+  // request turnover (Sec. 2.1.2): release keeps the leading mapped slots and makes the tensor
+  // available; acquire picks the best-fitting available tensor or maps a fresh one on demand
+  int tensor_release(int32_t id);
+  int tensor_acquire(int64_t need_tokens, int64_t max_tokens, uint32_t flags, int32_t* out);
+  // speculative pre-mapping (Sec. 3.1): one chunk for every request whose next token opens an empty slot
+  int premap_next(const int32_t* ids, int32_t batch, uint32_t flags, int32_t* n_mapped);
   int map_chunks(int32_t id, int32_t first, int32_t n, const int32_t* chunk_ids, uint32_t flags);
   int unmap_chunks(int32_t id, int32_t first, int32_t n);
   int transfer(const int32_t* chunk_ids, int32_t n, int new_owner);
@@ -72,7 +80,11 @@ class PoolCore {
   int fetch_plan(int32_t id, int32_t first, int32_t n, const int32_t* chunk_ids, std::vector<Move>& moves);
   void fetch_commit(int32_t id, const std::vector<Move>& moves);
 
+  // a tensor that belongs to a request; released ones take no call but acquire, destroy and read-out
   const TensorRec* tensor(int32_t id) const {
+    return (id >= 0 && id < g_.max_tensors && t_[id].used && !t_[id].released) ? &t_[id] : nullptr;
+  }
+  const TensorRec* tensor_any(int32_t id) const {
     return (id >= 0 && id < g_.max_tensors && t_[id].used) ? &t_[id] : nullptr;
   }
   const int32_t* row(int32_t id) const { return &table_[(size_t)id * g_.max_slots]; }
@@ -104,6 +116,7 @@ class PoolCore {
   std::vector<uint8_t> owner_, state_;
   std::vector<int32_t> map_tensor_, map_slot_, host_tensor_, host_slot_;
   std::set<int32_t> free_kv_, free_act_, free_host_, free_ids_;
+  std::set<std::pair<int32_t, int32_t>> released_;   // (leading mapped slots, handle) of every released tensor
   std::vector<TensorRec> t_;
   std::vector<int32_t> table_;     // max_tensors x max_slots, row-major, ENTRY_UNMAPPED where empty
   std::vector<int64_t> dirty_;

@@ -105,6 +105,24 @@ class Both:
             assert rco == 0
         return rc, out, ref
 
+    def release(self, tid):
+        return self.both("release", lambda: E.ellm_tensor_release(self.pool, tid, check=False),
+                         lambda: self.orc.release(tid))
+
+    def acquire(self, need_tokens, max_tokens, flags=0):
+        rc, tid = E.ellm_tensor_acquire(self.pool, need_tokens, max_tokens, flags, check=False)
+        if self.orc is not None:
+            assert (rc, tid) == self.orc.acquire(need_tokens, max_tokens, flags)
+        if rc == 0 and tid not in self.ids:
+            self.ids.append(tid)
+        return rc, tid
+
+    def premap_next(self, ids, flags=0):
+        a = E.ellm_kv_premap_next(self.pool, ids, flags, check=False)
+        if self.orc is not None:
+            assert a == self.orc.premap_next(ids, flags)
+        return a
+
     def offload(self, tid, first, n):
         return self.both("offload", lambda: E.ellm_chunk_deflate_to_host(self.pool, tid, first, n, check=False),
                          lambda: self.orc.offload(tid, first, n))

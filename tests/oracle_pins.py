@@ -354,7 +354,95 @@ def pin_inflation_walkthrough(lib, path):
     pool.close()
 
 
+def pin_best_fit_is_the_arg_min(lib):
+    """Sec. 2.1.2: among the available tensors with size >= s the smallest is taken (brute force
+    over the sizes here; equal sizes: lowest handle, this build's reading). The mapping of the
+    chosen tensor is kept as it is; with no fitting tensor a fresh one is mapped on demand."""
+    rng = np.random.default_rng(7)
+    Tc = 16
+    for trial in range(30):
+        pool = make_pool(lib, 8, 8, 64, Tc, n_chunks=64, n_host=4, max_tensors=12, max_slots=8)
+        n_t = int(rng.integers(1, 9))
+        slots = rng.integers(0, 7, size=n_t)                   # mapped slots per tensor; equal sizes are likely
+        tables = []
+        for i in range(n_t):
+            rc, t = pool.tensor_create(8 * Tc)
+            assert rc == 0 and t == i
+            assert pool.map_chunks(t, 0, int(slots[i])) == 0
+            tables.append(pool.table(t)[0].copy())
+        released = sorted(rng.choice(n_t, size=int(rng.integers(0, n_t + 1)), replace=False).tolist())
+        for t in released:
+            assert pool.release(t) == 0
+            assert pool.is_released(t) == 1 and pool.table(t)[1] == 0
+            assert np.array_equal(pool.table(t)[0], tables[t])          # the mapping is retained
+        s = int(rng.integers(0, 7 * Tc))
+        sizes = {t: int(slots[t]) * Tc for t in released}
+        feasible = [t for t in released if sizes[t] >= s]
+        rc, got = pool.acquire(s, 8 * Tc)
+        assert rc == 0
+        if feasible:
+            smallest = min(sizes[t] for t in feasible)
+            want = min(t for t in feasible if sizes[t] == smallest)
+            assert got == want, (trial, s, sizes, got, want)
+            assert pool.is_released(got) == 0
+            assert np.array_equal(pool.table(got)[0], tables[got])      # no mapping changed
+        else:
+            assert got == n_t                                           # lowest unused handle
+            need = -(-s // Tc)
+            tab = pool.table(got)[0]
+            assert (tab[:need] >= 0).all() and (tab[need:] == -1).all()
+            assert len(set(tab[:need].tolist())) == need
+        assert pool.check_invariants() == 0
+        pool.close()
+
+
+def pin_release_acquire_premap_rules(lib):
+    """A released tensor keeps only its leading mapped run, takes no request call, and is the first
+    source of chunks when on-demand mapping runs short (smallest available tensor first, from its
+    tail); pre-mapping gives exactly the requests about to open an empty slot one chunk each."""
+    Tc = 16
+    pool = make_pool(lib, 8, 8, 64, Tc, n_chunks=10, n_host=4, max_tensors=6, max_slots=8)
+    _, a = pool.tensor_create(8 * Tc)
+    _, b = pool.tensor_create(8 * Tc)
+    assert pool.map_chunks(a, 0, 3) == 0 and pool.map_chunks(b, 0, 5) == 0      # a: 0,1,2  b: 3..7
+    tok = np.zeros((40, 8, 64), np.uint16)
+    assert pool.append([a], tok, tok, [40]) == 0
+    assert pool.offload(a, 1, 1) == 0                                            # a: 0, host, 2
+    assert pool.release(a) == 0
+    assert list(pool.table(a)[0][:3]) == [0, -1, -1] and pool.table(a)[1] == 0   # run of 1 kept, rest given back
+    th, _ = pool.host_slots()
+    assert (th == -1).all()
+    for call in (lambda: pool.map_chunks(a, 1, 1), lambda: pool.append([a], tok, tok, [1]),
+                 lambda: pool.decode([a], np.zeros((1, 8, 64), np.uint16))[0], lambda: pool.release(a),
+                 lambda: pool.offload(a, 0, 1), lambda: pool.premap_next([a])[0]):
+        assert call() == -1
+    assert pool.release(b) == 0
+    # 10 chunks: 0 (a), 3..7 (b) mapped; free: 1, 2, 8, 9. A request for 7 slots fits no released tensor:
+    # free chunks 1, 2, 8, 9 first, then from the smallest released tensor (a: chunk 0), then b's tail (7, 6)
+    rc, c = pool.acquire(7 * Tc, 8 * Tc)
+    assert rc == 0 and c == 2
+    assert list(pool.table(c)[0][:7]) == [1, 2, 8, 9, 0, 7, 6]
+    assert list(pool.table(a)[0][:1]) == [-1] and list(pool.table(b)[0][:5]) == [3, 4, 5, -1, -1]
+    assert pool.acquire(4 * Tc, 8 * Tc)[0] == -2                                 # 3 chunks left in b, none free
+    rc, d = pool.acquire(2 * Tc, 8 * Tc)
+    assert rc == 0 and d == b and list(pool.table(b)[0][:3]) == [3, 4, 5]        # b (3 slots) fits; a (0) does not
+    # pre-mapping
+    assert pool.tensor_destroy(c) == 0
+    assert pool.append([b], tok, tok, [32]) == 0                                 # b: 2 full slots of 3 -> next slot is mapped
+    rc, e = pool.acquire(0, 8 * Tc)
+    assert rc == 0 and e == a                                                    # a (size 0) is the best fit for nothing
+    rc, n = pool.premap_next([b, e])
+    assert (rc, n) == (0, 1) and pool.table(e)[0][0] == 0 and pool.table(b)[0][3] == -1
+    assert pool.premap_next([b, e]) == (0, 0)
+    assert pool.append([b], tok, tok, [16]) == 0
+    rc, n = pool.premap_next([b, e])
+    assert (rc, n) == (0, 1) and pool.table(b)[0][3] == 1
+    assert pool.check_invariants() == 0
+    pool.close()
+
+
 ALL_PINS = [pin_sdpa_library, pin_single_token, pin_zero_query_is_mean, pin_constant_v,
             pin_weights_sum_to_one, pin_two_token_logistic, pin_dominant_key, pin_shift_invariance,
             pin_gqa_grouping, pin_chunked_equals_twin_and_online, pin_layout_bytes,
-            pin_remap_and_roundtrip_invariance, pin_allocator_order_and_inflation]
+            pin_remap_and_roundtrip_invariance, pin_allocator_order_and_inflation, pin_best_fit_is_the_arg_min,
+            pin_release_acquire_premap_rules]

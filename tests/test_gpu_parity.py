@@ -335,6 +335,56 @@ def test_layerwise_fetch_under_attention():
     T.close()
 
 
+def test_request_turnover_best_fit_reuse():
+    """Requests finish and are released with their chunks still mapped; new requests take the
+    best-fitting released tensor (no table entry changes), write their prompt with a multi-token
+    append over the previous owner's rows, pre-map one step ahead and decode. The previous
+    owner's stale rows lie right behind the new length, so any read past the length shows."""
+    cfg = W.scaled(W.CONFIGS["llama8b"], batch=8, n_chunks=64, len_lo=200, len_hi=1900, lognormal_median=800)
+    st = W.draw_step(cfg, seed=51)
+    B = H.Both(cfg, max_tensors=12)
+    ids = H.load_step(B, st)
+    rc, out, ref = B.append_decode(ids, st.k_new, st.v_new, st.q)
+    assert rc == 0
+    H.check_close(out, ref, "before turnover")
+    rng = np.random.default_rng(52)
+    Tc = cfg.tokens_per_chunk
+    live = list(ids)
+    lens = {t: int(l) for t, l in zip(ids, st.lens)}
+    for round_ in range(4):
+        done = [live[i] for i in sorted(rng.choice(len(live), size=3, replace=False))]
+        tables = {t: E.ellm_tensor_get_table(B.pool, t)[0].copy() for t in done}
+        for t in done:
+            assert B.release(t) == 0
+            live.remove(t)
+        for _ in range(3):
+            prompt = int(rng.integers(1, 1500))
+            rc, t = B.acquire(prompt, cfg.max_tokens, E.ELLM_MAP_ALLOW_INFLATE)
+            assert rc == 0
+            if t in tables:                        # a released tensor was reused: same chunks as before
+                run = int((tables[t] >= 0).cumprod().sum())
+                assert np.array_equal(E.ellm_tensor_get_table(B.pool, t)[0][:run], tables[t][:run])
+                assert run * Tc >= prompt
+            k = W.normal_bf16(rng, (prompt, cfg.n_kv_heads, cfg.head_dim))
+            v = W.normal_bf16(rng, (prompt, cfg.n_kv_heads, cfg.head_dim))
+            assert B.append([t], k, v, [prompt]) == 0
+            live.append(t)
+            lens[t] = prompt
+        rc, n = B.premap_next(live, E.ELLM_MAP_ALLOW_INFLATE)
+        assert rc == 0
+        E.ellm_pool_flush_tables(B.pool)
+        shape = (len(live), cfg.n_kv_heads, cfg.head_dim)
+        k1, v1 = W.normal_bf16(rng, shape), W.normal_bf16(rng, shape)
+        q = W.normal_bf16(rng, (len(live), cfg.n_q_heads, cfg.head_dim))
+        rc, out, ref = B.append_decode(live, k1, v1, q)
+        assert rc == 0, E.ellm_last_error()
+        H.check_close(out, ref, f"turnover round {round_}")
+        for t in live:
+            lens[t] += 1
+        B.compare_state()
+    B.close()
+
+
 def test_error_paths_launch_nothing():
     cfg = W.scaled(W.CONFIGS["tiny"], batch=2, host_slots=4)
     B = H.Both(cfg)

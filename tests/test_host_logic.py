@@ -54,6 +54,7 @@ class Pair:
             assert alive == oalive
             if alive:
                 assert np.array_equal(tab, otab) and ln == oln
+                assert E.ellm_tensor_is_released(self.lib, tid) == self.orc.is_released(tid)
         assert E.ellm_pool_self_check(self.lib) == 0
         assert self.orc.check_invariants() == 0
         # no physical chunk backs two slots
@@ -76,8 +77,8 @@ def random_walk(seed, steps=600, **kw):
     seen_codes = set()
     for _ in range(steps):
         op = rng.choice(["create", "destroy", "map", "map_ids", "unmap", "transfer", "busy", "append",
-                         "decode", "offload", "fetch", "fetch_ids"],
-                        p=[.08, .04, .16, .08, .04, .08, .08, .2, .06, .08, .06, .04])
+                         "decode", "offload", "fetch", "fetch_ids", "release", "acquire", "premap"],
+                        p=[.07, .03, .14, .07, .03, .07, .07, .18, .05, .07, .05, .03, .05, .05, .04])
         alive = [t for t in range(P.max_tensors) if P._alive(t)]
         if alive and rng.random() < 0.8:
             # mostly plausible arguments, so the walk reaches deep states (full host buffer, long tensors)
@@ -138,6 +139,27 @@ def random_walk(seed, steps=600, **kw):
             orc_rc, _ = P.orc.decode(tids, np.zeros((max(nb, 1), 8, P.D), np.uint16), threads=1)
             # with no device behind it the library validates, then reports NO_DEVICE instead of OK
             assert (rc == orc_rc) or (orc_rc == 0 and rc == (E.ERR.NO_DEVICE if nb else 0)), (rc, orc_rc)
+        elif op == "release":
+            rc = E.ellm_tensor_release(P.lib, tid, check=False)
+            assert rc == P.orc.release(tid), op
+        elif op == "acquire":
+            need = int(rng.integers(-1, 16 * 8))
+            mt = int(rng.integers(0, 16 * 13))
+            fl = int(rng.integers(0, 2))
+            a = E.ellm_tensor_acquire(P.lib, need, mt, fl, check=False)
+            b = P.orc.acquire(need, mt, fl)
+            assert a[0] == b[0] and (a[0] != 0 or a[1] == b[1]), (op, a, b)
+            rc = a[0]
+        elif op == "premap":
+            nb = int(rng.integers(0, 4))
+            tids = rng.integers(-1, P.max_tensors, size=nb).astype(np.int32)
+            if alive and rng.random() < 0.8:
+                tids = rng.choice(alive, size=min(nb, len(alive)), replace=False).astype(np.int32)
+            fl = int(rng.integers(0, 2))
+            a = E.ellm_kv_premap_next(P.lib, tids, fl, check=False)
+            b = P.orc.premap_next(tids, fl)
+            assert a[0] == b[0] and (a[0] != 0 or a[1] == b[1]), (op, a, b)
+            rc = a[0]
         elif op == "offload":
             rc = E.ellm_chunk_deflate_to_host(P.lib, tid, first, n, check=False)
             assert rc == P.orc.offload(tid, first, n), op
@@ -160,8 +182,8 @@ def test_random_call_sequences_match_oracle(seed):
 
 def test_random_walks_reach_every_error_code():
     seen = set()
-    for seed in range(10, 16):
-        seen |= random_walk(seed, steps=500, n_host=3 if seed % 2 else 10)
+    for seed in range(10, 18):
+        seen |= random_walk(seed, steps=600, n_host=2 if seed % 2 else 10)
     for code in (E.ERR.OK, E.ERR.INVALID, E.ERR.OOM, E.ERR.OWNED, E.ERR.UNMAPPED, E.ERR.NOT_RESIDENT,
                  E.ERR.RANGE, E.ERR.EMPTY, E.ERR.HOST_FULL):
         assert code in seen, code

@@ -1,7 +1,8 @@
 """Each planted mistake in the oracle (built as a separate, deliberately wrong library on the CPU)
 must fail at least one pin. This shows the pins are sharp enough to notice a dropped term, a wrong
 head mapping, swapped planes, a transposed layout, a missing normalisation, a stale newest token,
-a wrong allocation order and broken migration bookkeeping."""
+a wrong allocation order, broken migration bookkeeping, a worst-fit choice and a release that
+retains nothing."""
 import os
 
 import pytest
@@ -23,6 +24,8 @@ MUTANTS = {
     8: "pool picks the highest free chunk",
     9: "offload does not free the device chunk",
     10: "fetch does not copy the bytes back",
+    11: "acquire takes the largest fitting available tensor instead of the smallest",
+    12: "release unmaps everything instead of keeping the mapping",
 }
 
 
