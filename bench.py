@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--migration", action="store_true",
                     help="also time the elastic step: 25%% of the requests parked in pinned host memory, fetched and "
                          "offloaded every step, all at once and layer by layer under the attention")
+    ap.add_argument("--turnover", action="store_true",
+                    help="also time request turnover on the host: release + best-fit acquire against destroy + create + map")
     ap.add_argument("--prefill-append", type=int, default=0, metavar="N",
                     help="also time a multi-token append of N tokens per request and layer")
     return ap.parse_args()
@@ -140,11 +142,16 @@ def main():
     f_append, f_decode, f_fused = E.lib.ellm_kv_append, E.lib.ellm_decode_attention, E.lib.ellm_kv_append_decode
     fused = not args.separate_calls
 
+    f_premap = E.lib.ellm_kv_premap_next
+    c_inflate = C.c_uint32(E.ELLM_MAP_ALLOW_INFLATE)
+
     def map_ahead():
         # a3: requests whose next token opens a new chunk get one mapped (inflating if needed)
-        for b in np.flatnonzero(lens % Tc == 0):
-            for l in range(n_layers):
-                E.ellm_tensor_map_chunks(pool, int(ids[l][b]), int(lens[b]) // Tc, 1, None, E.ELLM_MAP_ALLOW_INFLATE)
+        if not (lens % Tc == 0).any():
+            return
+        for l in range(n_layers):
+            if f_premap(c_pool, c_ids[l], B, c_inflate, None):
+                raise E.EllmError(-1, E.ellm_last_error())
 
     def layer_call(l):
         if fused:
@@ -210,6 +217,9 @@ def main():
     mig = None
     if args.migration:
         mig = time_migration(E, torch, pool, ids, lens, Tc, cfg, B, n_layers, map_ahead, layer_call)
+    turn = None
+    if args.turnover:
+        turn = time_turnover(E, torch, pool, ids, lens, cfg, n_layers, max_tokens)
     pre = None
     if args.prefill_append:
         pre = time_prefill_append(E, torch, pool, ids, lens, cfg, n_layers, args.prefill_append, max_tokens)
@@ -235,6 +245,8 @@ def main():
         res["migration"] = mig
     if pre:
         res["prefill_append"] = pre
+    if turn:
+        res["turnover"] = turn
     E.ellm_pool_destroy(pool)
     print(json.dumps(res))
 
@@ -413,6 +425,50 @@ def _time_migration(E, torch, pool, ids, lens, Tc, cfg, n_layers, map_ahead, lay
             "ms_step_fetch_all_then_compute": round(t_block, 3), "ms_step_layerwise": round(t_layer, 3),
             "pcie_GBps_both_ways_avg": round(2 * nbytes / (t_copy * 1e-3) / 1e9, 2),
             "ms_hidden_by_layerwise": round(t_block - t_layer, 3)}
+
+
+def time_turnover(E, torch, pool, ids, lens, cfg, n_layers, max_tokens, rounds=20):
+    """Host cost of replacing a finished request by a new one of the same prompt length in every layer:
+    (a) release + acquire, where the best-fitting available tensor is taken with its mapping intact and
+    no table entry changes; (b) destroy + create + map, where every slot is mapped again and the device
+    table has to be patched. Microseconds per request and layer; the tensors end up as they started."""
+    B, Tc = cfg.batch, cfg.tokens_per_chunk
+    order = np.argsort(lens)
+    pick = [int(order[B // 2]), int(order[3 * B // 4]), int(order[B // 4])]
+    torch.cuda.synchronize()
+    t_reuse = t_remap = 0.0
+    n_ops = 0
+    for _ in range(rounds):
+        for b in pick:
+            need = int(lens[b])
+            t0 = time.perf_counter()
+            for l in range(n_layers):
+                E.ellm_tensor_release(pool, int(ids[l][b]))
+            for l in range(n_layers):
+                t = E.ellm_tensor_acquire(pool, need, max_tokens)
+                ids[l][b] = t
+            t1 = time.perf_counter()
+            for l in range(n_layers):
+                E.ellm_tensor_destroy(pool, int(ids[l][b]))
+            for l in range(n_layers):
+                t = E.ellm_tensor_create(pool, max_tokens)
+                E.ellm_tensor_map_chunks(pool, t, 0, -(-need // Tc), None, E.ELLM_MAP_ALLOW_INFLATE)
+                ids[l][b] = t
+            t2 = time.perf_counter()
+            t_reuse += t1 - t0
+            t_remap += t2 - t1
+            n_ops += n_layers
+    # the tensors are empty now: give them their length back (contents do not matter any more)
+    kd = torch.zeros((int(lens.max()), cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+    for b in pick:
+        for l in range(n_layers):
+            E.ellm_kv_append(pool, [int(ids[l][b])], kd, kd, [int(lens[b])])
+    torch.cuda.synchronize()
+    return {"us_release_plus_best_fit_acquire": round(t_reuse / n_ops * 1e6, 2),
+            "us_destroy_create_map": round(t_remap / n_ops * 1e6, 2),
+            "slots_per_request": [int(-(-int(lens[b]) // Tc)) for b in pick],
+            "note": "host time per request and layer through the Python binding; the second path also leaves one "
+                    "table entry per slot to be patched on the device by the next call"}
 
 
 def time_prefill_append(E, torch, pool, ids, lens, cfg, n_layers, n_tok, max_tokens):
