@@ -248,7 +248,8 @@ int ellm_kv_append_decode(ellm_pool* pool, const ellm_tensor_id* ids, int32_t ba
  * on its own stream, for the copies that touched its tensors' chunks. All append / decode calls
  * of a pool are expected on one stream, or on streams the caller orders.
  * Checks: bad handle, n_slots < 0 -> INVALID; range -> RANGE; slots ascending: empty -> UNMAPPED,
- * already on host -> NOT_RESIDENT; fewer than n_slots free host slots -> HOST_FULL. */
+ * already on host -> NOT_RESIDENT; fewer than n_slots free host slots, or more occupied host slots
+ * than the logical host buffer allows -> HOST_FULL. */
 int ellm_chunk_deflate_to_host(ellm_pool* pool, ellm_tensor_id id, int32_t first_slot, int32_t n_slots);
 
 /* Fetch (Sec. 2.2.2): bring host-resident slots back into FREE KV-owned device chunks
@@ -259,6 +260,29 @@ int ellm_chunk_deflate_to_host(ellm_pool* pool, ellm_tensor_id id, int32_t first
  * ACT-owned -> OWNED; pool-chosen: too few -> OOM. */
 int ellm_chunk_inflate_from_host(ellm_pool* pool, ellm_tensor_id id, int32_t first_slot, int32_t n_slots,
                                  const int32_t* chunk_ids);
+
+/* Logical host buffer (Sec. 2.3.2): the part of the host slots that offloads may fill. Offloads
+ * fail with HOST_FULL once occupied host slots + the request would exceed it; shrinking it evicts
+ * nothing that is already stored. Initially all host slots. n outside 0 .. host slots -> RANGE. */
+int ellm_pool_set_logical_host_slots(ellm_pool* pool, int32_t n);
+int ellm_pool_get_logical_host_slots(ellm_pool* pool, int32_t* n);
+
+/* SLO-aware scaling of the logical host buffer (Sec. 2.3.2). configure: the two thresholds (same
+ * unit as the latencies passed to observe), the tuning factor alpha (paper: 2), the window in
+ * scheduling iterations (paper: 5) and the violations within it that make an event (paper: 3).
+ * observe: the latencies of one scheduling iteration, time to first token and time per output
+ * token (a negative value = none measured). The paper fixes: an event when the latency exceeded
+ * its threshold `threshold` times within the window; time per output token -> the buffer shrinks,
+ * time to first token -> it grows, at a rate set by alpha. This library's reading of what it
+ * leaves open: shrink to floor(size / alpha), grow to min(all host slots, ceil(max(1, size) *
+ * alpha)); when both events fall together the buffer shrinks; the window slides over the
+ * iterations since the last change and starts empty after one. *logical_host_slots (may be NULL)
+ * receives the size after the call.
+ * Checks: thresholds <= 0, alpha <= 1, window < 1, threshold outside 1 .. window, NaN latency,
+ * observe before configure -> INVALID. */
+int ellm_pool_slo_configure(ellm_pool* pool, double ttft_slo, double tpot_slo, double alpha, int32_t window,
+                            int32_t threshold);
+int ellm_pool_slo_observe(ellm_pool* pool, double ttft, double tpot, int32_t* logical_host_slots);
 
 /* Block until all migrations enqueued so far have finished. Returns HIP on an asynchronous fault. */
 int ellm_pool_sync(ellm_pool* pool);

@@ -75,6 +75,14 @@ typedef struct {
   uint8_t** chunk_img;                 /* per chunk byte image, allocated on first touch (zeros) */
   uint8_t** host_img;                  /* per host slot byte image */
   orc_tensor* t;
+  /* logical host buffer and its SLO-aware scaling (Sec. 2.3.2) */
+  int32_t logical_host;
+  int slo_on;
+  double slo_ttft, slo_tpot, slo_alpha;
+  int32_t slo_window, slo_threshold;
+  double* hist_ttft;                   /* every observation ever made, in order */
+  double* hist_tpot;
+  int64_t hist_n, hist_cap, hist_start;  /* hist_start: first observation after the last size change */
 } orc_pool;
 
 static double bf16_to_f64(uint16_t b) {
@@ -114,6 +122,7 @@ orc_pool* orc_pool_create(int32_t n_chunks, uint32_t chunk_bytes, int32_t n_host
   p->tokens_per_chunk = (int32_t)(chunk_bytes / bpt);
   p->Hq = Hq; p->Hkv = Hkv; p->D = D; p->G = Hq / Hkv;
   p->max_tensors = max_tensors; p->max_slots = max_slots; p->keep_twin = keep_twin;
+  p->logical_host = n_host;
   p->owner = (uint8_t*)calloc(n_chunks, 1);
   p->state = (uint8_t*)calloc(n_chunks, 1);
   p->map_tensor = (int32_t*)malloc(sizeof(int32_t) * n_chunks);
@@ -138,6 +147,7 @@ void orc_pool_destroy(orc_pool* p) {
   for (int32_t i = 0; i < p->max_tensors; i++) {
     free(p->t[i].table); free(p->t[i].twin_k); free(p->t[i].twin_v);
   }
+  free(p->hist_ttft); free(p->hist_tpot);
   free(p->chunk_img); free(p->host_img); free(p->t);
   free(p->owner); free(p->state); free(p->map_tensor); free(p->map_slot);
   free(p->host_tensor); free(p->host_slot);
@@ -252,6 +262,63 @@ int orc_tensor_unmap_chunks(orc_pool* p, int32_t id, int32_t first, int32_t n) {
   if (first < live) return ORC_INVALID;
   for (int32_t i = 0; i < n; i++) if (t->table[first + i] == ENTRY_NONE) return ORC_UNMAPPED;
   for (int32_t i = 0; i < n; i++) { release_entry(p, t->table[first + i]); t->table[first + i] = ENTRY_NONE; }
+  return ORC_OK;
+}
+
+/* ---- logical host buffer (Sec. 2.3.2 "SLO-aware Buffer Scaling Policy") ------------------------ */
+
+int orc_pool_set_logical_host_slots(orc_pool* p, int32_t n) {
+  if (n < 0 || n > p->n_host) return ORC_RANGE;
+  p->logical_host = n;
+  return ORC_OK;
+}
+
+int32_t orc_pool_get_logical_host_slots(orc_pool* p) { return p->logical_host; }
+
+int orc_pool_slo_configure(orc_pool* p, double ttft_slo, double tpot_slo, double alpha, int32_t window, int32_t threshold) {
+  if (!(ttft_slo > 0) || !(tpot_slo > 0) || !(alpha > 1) || window < 1 || threshold < 1 || threshold > window)
+    return ORC_INVALID;
+  p->slo_on = 1;
+  p->slo_ttft = ttft_slo; p->slo_tpot = tpot_slo; p->slo_alpha = alpha;
+  p->slo_window = window; p->slo_threshold = threshold;
+  p->hist_n = p->hist_start = 0;
+  return ORC_OK;
+}
+
+/* The whole history is kept and recounted at every call: of the observations made since the last
+ * change of size, the newest `window` are looked at; `threshold` of them over the time-per-output-
+ * token SLO shrink the buffer (that case first), else `threshold` over the time-to-first-token SLO
+ * grow it. A negative latency is "none measured" and never a violation. */
+int orc_pool_slo_observe(orc_pool* p, double ttft, double tpot, int32_t* logical_out) {
+  if (!p->slo_on || ttft != ttft || tpot != tpot) return ORC_INVALID;
+  if (p->hist_n == p->hist_cap) {
+    p->hist_cap = p->hist_cap ? 2 * p->hist_cap : 64;
+    p->hist_ttft = (double*)realloc(p->hist_ttft, sizeof(double) * (size_t)p->hist_cap);
+    p->hist_tpot = (double*)realloc(p->hist_tpot, sizeof(double) * (size_t)p->hist_cap);
+  }
+  p->hist_ttft[p->hist_n] = ttft;
+  p->hist_tpot[p->hist_n] = tpot;
+  p->hist_n++;
+  int64_t from = p->hist_n - p->slo_window;
+#if ORC_MUTANT == 13
+  from = p->hist_start;                                                    /* window never slides */
+#endif
+  if (from < p->hist_start) from = p->hist_start;
+  int over_ttft = 0, over_tpot = 0;
+  for (int64_t i = from; i < p->hist_n; i++) {
+    if (p->hist_ttft[i] > p->slo_ttft) over_ttft++;
+    if (p->hist_tpot[i] > p->slo_tpot) over_tpot++;
+  }
+  if (over_tpot >= p->slo_threshold) {
+    p->logical_host = (int32_t)floor((double)p->logical_host / p->slo_alpha);
+    p->hist_start = p->hist_n;
+  } else if (over_ttft >= p->slo_threshold) {
+    double base = p->logical_host < 1 ? 1.0 : (double)p->logical_host;
+    double grown = ceil(base * p->slo_alpha);
+    p->logical_host = grown > (double)p->n_host ? p->n_host : (int32_t)grown;
+    p->hist_start = p->hist_n;
+  }
+  if (logical_out) *logical_out = p->logical_host;
   return ORC_OK;
 }
 
@@ -486,6 +553,7 @@ int orc_chunk_offload(orc_pool* p, int32_t id, int32_t first, int32_t n) {
   int32_t free_slots = 0;
   for (int32_t s = 0; s < p->n_host; s++) if (p->host_tensor[s] < 0) free_slots++;
   if (free_slots < n) return ORC_HOST_FULL;
+  if (p->n_host - free_slots + n > p->logical_host) return ORC_HOST_FULL;   /* Sec. 2.3.2: logical buffer */
   int32_t hs = 0;
   for (int32_t i = 0; i < n; i++) {
     while (p->host_tensor[hs] >= 0) hs++;

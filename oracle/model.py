@@ -37,6 +37,10 @@ def load(path: str | None = None) -> C.CDLL:
     lib.orc_tensor_acquire.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_uint32, _i32p]
     lib.orc_tensor_is_released.argtypes = [C.c_void_p, C.c_int32]
     lib.orc_kv_premap_next.argtypes = [C.c_void_p, _i32p, C.c_int32, C.c_uint32, _i32p]
+    lib.orc_pool_set_logical_host_slots.argtypes = [C.c_void_p, C.c_int32]
+    lib.orc_pool_get_logical_host_slots.argtypes = [C.c_void_p]
+    lib.orc_pool_slo_configure.argtypes = [C.c_void_p, C.c_double, C.c_double, C.c_double, C.c_int32, C.c_int32]
+    lib.orc_pool_slo_observe.argtypes = [C.c_void_p, C.c_double, C.c_double, _i32p]
     lib.orc_tensor_map_chunks.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _i32p, C.c_uint32]
     lib.orc_tensor_unmap_chunks.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
     lib.orc_pool_transfer.argtypes = [C.c_void_p, _i32p, C.c_int32, C.c_int]
@@ -128,6 +132,21 @@ class OraclePool:
         a, p = _i32(ids)
         out = C.c_int32(0)
         rc = self.lib.orc_kv_premap_next(self.h, p, a.size, int(flags), C.byref(out))
+        return rc, out.value
+
+    def set_logical_host_slots(self, n):
+        return self.lib.orc_pool_set_logical_host_slots(self.h, int(n))
+
+    def logical_host_slots(self):
+        return self.lib.orc_pool_get_logical_host_slots(self.h)
+
+    def slo_configure(self, ttft_slo, tpot_slo, alpha=2.0, window=5, threshold=3):
+        return self.lib.orc_pool_slo_configure(self.h, float(ttft_slo), float(tpot_slo), float(alpha), int(window),
+                                               int(threshold))
+
+    def slo_observe(self, ttft, tpot):
+        out = C.c_int32(0)
+        rc = self.lib.orc_pool_slo_observe(self.h, float(ttft), float(tpot), C.byref(out))
         return rc, out.value
 
     def map_chunks(self, tid, first, n, chunk_ids=None, flags=0):

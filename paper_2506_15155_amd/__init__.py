@@ -10,7 +10,8 @@ from .binding import (  # noqa: F401
     ellm_pool_create, ellm_pool_destroy, ellm_tensor_create, ellm_tensor_destroy,
     ellm_tensor_map_chunks, ellm_tensor_unmap_chunks, ellm_pool_transfer, ellm_pool_set_act_busy,
     ellm_kv_append, ellm_decode_attention, ellm_kv_append_decode, ellm_tensor_release, ellm_tensor_acquire,
-    ellm_tensor_is_released, ellm_kv_premap_next, ellm_pool_flush_tables, ellm_chunk_deflate_to_host, ellm_chunk_inflate_from_host,
+    ellm_tensor_is_released, ellm_kv_premap_next, ellm_pool_flush_tables, ellm_pool_set_logical_host_slots,
+    ellm_pool_get_logical_host_slots, ellm_pool_slo_configure, ellm_pool_slo_observe, ellm_chunk_deflate_to_host, ellm_chunk_inflate_from_host,
     ellm_pool_sync, ellm_pool_get_geometry, ellm_tensor_get_table, ellm_pool_get_owner_state,
     ellm_pool_get_host_slots, ellm_decode_plan, ellm_pool_set_split_tokens, ellm_pool_self_check,
     ellm_pool_profile_enable, ellm_pool_profile_collect,

@@ -61,6 +61,10 @@ _sigs = {
     "ellm_tensor_is_released": [_vp, C.c_int32],
     "ellm_kv_premap_next": [_vp, _i32p, C.c_int32, C.c_uint32, _i32p],
     "ellm_pool_flush_tables": [_vp, _vp],
+    "ellm_pool_set_logical_host_slots": [_vp, C.c_int32],
+    "ellm_pool_get_logical_host_slots": [_vp, _i32p],
+    "ellm_pool_slo_configure": [_vp, C.c_double, C.c_double, C.c_double, C.c_int32, C.c_int32],
+    "ellm_pool_slo_observe": [_vp, C.c_double, C.c_double, _i32p],
     "ellm_tensor_map_chunks": [_vp, C.c_int32, C.c_int32, C.c_int32, _i32p, C.c_uint32],
     "ellm_tensor_unmap_chunks": [_vp, C.c_int32, C.c_int32, C.c_int32],
     "ellm_pool_transfer": [_vp, _i32p, C.c_int32, C.c_int],
@@ -210,6 +214,31 @@ def ellm_kv_premap_next(pool, ids, flags=0, check=True):
 
 def ellm_pool_flush_tables(pool, stream=None, check=True):
     return _ret(lib.ellm_pool_flush_tables(pool, _stream(stream)), check)
+
+
+def ellm_pool_set_logical_host_slots(pool, n, check=True):
+    return _ret(lib.ellm_pool_set_logical_host_slots(pool, int(n)), check)
+
+
+def ellm_pool_get_logical_host_slots(pool):
+    out = C.c_int32(0)
+    _ret(lib.ellm_pool_get_logical_host_slots(pool, C.byref(out)), True)
+    return out.value
+
+
+def ellm_pool_slo_configure(pool, ttft_slo, tpot_slo, alpha=2.0, window=5, threshold=3, check=True):
+    return _ret(lib.ellm_pool_slo_configure(pool, float(ttft_slo), float(tpot_slo), float(alpha), int(window),
+                                            int(threshold)), check)
+
+
+def ellm_pool_slo_observe(pool, ttft, tpot, check=True):
+    """Returns the logical size after the call (check=True) or (rc, size)."""
+    out = C.c_int32(0)
+    rc = lib.ellm_pool_slo_observe(pool, float(ttft), float(tpot), C.byref(out))
+    if check:
+        _ret(rc, True)
+        return out.value
+    return rc, out.value
 
 
 def ellm_tensor_map_chunks(pool, tid, first_slot, n_slots, chunk_ids=None, flags=0, check=True):

@@ -538,6 +538,27 @@ int ellm_pool_flush_tables(ellm_pool* p, void* stream) {
   return flush_table(p, (hipStream_t)stream);
 }
 
+int ellm_pool_set_logical_host_slots(ellm_pool* p, int32_t n) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  return core_err(p, p->core->set_logical_host_slots(n));
+}
+
+int ellm_pool_get_logical_host_slots(ellm_pool* p, int32_t* n) {
+  if (!p || !n) return set_err(ELLM_ERR_INVALID, "get_logical_host_slots: NULL argument");
+  *n = p->core->logical_host_slots();
+  return ELLM_OK;
+}
+
+int ellm_pool_slo_configure(ellm_pool* p, double ttft_slo, double tpot_slo, double alpha, int32_t window, int32_t threshold) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  return core_err(p, p->core->slo_configure(ttft_slo, tpot_slo, alpha, window, threshold));
+}
+
+int ellm_pool_slo_observe(ellm_pool* p, double ttft, double tpot, int32_t* logical_host_slots) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  return core_err(p, p->core->slo_observe(ttft, tpot, logical_host_slots));
+}
+
 int ellm_decode_plan(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, int32_t* n_split, int32_t* split_tokens) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
   int rc = core_err(p, p->core->decode_check(ids, batch));

@@ -2,6 +2,7 @@
 #include "pool_core.hpp"
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 
 namespace ellm {
@@ -18,6 +19,7 @@ PoolCore::PoolCore(const Geometry& g, const uint8_t* initial_owner) : g_(g) {
     else free_kv_.insert(free_kv_.end(), c);
   }
   for (int32_t s = 0; s < g.n_host_slots; s++) free_host_.insert(free_host_.end(), s);
+  logical_host_ = g.n_host_slots;
   for (int32_t i = 0; i < g.max_tensors; i++) free_ids_.insert(free_ids_.end(), i);
   t_.resize(g.max_tensors);
   table_.assign((size_t)g.max_tensors * g.max_slots, ENTRY_UNMAPPED);
@@ -162,6 +164,50 @@ int PoolCore::tensor_acquire(int64_t need, int64_t max_tokens, uint32_t flags, i
   if (rc) return rc;
   for (int32_t i = 0; i < n; i++) take_chunk(pick[i], id, i);
   *out = id;
+  return OK;
+}
+
+int PoolCore::set_logical_host_slots(int32_t n) {
+  if (n < 0 || n > g_.n_host_slots) return fail(ERR_RANGE, "set_logical_host_slots: outside 0 .. host slots");
+  logical_host_ = n;
+  return OK;
+}
+
+int PoolCore::slo_configure(double ttft_slo, double tpot_slo, double alpha, int32_t window, int32_t threshold) {
+  if (!(ttft_slo > 0) || !(tpot_slo > 0) || !(alpha > 1) || window < 1 || threshold < 1 || threshold > window)
+    return fail(ERR_INVALID, "slo_configure: need positive thresholds, alpha > 1, 1 <= threshold <= window");
+  slo_ = Slo();
+  slo_.on = true;
+  slo_.ttft = ttft_slo; slo_.tpot = tpot_slo; slo_.alpha = alpha;
+  slo_.window = window; slo_.threshold = threshold;
+  return OK;
+}
+
+// One scheduling iteration's latencies (a negative value: none measured in this iteration). A
+// violation event is `threshold` iterations over the SLO among the last `window`; time per output
+// token over -> the buffer shrinks by alpha, time to first token over -> it grows by alpha; both at
+// once -> it shrinks. After a change the count starts again.
+int PoolCore::slo_observe(double ttft, double tpot, int32_t* logical_out) {
+  if (!slo_.on) return fail(ERR_INVALID, "slo_observe: not configured");
+  if (ttft != ttft || tpot != tpot) return fail(ERR_INVALID, "slo_observe: NaN latency");
+  slo_.ttft_hits.push_back(ttft > slo_.ttft ? 1 : 0);
+  slo_.tpot_hits.push_back(tpot > slo_.tpot ? 1 : 0);
+  if ((int32_t)slo_.ttft_hits.size() > slo_.window) {
+    slo_.ttft_hits.erase(slo_.ttft_hits.begin());
+    slo_.tpot_hits.erase(slo_.tpot_hits.begin());
+  }
+  int32_t n_ttft = 0, n_tpot = 0;
+  for (uint8_t h : slo_.ttft_hits) n_ttft += h;
+  for (uint8_t h : slo_.tpot_hits) n_tpot += h;
+  if (n_tpot >= slo_.threshold) {
+    logical_host_ = (int32_t)std::floor((double)logical_host_ / slo_.alpha);
+    slo_.ttft_hits.clear(); slo_.tpot_hits.clear();
+  } else if (n_ttft >= slo_.threshold) {
+    const double grown = std::ceil(std::max(1.0, (double)logical_host_) * slo_.alpha);
+    logical_host_ = (int32_t)std::min<double>(g_.n_host_slots, grown);
+    slo_.ttft_hits.clear(); slo_.tpot_hits.clear();
+  }
+  if (logical_out) *logical_out = logical_host_;
   return OK;
 }
 
@@ -348,6 +394,8 @@ int PoolCore::offload_plan(int32_t id, int32_t first, int32_t n, std::vector<Mov
     if (e <= -2) return fail(ERR_NOT_RESIDENT, "deflate_to_host: slot is already in host memory");
   }
   if ((int32_t)free_host_.size() < n) return fail(ERR_HOST_FULL, "deflate_to_host: not enough free host slots");
+  if (g_.n_host_slots - (int32_t)free_host_.size() + n > logical_host_)
+    return fail(ERR_HOST_FULL, "deflate_to_host: the logical host buffer is full");
   auto it = free_host_.begin();
   for (int32_t i = 0; i < n; i++, ++it) moves.push_back(Move{first + i, row(id)[first + i], *it});
   return OK;

@@ -60,6 +60,13 @@ class PoolCore {
   // available; acquire picks the best-fitting available tensor or maps a fresh one on demand
   int tensor_release(int32_t id);
   int tensor_acquire(int64_t need_tokens, int64_t max_tokens, uint32_t flags, int32_t* out);
+  // logical host buffer (Sec. 2.3.2): offloads may fill at most this many host slots; shrinking it
+  // evicts nothing
+  int set_logical_host_slots(int32_t n);
+  int32_t logical_host_slots() const { return logical_host_; }
+  // SLO-aware scaling of the logical buffer (Sec. 2.3.2)
+  int slo_configure(double ttft_slo, double tpot_slo, double alpha, int32_t window, int32_t threshold);
+  int slo_observe(double ttft, double tpot, int32_t* logical_out);
   // speculative pre-mapping (Sec. 3.1): one chunk for every request whose next token opens an empty slot
   int premap_next(const int32_t* ids, int32_t batch, uint32_t flags, int32_t* n_mapped);
   int map_chunks(int32_t id, int32_t first, int32_t n, const int32_t* chunk_ids, uint32_t flags);
@@ -120,6 +127,13 @@ class PoolCore {
   std::vector<TensorRec> t_;
   std::vector<int32_t> table_;     // max_tensors x max_slots, row-major, ENTRY_UNMAPPED where empty
   std::vector<int64_t> dirty_;
+  int32_t logical_host_ = 0;
+  struct Slo {
+    bool on = false;
+    double ttft = 0, tpot = 0, alpha = 2;
+    int32_t window = 5, threshold = 3;
+    std::vector<uint8_t> ttft_hits, tpot_hits;   // violation flags of the iterations since the last change, newest last
+  } slo_;
   std::vector<uint32_t> stamp_;    // per-chunk / per-tensor marks for duplicate detection
   uint32_t stamp_now_ = 0;
   std::string err_;

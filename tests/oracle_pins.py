@@ -441,6 +441,46 @@ def pin_release_acquire_premap_rules(lib):
     pool.close()
 
 
+def pin_slo_buffer_trace(lib, path):
+    """Replays the hand-worked trace of the logical buffer scaling (Sec. 2.3.2) in tests/golden, then
+    checks that a shrunk logical buffer refuses offloads without evicting what is stored."""
+    pool = make_pool(lib, 8, 8, 64, 16, n_chunks=80, n_host=64, max_tensors=4, max_slots=70)
+    assert pool.slo_observe(1.0, 1.0)[0] == -1                       # not configured yet
+    assert pool.slo_configure(1000.0, 50.0, 2.0, 5, 3) == 0
+    assert pool.logical_host_slots() == 64
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        it, ttft, tpot, want = [x.strip() for x in line.split("|")[:4]]
+        rc, got = pool.slo_observe(float(ttft), float(tpot))
+        assert rc == 0 and got == int(want) == pool.logical_host_slots(), (line, got)
+    # down to nothing and up again: floor(size / 2) ... 1 -> 0, then 0 grows to 2
+    sizes = []
+    for _ in range(8):
+        for _ in range(3):
+            rc, got = pool.slo_observe(0.0, 99.0)
+        sizes.append(got)
+    assert sizes == [32, 16, 8, 4, 2, 1, 0, 0]
+    for _ in range(3):
+        rc, got = pool.slo_observe(5000.0, 0.0)
+    assert got == 2
+    # the logical size limits offloads, and shrinking it evicts nothing
+    _, t = pool.tensor_create(70 * 16)
+    assert pool.map_chunks(t, 0, 6) == 0
+    tok = np.zeros((96, 8, 64), np.uint16)
+    assert pool.append([t], tok, tok, [96]) == 0
+    assert pool.offload(t, 0, 3) == -8 and pool.offload(t, 0, 2) == 0          # two host slots usable
+    assert pool.set_logical_host_slots(1) == 0
+    th, _ = pool.host_slots()
+    assert int((th >= 0).sum()) == 2                                             # still stored
+    assert pool.offload(t, 2, 1) == -8
+    assert pool.set_logical_host_slots(3) == 0 and pool.offload(t, 2, 1) == 0
+    assert pool.set_logical_host_slots(65) == -6 and pool.set_logical_host_slots(-1) == -6
+    assert pool.check_invariants() == 0
+    pool.close()
+
+
 ALL_PINS = [pin_sdpa_library, pin_single_token, pin_zero_query_is_mean, pin_constant_v,
             pin_weights_sum_to_one, pin_two_token_logistic, pin_dominant_key, pin_shift_invariance,
             pin_gqa_grouping, pin_chunked_equals_twin_and_online, pin_layout_bytes,

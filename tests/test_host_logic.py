@@ -37,6 +37,7 @@ class Pair:
         oo, os_, omt, oms = self.orc.owner_state()
         assert np.array_equal(lo, oo) and np.array_equal(ls, os_)
         assert np.array_equal(lmt, omt) and np.array_equal(lms, oms)
+        assert E.ellm_pool_get_logical_host_slots(self.lib) == self.orc.logical_host_slots()
         lt, lsl = E.ellm_pool_get_host_slots(self.lib)
         ot, osl = self.orc.host_slots()
         assert np.array_equal(lt, ot) and np.array_equal(lsl, osl)
@@ -74,11 +75,13 @@ def random_walk(seed, steps=600, **kw):
     rng = np.random.default_rng(seed)
     owner = (rng.random(kw.get("n_chunks", 48)) < 0.35).astype(np.uint8)
     P = Pair(owner=owner, **kw)
+    if seed % 2:
+        assert E.ellm_pool_slo_configure(P.lib, 100.0, 5.0, 2.0, 5, 3, check=False) == 0 == P.orc.slo_configure(100.0, 5.0)
     seen_codes = set()
     for _ in range(steps):
         op = rng.choice(["create", "destroy", "map", "map_ids", "unmap", "transfer", "busy", "append",
-                         "decode", "offload", "fetch", "fetch_ids", "release", "acquire", "premap"],
-                        p=[.07, .03, .14, .07, .03, .07, .07, .18, .05, .07, .05, .03, .05, .05, .04])
+                         "decode", "offload", "fetch", "fetch_ids", "release", "acquire", "premap", "logical", "slo"],
+                        p=[.07, .03, .13, .07, .03, .07, .07, .17, .05, .07, .05, .03, .05, .04, .03, .01, .03])
         alive = [t for t in range(P.max_tensors) if P._alive(t)]
         if alive and rng.random() < 0.8:
             # mostly plausible arguments, so the walk reaches deep states (full host buffer, long tensors)
@@ -159,6 +162,15 @@ def random_walk(seed, steps=600, **kw):
             a = E.ellm_kv_premap_next(P.lib, tids, fl, check=False)
             b = P.orc.premap_next(tids, fl)
             assert a[0] == b[0] and (a[0] != 0 or a[1] == b[1]), (op, a, b)
+            rc = a[0]
+        elif op == "logical":
+            n_l = int(rng.integers(-1, P.n_host + 2))
+            rc = E.ellm_pool_set_logical_host_slots(P.lib, n_l, check=False)
+            assert rc == P.orc.set_logical_host_slots(n_l), op
+        elif op == "slo":
+            lat = (float(rng.choice([-1.0, 10.0, 200.0])), float(rng.choice([-1.0, 1.0, 9.0])))
+            a = E.ellm_pool_slo_observe(P.lib, *lat, check=False)
+            assert a == P.orc.slo_observe(*lat), (op, a)
             rc = a[0]
         elif op == "offload":
             rc = E.ellm_chunk_deflate_to_host(P.lib, tid, first, n, check=False)

@@ -26,6 +26,7 @@ MUTANTS = {
     10: "fetch does not copy the bytes back",
     11: "acquire takes the largest fitting available tensor instead of the smallest",
     12: "release unmaps everything instead of keeping the mapping",
+    13: "SLO window counts every iteration since the last change instead of the last five",
 }
 
 
@@ -33,7 +34,8 @@ MUTANTS = {
 def test_mutant_is_caught(tmp_path, m):
     lib = oracle.load(build.build(force=True, defines=(f"ORC_MUTANT={m}",), out=str(tmp_path / f"mut{m}.so")))
     failed = []
-    pins = list(P.ALL_PINS) + [lambda l: P.pin_inflation_walkthrough(l, os.path.join(GOLDEN, "inflation_walkthrough.txt"))]
+    pins = list(P.ALL_PINS) + [lambda l: P.pin_inflation_walkthrough(l, os.path.join(GOLDEN, "inflation_walkthrough.txt")),
+                               lambda l: P.pin_slo_buffer_trace(l, os.path.join(GOLDEN, "slo_buffer_trace.txt"))]
     for pin in pins:
         try:
             pin(lib)

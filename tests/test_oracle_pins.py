@@ -20,5 +20,9 @@ def test_pin(lib, pin):
     pin(lib)
 
 
+def test_slo_buffer_trace(lib):
+    P.pin_slo_buffer_trace(lib, os.path.join(GOLDEN, "slo_buffer_trace.txt"))
+
+
 def test_inflation_walkthrough(lib):
     P.pin_inflation_walkthrough(lib, os.path.join(GOLDEN, "inflation_walkthrough.txt"))
