@@ -45,6 +45,8 @@ def parse():
                          "offloaded every step, all at once and layer by layer under the attention")
     ap.add_argument("--turnover", action="store_true",
                     help="also time request turnover on the host: release + best-fit acquire against destroy + create + map")
+    ap.add_argument("--vmm-latency", action="store_true",
+                    help="also time the driver's virtual-memory calls per 2 MiB chunk (the paper's mapping mechanism)")
     ap.add_argument("--prefill-append", type=int, default=0, metavar="N",
                     help="also time a multi-token append of N tokens per request and layer")
     return ap.parse_args()
@@ -247,6 +249,11 @@ def main():
         res["prefill_append"] = pre
     if turn:
         res["turnover"] = turn
+    if args.vmm_latency:
+        rc, us = E.ellm_debug_vmm_latency(cfg.chunk_bytes, 256, check=False)
+        res["vmm_us_per_chunk"] = ({"create": round(us[0], 2), "map_and_set_access": round(us[1], 2), "unmap": round(us[2], 2),
+                                    "release": round(us[3], 2), "chunks": 256} if rc == 0
+                                   else {"error": E.ellm_last_error()})
     E.ellm_pool_destroy(pool)
     print(json.dumps(res))
 

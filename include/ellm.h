@@ -335,6 +335,14 @@ int ellm_debug_kv_stream_read(ellm_pool* pool, const ellm_tensor_id* ids, int32_
  * for every setting; bits may differ between settings. */
 int ellm_debug_set_partition(ellm_pool* pool, int32_t tail_percent, int32_t small_tiles);
 
+/* Measurement only: what the paper's own mechanism costs on this GPU (Sec. 2.1.1, Sec. 3.2: chunks
+ * mapped into a reserved virtual range through the driver's virtual-memory calls). Creates
+ * n_chunks (1..4096) physical allocations of chunk_bytes (rounded up to the driver's granularity),
+ * maps each into one reserved range and makes it accessible, clears the range, unmaps and releases
+ * everything. us (host, 4 doubles) receives host microseconds per chunk for: create, map +
+ * set-access, unmap, release. HIP when the driver refuses a call (text in ellm_last_error). */
+int ellm_debug_vmm_latency(uint64_t chunk_bytes, int32_t n_chunks, double* us);
+
 /* O(n) consistency scan of the host state (tables, chunk records, free lists, host slots agree;
  * no chunk backs two slots). Returns 0 when consistent, else a positive rule number. */
 int ellm_pool_self_check(ellm_pool* pool);

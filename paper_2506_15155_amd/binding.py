@@ -65,6 +65,7 @@ _sigs = {
     "ellm_pool_get_logical_host_slots": [_vp, _i32p],
     "ellm_pool_slo_configure": [_vp, C.c_double, C.c_double, C.c_double, C.c_int32, C.c_int32],
     "ellm_pool_slo_observe": [_vp, C.c_double, C.c_double, _i32p],
+    "ellm_debug_vmm_latency": [C.c_uint64, C.c_int32, C.POINTER(C.c_double)],
     "ellm_tensor_map_chunks": [_vp, C.c_int32, C.c_int32, C.c_int32, _i32p, C.c_uint32],
     "ellm_tensor_unmap_chunks": [_vp, C.c_int32, C.c_int32, C.c_int32],
     "ellm_pool_transfer": [_vp, _i32p, C.c_int32, C.c_int],
@@ -239,6 +240,16 @@ def ellm_pool_slo_observe(pool, ttft, tpot, check=True):
         _ret(rc, True)
         return out.value
     return rc, out.value
+
+
+def ellm_debug_vmm_latency(chunk_bytes, n_chunks, check=True):
+    """Host microseconds per chunk: (create, map + set-access, unmap, release)."""
+    us = (C.c_double * 4)()
+    rc = lib.ellm_debug_vmm_latency(int(chunk_bytes), int(n_chunks), us)
+    if check:
+        _ret(rc, True)
+        return tuple(us)
+    return rc, tuple(us)
 
 
 def ellm_tensor_map_chunks(pool, tid, first_slot, n_slots, chunk_ids=None, flags=0, check=True):

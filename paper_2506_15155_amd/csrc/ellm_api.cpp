@@ -5,6 +5,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -801,6 +802,54 @@ int ellm_debug_set_partition(ellm_pool* p, int32_t tail_percent, int32_t small_t
   p->tail_percent = tail_percent;
   p->small_tiles = small_tiles;
   return ELLM_OK;
+}
+
+// The paper's own mechanism, measured for comparison: chunks created as physical allocations and
+// mapped into a reserved virtual range with the driver's virtual-memory calls.
+int ellm_debug_vmm_latency(uint64_t chunk_bytes, int32_t n_chunks, double* us) {
+  if (!us || n_chunks < 1 || n_chunks > 4096 || chunk_bytes == 0) return set_err(ELLM_ERR_INVALID, "vmm_latency: bad argument");
+  using clk = std::chrono::steady_clock;
+  auto since = [](clk::time_point t0) { return std::chrono::duration<double, std::micro>(clk::now() - t0).count(); };
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
+  hipMemAllocationProp prop = {};
+  prop.type = hipMemAllocationTypePinned;
+  prop.location.type = hipMemLocationTypeDevice;
+  prop.location.id = dev;
+  size_t gran = 0;
+  HIP_TRY(hipMemGetAllocationGranularity(&gran, &prop, hipMemAllocationGranularityMinimum), "hipMemGetAllocationGranularity");
+  const size_t cb = ((size_t)chunk_bytes + gran - 1) / gran * gran;
+  void* va = nullptr;
+  HIP_TRY(hipMemAddressReserve(&va, cb * n_chunks, 0, nullptr, 0), "hipMemAddressReserve");
+  std::vector<hipMemGenericAllocationHandle_t> h(n_chunks);
+  hipMemAccessDesc acc = {};
+  acc.location = prop.location;
+  acc.flags = hipMemAccessFlagsProtReadWrite;
+  int created = 0, mapped = 0, rc = ELLM_OK;
+  hipError_t e = hipSuccess;
+  auto t0 = clk::now();
+  for (; created < n_chunks; created++)
+    if ((e = hipMemCreate(&h[created], cb, &prop, 0)) != hipSuccess) break;
+  us[0] = since(t0) / std::max(created, 1);
+  if (e == hipSuccess) {
+    t0 = clk::now();
+    for (; mapped < n_chunks; mapped++) {
+      if ((e = hipMemMap((char*)va + (size_t)mapped * cb, cb, 0, h[mapped], 0)) != hipSuccess) break;
+      if ((e = hipMemSetAccess((char*)va + (size_t)mapped * cb, cb, &acc, 1)) != hipSuccess) { mapped++; break; }
+    }
+    us[1] = since(t0) / std::max(mapped, 1);
+  }
+  if (e == hipSuccess) e = hipMemset(va, 0, cb * n_chunks);       // the mapping is usable
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  t0 = clk::now();
+  for (int i = 0; i < mapped; i++) (void)hipMemUnmap((char*)va + (size_t)i * cb, cb);
+  us[2] = since(t0) / std::max(mapped, 1);
+  t0 = clk::now();
+  for (int i = 0; i < created; i++) (void)hipMemRelease(h[i]);
+  us[3] = since(t0) / std::max(created, 1);
+  (void)hipMemAddressFree(va, cb * n_chunks);
+  if (e != hipSuccess) rc = hip_err(e, "virtual-memory call");
+  return rc;
 }
 
 int ellm_pool_self_check(ellm_pool* p) {
