@@ -29,6 +29,18 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   return u >> 16;
 }
 
+// v + (v of lane ^ 16), v + (v of lane ^ 32): gfx950's row and half-wave swaps exchange the odd rows
+// (upper half) of one register with the even rows (lower half) of another; fed the same value
+// twice they return the two partners side by side, with no trip through the LDS crossbar
+__device__ __forceinline__ float add_xor16(float v) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float add_xor32(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // DPP lane permutations inside a row of 16 lanes
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v) {
@@ -403,9 +415,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
 #pragma unroll
     for (int i = 0; i < G; i++) {
 #pragma unroll
-      for (int off = LPR; off < 64; off <<= 1) {
-#pragma unroll
-        for (int e = 0; e < 8; e++) acc[i][e] += __shfl_xor(acc[i][e], off);
+      for (int e = 0; e < 8; e++) {
+        if (LPR < 16) acc[i][e] += __shfl_xor(acc[i][e], 8);
+        acc[i][e] = add_xor32(add_xor16(acc[i][e]));
       }
       l[i] = wave_sum(l[i]);
     }
