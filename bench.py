@@ -7,7 +7,9 @@ its own, so one step streams 32 different layers' K/V (about 13 GB) and the last
 serve the reads. One step = for every layer: map a chunk ahead for requests about to cross a
 chunk boundary, append one token per request, decode-attend over the whole context.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (whole-step GB/s of algorithmic bytes), ms_per_step, the workload in
+`config`, `roofline` for the attention kernel (HIP-event time per launch against the 8 TB/s HBM peak, plus
+measured read ceilings) and `cpu_baseline` (the fp64 CPU oracle timed on the host cores).
 """
 from __future__ import annotations
 
@@ -59,7 +61,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
-              "(the path needs no collective; sharding is described in DESIGN.md)", file=sys.stderr)
+              "(the path needs no collective and nothing in it spans GPUs)", file=sys.stderr)
         sys.exit(2)
     import torch
     import paper_2506_15155_amd as E
