@@ -532,7 +532,7 @@ __global__ __launch_bounds__(256) void read_kernel(const uint4* __restrict__ src
 }
 
 // the K/V rows a decode over this batch reads, with the same work partition and load shape (one
-// wave per equal share of tiles, 64-row tiles, 128-bit loads), but no arithmetic
+// wave per piece of the same cut, 64-row tiles, 128-bit loads), but no arithmetic
 template <int D>
 __global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __restrict__ sink, BatchArgs a) {
   constexpr int LPR = D / 8, RPW = 64 / LPR, NL = 64 / RPW, ROWB = D * 2;
