@@ -315,6 +315,9 @@ int ellm_pool_set_split_tokens(ellm_pool* pool, int32_t split_tokens);
  * recorded launches, writes their durations in milliseconds to ms (host, cap entries), stores the
  * number recorded in *n and starts over. Not part of the paper's method. */
 int ellm_pool_profile_enable(ellm_pool* pool, int32_t max_records);
+/* Time only every stride-th decode launch (default 1 = all): an event pair costs a few microseconds
+ * of stream time, which a throughput measurement should not pay on every launch. */
+int ellm_pool_profile_stride(ellm_pool* pool, int32_t stride);
 int ellm_pool_profile_collect(ellm_pool* pool, float* ms, int32_t cap, int32_t* n);
 
 /* Calibration kernels for measurement; none computes anything of the method.

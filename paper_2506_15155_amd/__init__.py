@@ -14,7 +14,7 @@ from .binding import (  # noqa: F401
     ellm_pool_get_logical_host_slots, ellm_pool_slo_configure, ellm_pool_slo_observe, ellm_chunk_deflate_to_host, ellm_chunk_inflate_from_host,
     ellm_pool_sync, ellm_pool_get_geometry, ellm_tensor_get_table, ellm_pool_get_owner_state,
     ellm_pool_get_host_slots, ellm_decode_plan, ellm_pool_set_split_tokens, ellm_pool_self_check,
-    ellm_pool_profile_enable, ellm_pool_profile_collect,
+    ellm_pool_profile_enable, ellm_pool_profile_stride, ellm_pool_profile_collect,
     ellm_debug_set_partition, ellm_debug_vmm_latency, ellm_debug_copy, ellm_debug_stream_read, ellm_debug_kv_stream_read,
     ellm_last_error,
     ELLM_OWNER_KV, ELLM_OWNER_ACT, ELLM_CHUNK_FREE, ELLM_CHUNK_MAPPED, ELLM_CHUNK_BUSY,

@@ -87,6 +87,7 @@ _sigs = {
     "ellm_debug_copy": [_vp, _vp, C.c_uint64, _vp],
     "ellm_debug_stream_read": [_vp, C.c_uint64, _vp, _vp],
     "ellm_debug_kv_stream_read": [_vp, _i32p, C.c_int32, _vp, _vp],
+    "ellm_pool_profile_stride": [_vp, C.c_int32],
     "ellm_pool_profile_enable": [_vp, C.c_int32],
     "ellm_pool_profile_collect": [_vp, C.POINTER(C.c_float), C.c_int32, _i32p],
 }
@@ -354,6 +355,10 @@ def ellm_pool_self_check(pool):
 
 def ellm_pool_profile_enable(pool, max_records, check=True):
     return _ret(lib.ellm_pool_profile_enable(pool, int(max_records)), check)
+
+
+def ellm_pool_profile_stride(pool, stride, check=True):
+    return _ret(lib.ellm_pool_profile_stride(pool, int(stride)), check)
 
 
 def ellm_pool_profile_collect(pool, cap):

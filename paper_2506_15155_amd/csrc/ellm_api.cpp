@@ -83,6 +83,7 @@ struct ellm_pool {
   // optional timing of the partial (dominant) kernel with events on the caller's stream
   std::vector<hipEvent_t> prof_ev;     // 2 per record
   int32_t prof_used = 0;
+  int32_t prof_stride = 1, prof_phase = 0;   // every prof_stride-th launch is timed
 
   // scratch reused across calls
   std::vector<int32_t> n_eff;
@@ -611,7 +612,11 @@ static int decode_impl(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, c
 
   const ellm::PoolView pv = view_of(p);
   for (const ellm::BatchArgs& a : launches) {
-    const bool prof = (size_t)(p->prof_used + 1) * 2 <= p->prof_ev.size();
+    bool prof = (size_t)(p->prof_used + 1) * 2 <= p->prof_ev.size();
+    if (prof && p->prof_stride > 1) {
+      prof = p->prof_phase == 0;
+      p->prof_phase = (p->prof_phase + 1) % p->prof_stride;
+    }
     if (prof) HIP_TRY(hipEventRecord(p->prof_ev[2 * p->prof_used], stream), "hipEventRecord(profile)");
     int e = ellm::launch_decode_partial(pv, q, k_new, v_new, p->d_ws, scale_log2, a, stream);
     if (e) return hip_err((hipError_t)e, "decode partial launch");
@@ -747,6 +752,13 @@ int ellm_pool_profile_enable(ellm_pool* p, int32_t max_records) {
     HIP_TRY(hipEventCreate(&e), "hipEventCreate(profile)");
     p->prof_ev.push_back(e);
   }
+  return ELLM_OK;
+}
+
+int ellm_pool_profile_stride(ellm_pool* p, int32_t stride) {
+  if (!p || stride < 1) return set_err(ELLM_ERR_INVALID, "profile_stride: bad argument");
+  p->prof_stride = stride;
+  p->prof_phase = 0;
   return ELLM_OK;
 }
 
