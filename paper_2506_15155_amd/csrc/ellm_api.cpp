@@ -313,8 +313,8 @@ void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0
     const int64_t full = len / Tc, rem = len - full * Tc;
     tiles[i] = (int32_t)(full * tpc + (rem + ellm::TILE_TOKENS - 1) / ellm::TILE_TOKENS);
     total_tiles += tiles[i];
-    a.tensor[i] = ids[i];
-    a.len[i] = (int32_t)len;
+    a.req[i].tensor = ids[i];
+    a.req[i].len = (int32_t)len;
   }
   total_tiles *= p->geom.n_kv_heads;
   const int32_t slots = wave_slots(p);
@@ -332,14 +332,14 @@ void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0
   for (int32_t i = 0; i < n_req; i++) {
     const int64_t n_big = (int64_t)tiles[i] * keep_percent / 100 / big;
     const int64_t n_small = (tiles[i] - n_big * big + small - 1) / small;
-    a.big_prefix[i] = (int32_t)big_prefix;
-    a.small_prefix[i] = (int32_t)small_prefix;
+    a.req[i].big_prefix = (int32_t)big_prefix;
+    a.req[i].small_prefix = (int32_t)small_prefix;
+    a.req[i].n_big = (int32_t)n_big;
+    a.req[i].n_small = (int32_t)n_small;
     big_prefix += n_big;
     small_prefix += n_small;
     most = std::max<int32_t>(most, (int32_t)(n_big + n_small));
   }
-  a.big_prefix[n_req] = (int32_t)big_prefix;
-  a.small_prefix[n_req] = (int32_t)small_prefix;
   a.n_req = n_req;
   a.q_row0 = q_row0;
   a.big_per_head = (int32_t)big_prefix;
@@ -353,8 +353,8 @@ void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0
   if (a.use_piece_req) {
     std::memset(a.piece_req, 0, sizeof(a.piece_req));
     for (int32_t i = 0; i < n_req; i++) {
-      for (int32_t k = a.big_prefix[i]; k < a.big_prefix[i + 1]; k++) a.piece_req[k >> 2] |= (uint32_t)i << ((k & 3) * 8);
-      for (int32_t k = a.small_prefix[i]; k < a.small_prefix[i + 1]; k++) {
+      for (int32_t k = a.req[i].big_prefix; k < a.req[i].big_prefix + a.req[i].n_big; k++) a.piece_req[k >> 2] |= (uint32_t)i << ((k & 3) * 8);
+      for (int32_t k = a.req[i].small_prefix; k < a.req[i].small_prefix + a.req[i].n_small; k++) {
         const int32_t t = (int32_t)big_prefix + k;
         a.piece_req[t >> 2] |= (uint32_t)i << ((t & 3) * 8);
       }
@@ -573,7 +573,7 @@ int ellm_decode_plan(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, int
     per_wave = std::max(per_wave, a.tiles_big);
     if (n_split)
       for (int32_t i = 0; i < nb; i++)
-        n_split[b0 + i] = a.big_prefix[i + 1] - a.big_prefix[i] + a.small_prefix[i + 1] - a.small_prefix[i];
+        n_split[b0 + i] = a.req[i].n_big + a.req[i].n_small;
   }
   if (split_tokens) *split_tokens = per_wave * ellm::TILE_TOKENS;
   return ELLM_OK;

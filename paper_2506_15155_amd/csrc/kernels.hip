@@ -165,38 +165,51 @@ __device__ __forceinline__ int32_t tiles_of(int32_t len, int32_t Tc, int32_t til
   return full * tiles_per_chunk + (rest + TILE_TOKENS - 1) / TILE_TOKENS;
 }
 
-// request b with prefix[b] <= pos < prefix[b + 1] (wave-uniform result)
-__device__ __forceinline__ int find_request(const int32_t* prefix, int n_req, int pos, int lane) {
+// request b whose pieces of one phase include number pos: prefix[b] <= pos < prefix[b + 1]
+// (wave-uniform result)
+__device__ __forceinline__ int find_request(const BatchArgs& a, bool small, int pos, int lane) {
   int cnt = 0;
-  for (int base = 0; base < n_req; base += 64) {
+  for (int base = 0; base < a.n_req; base += 64) {
     const int i = base + lane;
-    cnt += __popcll(__ballot(i < n_req && prefix[i] <= pos));
+    const bool below = i < a.n_req && (small ? a.req[i].small_prefix : a.req[i].big_prefix) <= pos;
+    cnt += __popcll(__ballot(below));
   }
   return __builtin_amdgcn_readfirstlane(cnt - 1);
 }
 
-// which piece a workgroup handles: kv head, request, partial slot, first tile, number of tiles
-struct Piece { int32_t g, b, j, tile0, n_tiles; };
+// which piece a workgroup handles: kv head, request, partial slot, first tile, number of tiles, and
+// the request's length and tensor handle
+struct Piece { int32_t g, b, j, tile0, n_tiles, len, tensor; };
+
+// Every level of dependent scalar loads costs a wave about a microsecond before its first K/V
+// request can go out, and while the memory system is saturated more than that, so the look-up is
+// written to need few levels: the launch header, then one word of the request table, then
+// everything about the request at once (no branch between the loads: both phases' prefix
+// entries are fetched and the right one is selected afterwards).
 __device__ __forceinline__ Piece locate_piece(const PoolView& pv, const BatchArgs& a, int32_t index, int lane) {
-  const int32_t n_big_total = a.big_per_head * pv.n_kv_heads;
+  const int32_t big_ph = a.big_per_head, small_ph = a.small_per_head;
+  const int32_t tiles_big = a.tiles_big, tiles_small = a.tiles_small;
+  const int32_t n_big_total = big_ph * pv.n_kv_heads;
   const bool small = index >= n_big_total;
   const int32_t idx = small ? index - n_big_total : index;
-  const int32_t per_head = small ? a.small_per_head : a.big_per_head;
+  const int32_t per_head = small ? small_ph : big_ph;
   Piece p;
   p.g = idx / per_head;
   const int32_t rem = idx - p.g * per_head;
-  const int32_t* prefix = small ? a.small_prefix : a.big_prefix;
   if (a.use_piece_req) {
-    const int32_t i = small ? a.big_per_head + rem : rem;
+    const int32_t i = small ? big_ph + rem : rem;
     p.b = (a.piece_req[i >> 2] >> ((i & 3) * 8)) & 0xff;
   } else {
-    p.b = find_request(prefix, a.n_req, rem, lane);
+    p.b = find_request(a, small, rem, lane);
   }
-  const int32_t j = rem - prefix[p.b];
-  const int32_t n_big = a.big_prefix[p.b + 1] - a.big_prefix[p.b];
-  const int32_t tiles = tiles_of(a.len[p.b], pv.tokens_per_chunk, pv.tiles_per_chunk);
-  p.tile0 = small ? n_big * a.tiles_big + j * a.tiles_small : j * a.tiles_big;
-  p.n_tiles = small ? min(a.tiles_small, tiles - p.tile0) : a.tiles_big;
+  const BatchArgs::Req r = a.req[p.b];
+  p.len = r.len;
+  p.tensor = r.tensor;
+  const int32_t j = rem - (small ? r.small_prefix : r.big_prefix);
+  const int32_t n_big = r.n_big;
+  const int32_t tiles = tiles_of(p.len, pv.tokens_per_chunk, pv.tiles_per_chunk);
+  p.tile0 = small ? n_big * tiles_big + j * tiles_small : j * tiles_big;
+  p.n_tiles = small ? min(tiles_small, tiles - p.tile0) : tiles_big;
   p.j = small ? n_big + j : j;
   return p;
 }
@@ -322,10 +335,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
   {
     const Piece pc = locate_piece(pv, a, blockIdx.x, lane);
     const int32_t g = pc.g, b = pc.b, j = pc.j, tile0 = pc.tile0, n_tiles = pc.n_tiles;
-    const int32_t len = a.len[b];
+    const int32_t len = pc.len;
     const int hq0 = g * pv.group + g_first;            // first q head handled here
     // the table row is read-only for the kernel's lifetime: uniform (scalar) loads
-    const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)a.tensor[b] * pv.max_slots);
+    const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)pc.tensor * pv.max_slots);
 
     // first tile: cursor -> (slot, first row, valid rows); its K and V are requested at once
     int32_t slot = tile0 / pv.tiles_per_chunk;
@@ -453,7 +466,7 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const float* __restr
   constexpr int DPL = D / 64;        // output dims per lane
   const int b = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
   const int g = h / group;
-  const int n_part = a.big_prefix[b + 1] - a.big_prefix[b] + a.small_prefix[b + 1] - a.small_prefix[b];
+  const int n_part = a.req[b].n_big + a.req[b].n_small;
   const float* p0 = ws + ((a.ws_slot0 + (int64_t)(b * n_kv_heads + g) * a.max_partials) * group + (h - g * group)) *
                              (D + WS_ROW_PAD);
   const int64_t stride = (int64_t)group * (D + WS_ROW_PAD);
@@ -542,9 +555,9 @@ __global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __
   uint32_t x = 0;
   {
     const Piece pc = locate_piece(pv, a, blockIdx.x, lane);
-    const int32_t g = pc.g, b = pc.b, tile0 = pc.tile0, n_tiles = pc.n_tiles;
-    const int32_t len = a.len[b];
-    const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)a.tensor[b] * pv.max_slots);
+    const int32_t g = pc.g, tile0 = pc.tile0, n_tiles = pc.n_tiles;
+    const int32_t len = pc.len;
+    const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)pc.tensor * pv.max_slots);
     int32_t slot = tile0 / pv.tiles_per_chunk;
     int32_t r = (tile0 - slot * pv.tiles_per_chunk) * TILE_TOKENS;
     for (int32_t it = 0; it < n_tiles; it++) {

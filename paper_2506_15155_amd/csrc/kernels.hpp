@@ -6,7 +6,7 @@
 
 namespace ellm {
 
-constexpr int MAX_LAUNCH_REQ = 192;   // requests described by one launch's kernel arguments (4 KB in all)
+constexpr int MAX_LAUNCH_REQ = 128;   // requests described by one launch's kernel arguments (4 KB in all)
 constexpr int MAX_PIECE_REQ = 512;    // pieces per kv head that the request lookup table covers
 constexpr int MAX_PATCH = 448;        // table entries patched by one launch
 constexpr int TILE_TOKENS = 64;       // rows of K (and V) one wave handles at a time
@@ -45,10 +45,12 @@ struct BatchArgs {
   // request of piece i of a kv head (big pieces first, then small ones), one byte each: lets a wave
   // find its request with one scalar load instead of a search through the prefix arrays
   uint32_t piece_req[MAX_PIECE_REQ / 4];
-  int32_t tensor[MAX_LAUNCH_REQ];
-  int32_t len[MAX_LAUNCH_REQ];
-  int32_t big_prefix[MAX_LAUNCH_REQ + 1];
-  int32_t small_prefix[MAX_LAUNCH_REQ + 1];
+  // per request, one record, so that a wave gets all of it with one round of scalar loads
+  struct Req {
+    int32_t len, tensor;
+    int32_t big_prefix, small_prefix;   // pieces of the requests before this one, per phase
+    int32_t n_big, n_small;             // this request's pieces, per phase
+  } req[MAX_LAUNCH_REQ];
 };
 
 struct AppendArgs {
