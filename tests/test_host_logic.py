@@ -320,3 +320,12 @@ def test_split_plan_depends_only_on_lengths():
         assert E.ellm_decode_plan(P, ids)[1] == 64
         E.ellm_pool_destroy(P)
     assert plans[0] == plans[1]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU measurement: asking for more exits with a message, before any GPU work."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
