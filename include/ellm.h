@@ -332,11 +332,9 @@ int ellm_debug_copy(void* dst, const void* src, uint64_t bytes, void* stream);
 int ellm_debug_stream_read(const void* src, uint64_t bytes, void* sink, void* stream);
 int ellm_debug_kv_stream_read(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, void* sink, void* stream);
 
-/* Parameters of the automatic cut into pieces, for measurements: tail_percent (0..90) of every
- * request's tiles are kept back for small pieces of small_tiles (>= 1) 64-token tiles each. The
- * defaults are what the library was tuned to on MI355X. Results stay within the stated tolerance
- * for every setting; bits may differ between settings. */
-int ellm_debug_set_partition(ellm_pool* pool, int32_t tail_percent, int32_t small_tiles);
+/* Waves of a decode launch as a percentage (1..1600, default 100) of the waves the GPU holds at
+ * once, for measurements of the work partition. Results do not depend on it beyond rounding order. */
+int ellm_debug_set_waves(ellm_pool* pool, int32_t percent);
 
 /* Measurement only: what the paper's own mechanism costs on this GPU (Sec. 2.1.1, Sec. 3.2: chunks
  * mapped into a reserved virtual range through the driver's virtual-memory calls). Creates

@@ -83,7 +83,7 @@ _sigs = {
     "ellm_decode_plan": [_vp, _i32p, C.c_int32, _i32p, _i32p],
     "ellm_pool_set_split_tokens": [_vp, C.c_int32],
     "ellm_pool_self_check": [_vp],
-    "ellm_debug_set_partition": [_vp, C.c_int32, C.c_int32],
+    "ellm_debug_set_waves": [_vp, C.c_int32],
     "ellm_debug_copy": [_vp, _vp, C.c_uint64, _vp],
     "ellm_debug_stream_read": [_vp, C.c_uint64, _vp, _vp],
     "ellm_debug_kv_stream_read": [_vp, _i32p, C.c_int32, _vp, _vp],
@@ -382,5 +382,5 @@ def ellm_debug_kv_stream_read(pool, ids, sink, stream=None, check=True):
     return _ret(lib.ellm_debug_kv_stream_read(pool, p, n, _ptr(sink), _stream(stream)), check)
 
 
-def ellm_debug_set_partition(pool, tail_percent, small_tiles, check=True):
-    return _ret(lib.ellm_debug_set_partition(pool, int(tail_percent), int(small_tiles)), check)
+def ellm_debug_set_waves(pool, percent, check=True):
+    return _ret(lib.ellm_debug_set_waves(pool, int(percent)), check)

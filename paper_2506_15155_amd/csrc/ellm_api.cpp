@@ -77,8 +77,8 @@ struct ellm_pool {
   int64_t out_waits_compute = 0, out_waits_in = 0;
   int32_t split_override = 0;
   int32_t wave_slots = 0;              // resident partial-pass waves on the whole GPU (0 = not asked yet)
-  int32_t tail_percent = 10;           // share of every request's tiles kept for small pieces (automatic cut)
-  int32_t small_tiles = 1;             // tiles per small piece (automatic cut)
+  int32_t waves_percent = 100;         // waves of a launch, as a share of what the GPU holds at once
+  int64_t plan_total_tiles = 0;        // tiles per kv head of the launch planned last
 
   // optional timing of the partial (dominant) kernel with events on the caller's stream
   std::vector<hipEvent_t> prof_ev;     // 2 per record
@@ -292,74 +292,71 @@ int32_t wave_slots(ellm_pool* p) {
   return slots;
 }
 
-// The partition of one launch (at most MAX_LAUNCH_REQ requests). Every (request, kv head) pair is cut
-// into big pieces followed by small ones, one wave and one partial result per piece. The big pieces
-// are sized so that there is about one per resident wave: they fill the GPU once. The last
-// tail_percent of every request's tiles (and whatever does not fill a big piece) become small
-// pieces, which the dispatcher hands out as waves finish, so that faster waves and compute units
-// take more of them. The cut depends only on the batch's lengths, the pool geometry and the
-// device's wave capacity, never on physical chunk ids or on which wave runs which piece: every
-// rounding is reproducible and invariant under remapping.
-// With an override (tests) all pieces have the given size and only the remainder is "small".
+// The partition of one launch (at most MAX_LAUNCH_REQ requests). For each kv head the tiles of all
+// requests form one sequence, dealt out evenly to as many waves as the GPU holds at once (all kv
+// heads together): every wave reads the same amount, all are resident from the start, and a wave
+// whose share crosses from one request into the next writes one partial result for each. The cut
+// depends only on the batch's lengths, the pool geometry and the device's wave capacity, never on
+// physical chunk ids or on which wave runs when: every rounding is reproducible and invariant
+// under remapping.
+// With an override (tests) every wave gets the given number of tokens' worth of tiles.
 void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0, int64_t ws_slot0, ellm::BatchArgs& a,
                  int32_t extra = 0) {
   const int32_t Tc = p->geom.tokens_per_chunk;
   const int32_t tpc = (Tc + ellm::TILE_TOKENS - 1) / ellm::TILE_TOKENS;
-  int64_t total_tiles = 0;
+  int64_t total = 0;
   std::vector<int32_t>& tiles = p->tiles_tmp;
   tiles.resize(n_req);
   for (int32_t i = 0; i < n_req; i++) {
     const int64_t len = p->core->tensor(ids[i])->len + extra;   // extra: tokens of a fused append
     const int64_t full = len / Tc, rem = len - full * Tc;
     tiles[i] = (int32_t)(full * tpc + (rem + ellm::TILE_TOKENS - 1) / ellm::TILE_TOKENS);
-    total_tiles += tiles[i];
     a.req[i].tensor = ids[i];
     a.req[i].len = (int32_t)len;
+    a.req[i].tile_prefix = (int32_t)std::min<int64_t>(total, 0x7fffffff);
+    a.req[i].pad = 0;
+    total += tiles[i];
   }
-  total_tiles *= p->geom.n_kv_heads;
-  const int32_t slots = wave_slots(p);
-  int64_t big, small, keep_percent;
+  int64_t waves;
   if (p->split_override > 0) {
-    big = small = std::max<int64_t>(1, p->split_override / ellm::TILE_TOKENS);
-    keep_percent = 100;
+    const int64_t per = std::max<int64_t>(1, p->split_override / ellm::TILE_TOKENS);
+    waves = (total + per - 1) / per;
   } else {
-    keep_percent = 100 - p->tail_percent;
-    big = std::max<int64_t>(1, (total_tiles * keep_percent / 100 + slots - 1) / slots);
-    small = std::min<int64_t>(big, p->small_tiles);
+    waves = (int64_t)wave_slots(p) * p->waves_percent / 100 / p->geom.n_kv_heads;
   }
-  int64_t big_prefix = 0, small_prefix = 0;
+  waves = std::max<int64_t>(1, std::min<int64_t>(waves, total));
+  const int64_t each = total / waves, more = total - each * waves;
+  // wave that holds tile x: the first `more` waves hold each + 1 tiles, the others each
+  auto wave_of = [&](int64_t x) { return x < more * (each + 1) ? x / (each + 1) : more + (x - more * (each + 1)) / each; };
   int32_t most = 0;
+  int64_t at = 0;
   for (int32_t i = 0; i < n_req; i++) {
-    const int64_t n_big = (int64_t)tiles[i] * keep_percent / 100 / big;
-    const int64_t n_small = (tiles[i] - n_big * big + small - 1) / small;
-    a.req[i].big_prefix = (int32_t)big_prefix;
-    a.req[i].small_prefix = (int32_t)small_prefix;
-    a.req[i].n_big = (int32_t)n_big;
-    a.req[i].n_small = (int32_t)n_small;
-    big_prefix += n_big;
-    small_prefix += n_small;
-    most = std::max<int32_t>(most, (int32_t)(n_big + n_small));
+    const int64_t w0 = wave_of(at), w1 = wave_of(at + tiles[i] - 1);
+    a.req[i].wave_first = (int32_t)w0;
+    a.req[i].n_part = (int32_t)(w1 - w0 + 1);
+    most = std::max<int32_t>(most, a.req[i].n_part);
+    at += tiles[i];
   }
   a.n_req = n_req;
   a.q_row0 = q_row0;
-  a.big_per_head = (int32_t)big_prefix;
-  a.small_per_head = (int32_t)small_prefix;
-  a.tiles_big = (int32_t)big;
-  a.tiles_small = (int32_t)small;
+  a.tiles_per_head = (int32_t)std::min<int64_t>(total, 0x7fffffff);
+  a.waves_per_head = (int32_t)waves;
+  a.tiles_each = (int32_t)each;
+  a.tiles_extra = (int32_t)more;
   a.max_partials = most;
   a.ws_slot0 = (int32_t)ws_slot0;
   a.pad = 0;
-  a.use_piece_req = big_prefix + small_prefix <= ellm::MAX_PIECE_REQ ? 1 : 0;
-  if (a.use_piece_req) {
-    std::memset(a.piece_req, 0, sizeof(a.piece_req));
-    for (int32_t i = 0; i < n_req; i++) {
-      for (int32_t k = a.req[i].big_prefix; k < a.req[i].big_prefix + a.req[i].n_big; k++) a.piece_req[k >> 2] |= (uint32_t)i << ((k & 3) * 8);
-      for (int32_t k = a.req[i].small_prefix; k < a.req[i].small_prefix + a.req[i].n_small; k++) {
-        const int32_t t = (int32_t)big_prefix + k;
-        a.piece_req[t >> 2] |= (uint32_t)i << ((t & 3) * 8);
-      }
+  a.use_wave_req = waves <= ellm::MAX_WAVE_REQ ? 1 : 0;
+  if (a.use_wave_req) {
+    std::memset(a.wave_req, 0, sizeof(a.wave_req));
+    int32_t i = 0;
+    for (int64_t w = 0; w < waves; w++) {
+      const int64_t lo = w * each + std::min<int64_t>(w, more);
+      while (a.req[i].tile_prefix + (int64_t)tiles[i] <= lo) i++;
+      a.wave_req[w >> 2] |= (uint32_t)i << ((w & 3) * 8);
     }
   }
+  p->plan_total_tiles = total;
 }
 
 int64_t launch_ws_slots(const ellm_pool* p, const ellm::BatchArgs& a) {
@@ -570,10 +567,10 @@ int ellm_decode_plan(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, int
   for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
     const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
     plan_launch(p, ids + b0, nb, b0, 0, a);
-    per_wave = std::max(per_wave, a.tiles_big);
+    per_wave = std::max(per_wave, a.tiles_each + (a.tiles_extra > 0 ? 1 : 0));
     if (n_split)
       for (int32_t i = 0; i < nb; i++)
-        n_split[b0 + i] = a.req[i].n_big + a.req[i].n_small;
+        n_split[b0 + i] = a.req[i].n_part;
   }
   if (split_tokens) *split_tokens = per_wave * ellm::TILE_TOKENS;
   return ELLM_OK;
@@ -604,7 +601,8 @@ static int decode_impl(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, c
     plan_launch(p, ids + b0, nb, b0, ws_slots, launches.back(), extra);
     ws_slots += launch_ws_slots(p, launches.back());
     const ellm::BatchArgs& la = launches.back();
-    if (((int64_t)la.big_per_head + la.small_per_head) * p->geom.n_kv_heads > 0x7fffffffll || ws_slots > 0x7fffffffll)
+    if (p->plan_total_tiles > 0x7fffffffll || (int64_t)la.waves_per_head * p->geom.n_kv_heads > 0x7fffffffll ||
+        ws_slots > 0x7fffffffll)
       return set_err(ELLM_ERR_RANGE, "decode_attention: too much work for one call");
   }
   rc = ensure_workspace(p, ws_slots);
@@ -808,11 +806,9 @@ int ellm_debug_kv_stream_read(ellm_pool* p, const ellm_tensor_id* ids, int32_t b
   return leave_compute(p, stream, ids, batch);
 }
 
-int ellm_debug_set_partition(ellm_pool* p, int32_t tail_percent, int32_t small_tiles) {
-  if (!p || tail_percent < 0 || tail_percent > 90 || small_tiles < 1)
-    return set_err(ELLM_ERR_INVALID, "set_partition: bad argument");
-  p->tail_percent = tail_percent;
-  p->small_tiles = small_tiles;
+int ellm_debug_set_waves(ellm_pool* p, int32_t percent) {
+  if (!p || percent < 1 || percent > 1600) return set_err(ELLM_ERR_INVALID, "set_waves: bad argument");
+  p->waves_percent = percent;
   return ELLM_OK;
 }
 

@@ -165,60 +165,45 @@ __device__ __forceinline__ int32_t tiles_of(int32_t len, int32_t Tc, int32_t til
   return full * tiles_per_chunk + (rest + TILE_TOKENS - 1) / TILE_TOKENS;
 }
 
-// request b whose pieces of one phase include number pos: prefix[b] <= pos < prefix[b + 1]
-// (wave-uniform result)
-__device__ __forceinline__ int find_request(const BatchArgs& a, bool small, int pos, int lane) {
+// request whose tiles include tile number pos of a kv head's sequence: the last b with
+// tile_prefix[b] <= pos (wave-uniform result)
+__device__ __forceinline__ int find_request(const BatchArgs& a, int pos, int lane) {
   int cnt = 0;
   for (int base = 0; base < a.n_req; base += 64) {
     const int i = base + lane;
-    const bool below = i < a.n_req && (small ? a.req[i].small_prefix : a.req[i].big_prefix) <= pos;
+    const bool below = i < a.n_req && a.req[i].tile_prefix <= pos;
     cnt += __popcll(__ballot(below));
   }
   return __builtin_amdgcn_readfirstlane(cnt - 1);
 }
 
-// which piece a workgroup handles: kv head, request, partial slot, first tile, number of tiles, and
-// the request's length and tensor handle
-struct Piece { int32_t g, b, j, tile0, n_tiles, len, tensor; };
+// what a workgroup (one wave) handles: kv head g, wave w of that head, n_tiles tiles of the head's
+// sequence from tile t_lo on, the first of which belongs to request b
+struct Share { int32_t g, w, t_lo, n_tiles, b; };
 
 // Every level of dependent scalar loads costs a wave about a microsecond before its first K/V
 // request can go out, and while the memory system is saturated more than that, so the look-up is
 // written to need few levels: the launch header, then one word of the request table, then
-// everything about the request at once (no branch between the loads: both phases' prefix
-// entries are fetched and the right one is selected afterwards).
-__device__ __forceinline__ Piece locate_piece(const PoolView& pv, const BatchArgs& a, int32_t index, int lane) {
-  const int32_t big_ph = a.big_per_head, small_ph = a.small_per_head;
-  const int32_t tiles_big = a.tiles_big, tiles_small = a.tiles_small;
-  const int32_t n_big_total = big_ph * pv.n_kv_heads;
-  const bool small = index >= n_big_total;
-  const int32_t idx = small ? index - n_big_total : index;
-  const int32_t per_head = small ? small_ph : big_ph;
-  Piece p;
-  p.g = idx / per_head;
-  const int32_t rem = idx - p.g * per_head;
-  if (a.use_piece_req) {
-    const int32_t i = small ? big_ph + rem : rem;
-    p.b = (a.piece_req[i >> 2] >> ((i & 3) * 8)) & 0xff;
-  } else {
-    p.b = find_request(a, small, rem, lane);
-  }
-  const BatchArgs::Req r = a.req[p.b];
-  p.len = r.len;
-  p.tensor = r.tensor;
-  const int32_t j = rem - (small ? r.small_prefix : r.big_prefix);
-  const int32_t n_big = r.n_big;
-  const int32_t tiles = tiles_of(p.len, pv.tokens_per_chunk, pv.tiles_per_chunk);
-  p.tile0 = small ? n_big * tiles_big + j * tiles_small : j * tiles_big;
-  p.n_tiles = small ? min(tiles_small, tiles - p.tile0) : tiles_big;
-  p.j = small ? n_big + j : j;
-  return p;
+// everything about the request at once.
+__device__ __forceinline__ Share locate_share(const BatchArgs& a, int32_t index, int lane) {
+  Share s;
+  const int32_t W = a.waves_per_head, each = a.tiles_each, extra = a.tiles_extra;
+  s.g = index / W;
+  s.w = index - s.g * W;
+  s.t_lo = s.w * each + min(s.w, extra);
+  s.n_tiles = each + (s.w < extra ? 1 : 0);
+  if (a.use_wave_req) s.b = (a.wave_req[s.w >> 2] >> ((s.w & 3) * 8)) & 0xff;
+  else s.b = find_request(a, s.t_lo, lane);
+  return s;
 }
 
 // ---------------------------------------------------------------------------------------------
-// decode attention, partial pass (split-K): one wave per piece of a (request, kv head) pair
+// decode attention, partial pass (split-K): one wave per equal share of a kv head's tiles
 //
-// A tile is up to 64 consecutive rows of one chunk of one (request, kv head); a piece is a few
-// consecutive tiles. Per tile:
+// A tile is up to 64 consecutive rows of one chunk of one (request, kv head). A wave walks its
+// share tile by tile; where a request ends inside the share it writes that request's partial
+// result, takes the next request's query, and goes on without letting its loads run dry: the next
+// request's first K tile is already in flight by then. Per tile:
 //   K  64 rows are fetched with coalesced 128-bit loads (LPR = D/8 lanes per row) that write straight
 //      into LDS (no staging registers), then read back transposed: lane t owns token t and reads
 //      its whole row, so a score needs no cross-lane reduction. The query values of the G heads of
@@ -270,11 +255,24 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     const uint32_t off_ = (uint32_t)min(RPW * u + rg, (nvalid) - 1) * ROWB + sub * 16;              \
     dst[u] = *reinterpret_cast<const uint4*>((base) + off_);                                        \
   }
-// move the cursor (slot, r) to the next tile and compute its address and valid rows
+// Move the cursor to the next tile of the share and compute its address and valid rows. `left`
+// counts the tiles of the cursor's request from the cursor tile on; when it is 1 the next tile is
+// the first one of the next request.
 #define ELLM_NEXT_TILE()                                                                            \
-  r += TILE_TOKENS;                                                                                 \
-  if (r >= Tc) { r = 0; slot += 1; }                                                                \
-  nv_next = min(TILE_TOKENS, min(Tc - r, len - (slot * Tc + r)));                                   \
+  if (left == 1) {                                                                                  \
+    cb += 1;                                                                                        \
+    const BatchArgs::Req nx_ = a.req[cb];                                                           \
+    len = nx_.len;                                                                                  \
+    left = tiles_of(len, Tc, pv.tiles_per_chunk);                                                   \
+    trow = (const_i32_ptr)(pv.table + (int64_t)nx_.tensor * pv.max_slots);                          \
+    slot = 0;                                                                                       \
+    r = 0;                                                                                          \
+  } else {                                                                                          \
+    left -= 1;                                                                                      \
+    r += TILE_TOKENS;                                                                               \
+    if (r >= Tc) { r = 0; slot += 1; }                                                              \
+  }                                                                                                 \
+  nv_c = min(TILE_TOKENS, min(Tc - r, len - (slot * Tc + r)));                                      \
   kb = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + ((uint64_t)(g * 2) * Tc + r) * ROWB;
 // scores of one tile (lane = token) and online softmax: leaves the tile's weights, rounded to bf16,
 // in pu[] (one per head, for this lane's token). Consecutive dot products go to different heads'
@@ -332,44 +330,48 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     }                                                                                               \
   }
 
-  {
-    const Piece pc = locate_piece(pv, a, blockIdx.x, lane);
-    const int32_t g = pc.g, b = pc.b, j = pc.j, tile0 = pc.tile0, n_tiles = pc.n_tiles;
-    const int32_t len = pc.len;
-    const int hq0 = g * pv.group + g_first;            // first q head handled here
-    // the table row is read-only for the kernel's lifetime: uniform (scalar) loads
-    const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)pc.tensor * pv.max_slots);
+// query of request b_: lane keeps pair (16 c + lane % 16) of each head in qreg[.][c]
+#define ELLM_LOAD_Q(b_)                                                                             \
+  {                                                                                                 \
+    const uint32_t* qsrc =                                                                          \
+        reinterpret_cast<const uint32_t*>(q + ((int64_t)(a.q_row0 + (b_)) * pv.n_q_heads + hq0) * D); \
+    _Pragma("unroll") for (int i = 0; i < G; i++)                                                   \
+      _Pragma("unroll") for (int c = 0; c < QR; c++) qreg[i][c] = qsrc[i * (D / 2) + c * 16 + (lane & 15)]; \
+  }
+// Fused append: len counts the new token already, but its K/V row is still in k_new / v_new. The wave
+// that reaches the end of a request's sequence takes that row from there (lane's 16-byte piece `sub`
+// of each), puts it where the last tile's loads would have found it, and writes it to the chunk.
+#define ELLM_LOAD_NEW_ROW(b_)                                                                       \
+  if (APPEND) {                                                                                     \
+    const int64_t row16 = ((int64_t)(a.q_row0 + (b_)) * pv.n_kv_heads + g) * LPR + sub;             \
+    kn = k_new[row16];                                                                              \
+    vn = v_new[row16];                                                                              \
+  }
 
-    // first tile: cursor -> (slot, first row, valid rows); its K and V are requested at once
+  {
+    const Share sh = locate_share(a, blockIdx.x, lane);
+    const int32_t g = sh.g, n_tiles = sh.n_tiles;
+    const int hq0 = g * pv.group + g_first;            // first q head handled here
+    // cursor: the tile whose K is in LDS or on its way there. cb: its request; len, trow: that
+    // request's length and table row (read-only for the kernel's lifetime: uniform loads)
+    int32_t cb = sh.b;
+    const BatchArgs::Req first = a.req[cb];
+    int32_t len = first.len;
+    const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)first.tensor * pv.max_slots);
+    const int32_t tile0 = sh.t_lo - first.tile_prefix;
+    int32_t left = tiles_of(len, Tc, pv.tiles_per_chunk) - tile0;
     int32_t slot = tile0 / pv.tiles_per_chunk;
     int32_t r = (tile0 - slot * pv.tiles_per_chunk) * TILE_TOKENS;
-    int32_t nv = min(TILE_TOKENS, min(Tc - r, len - (slot * Tc + r))), nv_next = nv;
+    int32_t nv_c = min(TILE_TOKENS, min(Tc - r, len - (slot * Tc + r)));
     const char* kb = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + ((uint64_t)(g * 2) * Tc + r) * ROWB;
-    ELLM_LOAD_K_TILE(kb, nv)
+    ELLM_LOAD_K_TILE(kb, nv_c)
 
-    // query: lane keeps pair (16 c + lane % 16) of each head in qreg[.][c]
+    // the request being accumulated, and which of its partials this wave writes
+    int32_t b = cb, j = sh.w - first.wave_first;
     uint32_t qreg[G][QR];
-    {
-      const uint32_t* qsrc = reinterpret_cast<const uint32_t*>(q + ((int64_t)(a.q_row0 + b) * pv.n_q_heads + hq0) * D);
-#pragma unroll
-      for (int i = 0; i < G; i++)
-#pragma unroll
-        for (int c = 0; c < QR; c++) qreg[i][c] = qsrc[i * (D / 2) + c * 16 + (lane & 15)];
-    }
-
-    // Fused append: a.len counts the new token already, but its K/V row is still in k_new / v_new.
-    // The wave whose piece ends the sequence fetches that row (lane's 16-byte piece `sub` of each),
-    // puts it where the last tile's loads would have found it, and writes it to the chunk.
-    bool appends = false;
     uint4 kn, vn;
-    if (APPEND) {
-      appends = tile0 + n_tiles == tiles_of(len, Tc, pv.tiles_per_chunk);
-      if (appends) {
-        const int64_t row16 = ((int64_t)(a.q_row0 + b) * pv.n_kv_heads + g) * LPR + sub;
-        kn = k_new[row16];
-        vn = v_new[row16];
-      }
-    }
+    ELLM_LOAD_Q(b)
+    ELLM_LOAD_NEW_ROW(b)
 
     float m[G], l[G], acc[G][8];
 #pragma unroll
@@ -381,13 +383,17 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     bool q_settled = false;
 
     for (int32_t it = 0; it < n_tiles; it++) {
-      // the K tile is the only load outstanding here: wait until it has landed in LDS, then start
-      // this tile's V, which stays in flight while the scores are computed
+      // the K tile (and, after a change of request, the query) is all that is outstanding here:
+      // wait until it has landed in LDS, then start this tile's V, which stays in flight while the
+      // scores are computed
       __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
       __builtin_amdgcn_wave_barrier();
+      const int32_t nv = nv_c;
+      const bool last = left == 1;         // this tile ends its request
+      const bool more = it + 1 < n_tiles;
       uint4 vr[NL];
       ELLM_LOAD_TILE(vr, kb + plane, nv)
-      if (APPEND && appends && it + 1 == n_tiles) {
+      if (APPEND && last) {
         // the new token is row nv - 1 of this tile: K goes into the LDS tile (same swizzle as the
         // loads) and both rows go to the chunk; V replaces what the loads fetched for that row once
         // they have arrived
@@ -410,43 +416,61 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
       // V of this tile must have arrived now (it is the only load outstanding); then the K tile,
       // which has been consumed, is replaced by the next one while V is multiplied
       __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-      if (APPEND && appends && it + 1 == n_tiles) {
+      if (APPEND && last) {
 #pragma unroll
         for (int u = 0; u < NL; u++)
           if (RPW * u + rg >= nv - 1) vr[u] = vn;
       }
-      if (it + 1 < n_tiles) {
+      if (more) {
         ELLM_NEXT_TILE()
-        nv = nv_next;
-        ELLM_LOAD_K_TILE(kb, nv)
+        ELLM_LOAD_K_TILE(kb, nv_c)
       }
       __builtin_amdgcn_sched_barrier(0);
       ELLM_TILE_PV(vr)
-    }
 
-    // every row-group holds the same dims for different tokens under one common maximum: add them up
+      if (last || !more) {
+        // request b ends here, or the share does: write partial j of pair (b, g).
+        // Every row-group holds the same dims for different tokens under one common maximum: add them up
 #pragma unroll
-    for (int i = 0; i < G; i++) {
+        for (int i = 0; i < G; i++) {
 #pragma unroll
-      for (int e = 0; e < 8; e++) {
-        if (LPR < 16) acc[i][e] += __shfl_xor(acc[i][e], 8);
-        acc[i][e] = add_xor32(add_xor16(acc[i][e]));
-      }
-      l[i] = wave_sum(l[i]);
-    }
-    // partial j of pair (b, g): [q head][D accumulators, m, l, 2 unused]
-    float* wout = ws + ((a.ws_slot0 + (int64_t)(b * pv.n_kv_heads + g) * a.max_partials + j) * pv.group + g_first) *
-                           (D + WS_ROW_PAD);
-    if (rg == 0) {
+          for (int e = 0; e < 8; e++) {
+            if (LPR < 16) acc[i][e] += __shfl_xor(acc[i][e], 8);
+            acc[i][e] = add_xor32(add_xor16(acc[i][e]));
+          }
+          l[i] = wave_sum(l[i]);
+        }
+        // [q head][D accumulators, m, l, 2 unused]
+        float* wout = ws + ((a.ws_slot0 + (int64_t)(b * pv.n_kv_heads + g) * a.max_partials + j) * pv.group + g_first) *
+                               (D + WS_ROW_PAD);
+        if (rg == 0) {
 #pragma unroll
-      for (int i = 0; i < G; i++) {
-        float4* dst = reinterpret_cast<float4*>(wout + i * (D + WS_ROW_PAD) + sub * 8);
-        dst[0] = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
-        dst[1] = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
-        if (sub == 0) { wout[i * (D + WS_ROW_PAD) + D] = m[i]; wout[i * (D + WS_ROW_PAD) + D + 1] = l[i]; }
+          for (int i = 0; i < G; i++) {
+            float4* dst = reinterpret_cast<float4*>(wout + i * (D + WS_ROW_PAD) + sub * 8);
+            dst[0] = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+            dst[1] = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
+            if (sub == 0) { wout[i * (D + WS_ROW_PAD) + D] = m[i]; wout[i * (D + WS_ROW_PAD) + D + 1] = l[i]; }
+          }
+        }
+        if (more) {
+          // the cursor is already in the next request, whose first tile this wave holds
+          b = cb;
+          j = 0;
+          ELLM_LOAD_Q(b)
+          ELLM_LOAD_NEW_ROW(b)
+          q_settled = false;
+#pragma unroll
+          for (int i = 0; i < G; i++) {
+            m[i] = NEG_BIG; l[i] = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; e++) acc[i][e] = 0.f;
+          }
+        }
       }
     }
   }
+#undef ELLM_LOAD_Q
+#undef ELLM_LOAD_NEW_ROW
 #undef ELLM_LOAD_TILE
 #undef ELLM_LOAD_K_TILE
 #undef ELLM_NEXT_TILE
@@ -466,7 +490,7 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const float* __restr
   constexpr int DPL = D / 64;        // output dims per lane
   const int b = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
   const int g = h / group;
-  const int n_part = a.req[b].n_big + a.req[b].n_small;
+  const int n_part = a.req[b].n_part;
   const float* p0 = ws + ((a.ws_slot0 + (int64_t)(b * n_kv_heads + g) * a.max_partials) * group + (h - g * group)) *
                              (D + WS_ROW_PAD);
   const int64_t stride = (int64_t)group * (D + WS_ROW_PAD);
@@ -545,7 +569,7 @@ __global__ __launch_bounds__(256) void read_kernel(const uint4* __restrict__ src
 }
 
 // the K/V rows a decode over this batch reads, with the same work partition and load shape (one
-// wave per piece of the same cut, 64-row tiles, 128-bit loads), but no arithmetic
+// wave per share of the same cut, 64-row tiles, 128-bit loads), but no arithmetic
 template <int D>
 __global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __restrict__ sink, BatchArgs a) {
   constexpr int LPR = D / 8, RPW = 64 / LPR, NL = 64 / RPW, ROWB = D * 2;
@@ -554,14 +578,17 @@ __global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __
   const int32_t Tc = pv.tokens_per_chunk;
   uint32_t x = 0;
   {
-    const Piece pc = locate_piece(pv, a, blockIdx.x, lane);
-    const int32_t g = pc.g, tile0 = pc.tile0, n_tiles = pc.n_tiles;
-    const int32_t len = pc.len;
-    const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)pc.tensor * pv.max_slots);
+    const Share sh = locate_share(a, blockIdx.x, lane);
+    const int32_t g = sh.g;
+    int32_t cb = sh.b;
+    BatchArgs::Req rec = a.req[cb];
+    const int32_t tile0 = sh.t_lo - rec.tile_prefix;
+    int32_t left = tiles_of(rec.len, Tc, pv.tiles_per_chunk) - tile0;
     int32_t slot = tile0 / pv.tiles_per_chunk;
     int32_t r = (tile0 - slot * pv.tiles_per_chunk) * TILE_TOKENS;
-    for (int32_t it = 0; it < n_tiles; it++) {
-      const int32_t nv = min(TILE_TOKENS, min(Tc - r, len - (slot * Tc + r)));
+    for (int32_t it = 0; it < sh.n_tiles; it++) {
+      const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)rec.tensor * pv.max_slots);
+      const int32_t nv = min(TILE_TOKENS, min(Tc - r, rec.len - (slot * Tc + r)));
       const char* kb = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + ((uint64_t)(g * 2) * Tc + r) * ROWB;
       const char* vb = kb + (uint64_t)Tc * ROWB;
       uint4 kr[NL], vr[NL];
@@ -573,8 +600,19 @@ __global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __
       }
 #pragma unroll
       for (int u = 0; u < NL; u++) x ^= kr[u].x ^ kr[u].y ^ kr[u].z ^ kr[u].w ^ vr[u].x ^ vr[u].y ^ vr[u].z ^ vr[u].w;
-      r += TILE_TOKENS;
-      if (r >= Tc) { r = 0; slot += 1; }
+      if (it + 1 < sh.n_tiles) {
+        if (left == 1) {
+          cb += 1;
+          rec = a.req[cb];
+          left = tiles_of(rec.len, Tc, pv.tiles_per_chunk);
+          slot = 0;
+          r = 0;
+        } else {
+          left -= 1;
+          r += TILE_TOKENS;
+          if (r >= Tc) { r = 0; slot += 1; }
+        }
+      }
     }
   }
   if (x == 0x9e3779b9u) sink[0] = x;
@@ -634,7 +672,7 @@ int partial_waves_per_cu(int head_dim, int group) {
 template <int D, int G>
 static void launch_partial_t(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
                              float scale_log2, int32_t g_first, const BatchArgs& a, hipStream_t stream) {
-  const unsigned grid = (unsigned)((a.big_per_head + a.small_per_head) * pv.n_kv_heads);
+  const unsigned grid = (unsigned)(a.waves_per_head * pv.n_kv_heads);
   if (k_new)
     hipLaunchKernelGGL((decode_partial_kernel<D, G, true>), dim3(grid), dim3(64), 0, stream, pv, (const uint16_t*)q,
                        (const uint4*)k_new, (const uint4*)v_new, ws, scale_log2, g_first, a);
@@ -662,7 +700,7 @@ static int launch_partial_d(const PoolView& pv, const void* q, const void* k_new
 
 int launch_decode_partial(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
                           float scale_log2, const BatchArgs& a, hipStream_t stream) {
-  if (a.n_req <= 0 || a.big_per_head + a.small_per_head <= 0) return 0;
+  if (a.n_req <= 0 || a.waves_per_head <= 0) return 0;
   return pv.head_dim == 128 ? launch_partial_d<128>(pv, q, k_new, v_new, ws, scale_log2, a, stream)
                             : launch_partial_d<64>(pv, q, k_new, v_new, ws, scale_log2, a, stream);
 }
@@ -698,7 +736,7 @@ int launch_read(const void* src, int64_t bytes, uint32_t* sink, hipStream_t stre
 }
 
 int launch_kv_stream(const PoolView& pv, uint32_t* sink, const BatchArgs& a, hipStream_t stream) {
-  const unsigned grid = (unsigned)((a.big_per_head + a.small_per_head) * pv.n_kv_heads);
+  const unsigned grid = (unsigned)(a.waves_per_head * pv.n_kv_heads);
   if (a.n_req <= 0 || grid == 0) return 0;
   if (pv.head_dim == 128)
     hipLaunchKernelGGL(kv_stream_kernel<128>, dim3(grid), dim3(64), 0, stream, pv, sink, a);

@@ -7,7 +7,7 @@
 namespace ellm {
 
 constexpr int MAX_LAUNCH_REQ = 128;   // requests described by one launch's kernel arguments (4 KB in all)
-constexpr int MAX_PIECE_REQ = 512;    // pieces per kv head that the request lookup table covers
+constexpr int MAX_WAVE_REQ = 512;     // waves per kv head that the request lookup table covers
 constexpr int MAX_PATCH = 448;        // table entries patched by one launch
 constexpr int TILE_TOKENS = 64;       // rows of K (and V) one wave handles at a time
 constexpr int WS_ROW_PAD = 4;         // a partial row is head_dim accumulators, m, l and 2 unused floats
@@ -24,32 +24,34 @@ struct PoolView {
 };
 
 // One decode launch: requests [q_row0, q_row0 + n_req) of the caller's batch.
-// The tiles of every (request, kv head) pair are cut into pieces, one wave and one partial result
-// each: first n_big "big" pieces of tiles_big tiles, then the remaining tiles in "small" pieces of
-// tiles_small tiles (the last one may be shorter). The grid runs all big pieces first, kv head
-// major (index g * big_per_head + big_prefix[b] + j), then all small pieces in the same order: the
-// big pieces fill the GPU once, and the small ones are handed out by the hardware dispatcher as
-// waves finish, which evens out waves and compute units that run at different speeds. Partial j of
-// a pair is big piece j, or small piece j - n_big; the cut is fixed by the plan, so results do not
-// depend on which wave ran when.
+// For every kv head the tiles of all requests, laid end to end in request order, form one sequence
+// of tiles_per_head tiles, which is dealt out evenly to waves_per_head waves: wave w takes
+// tiles_each tiles, the first tiles_extra waves one more, each from where the wave before it
+// stopped. A wave whose share runs from one request into the next writes a partial result for
+// each; so request b gets n_part partials per kv head, numbered from the wave that holds its first
+// tile (wave_first). All waves of a launch are resident at once and have the same amount to read,
+// so none waits for a slot and none is left over at the end. The cut is fixed by the plan, so
+// results do not depend on which wave ran when.
 struct BatchArgs {
   int32_t n_req;
   int32_t q_row0;             // row of the first request in q / out
-  int32_t big_per_head;       // = big_prefix[n_req]
-  int32_t small_per_head;     // = small_prefix[n_req]
-  int32_t tiles_big, tiles_small;
-  int32_t max_partials;       // partial slots per (request, kv head) = most pieces any request has
+  int32_t tiles_per_head;     // tiles of all requests of the launch, for one kv head
+  int32_t waves_per_head;     // <= tiles_per_head
+  int32_t tiles_each, tiles_extra;   // tiles_per_head = waves_per_head * tiles_each + tiles_extra
+  int32_t max_partials;       // partial slots per (request, kv head) = most partials any request has
   int32_t ws_slot0;           // first partial slot of this launch in the workspace
-  int32_t use_piece_req;      // piece_req is filled in (big_per_head + small_per_head <= MAX_PIECE_REQ)
+  int32_t use_wave_req;       // wave_req is filled in (waves_per_head <= MAX_WAVE_REQ)
   int32_t pad;
-  // request of piece i of a kv head (big pieces first, then small ones), one byte each: lets a wave
-  // find its request with one scalar load instead of a search through the prefix arrays
-  uint32_t piece_req[MAX_PIECE_REQ / 4];
+  // request that holds the first tile of wave w of a kv head, one byte each: lets a wave find its
+  // request with one scalar load instead of a search through the prefix entries
+  uint32_t wave_req[MAX_WAVE_REQ / 4];
   // per request, one record, so that a wave gets all of it with one round of scalar loads
   struct Req {
     int32_t len, tensor;
-    int32_t big_prefix, small_prefix;   // pieces of the requests before this one, per phase
-    int32_t n_big, n_small;             // this request's pieces, per phase
+    int32_t tile_prefix;      // tiles of the requests before this one
+    int32_t wave_first;       // wave that holds this request's first tile
+    int32_t n_part;           // waves that hold tiles of this request
+    int32_t pad;
   } req[MAX_LAUNCH_REQ];
 };
 
