@@ -301,12 +301,13 @@ int ellm_pool_get_owner_state(ellm_pool* pool, uint8_t* owner, uint8_t* state,
 /* Per host slot (host arrays of n_host_slots, any may be NULL): the (tensor, slot) stored, else -1. */
 int ellm_pool_get_host_slots(ellm_pool* pool, int32_t* tensor, int32_t* slot);
 /* The partition the next decode over these handles would use: n_split[b] (host array of batch) is
- * the number of pieces (partial results) each (request b, kv head) pair is cut into, *split_tokens
- * the tokens per piece. For tests of the split partition. */
+ * the number of partial results of each (request b, kv head) pair, i.e. the number of waves whose
+ * share of the kv head's tiles holds tiles of the request; *split_tokens is the largest share, in
+ * tokens (a multiple of 64). For tests of the partition. */
 int ellm_decode_plan(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch,
                      int32_t* n_split, int32_t* split_tokens);
-/* Override the tokens per piece (rounded down to whole 64-token tiles, at least one; 0 = automatic).
- * For tests that compare partitions. */
+/* Override the tokens per wave (rounded down to whole 64-token tiles, at least one; 0 = automatic:
+ * as many waves as the GPU holds at once). For tests that compare partitions. */
 int ellm_pool_set_split_tokens(ellm_pool* pool, int32_t split_tokens);
 
 /* Measurement hooks. profile_enable(max_records > 0) makes each decode launch record a pair of

@@ -261,7 +261,7 @@ int leave_migration(ellm_pool* p, const std::vector<ellm::Move>& moves, bool fet
 }
 
 int ensure_workspace(ellm_pool* p, int64_t n_slots) {
-  const size_t need = (size_t)n_slots * p->geom.group * (p->geom.head_dim + ellm::WS_ROW_PAD) * sizeof(float);
+  const size_t need = (size_t)n_slots * p->geom.group * (p->geom.head_dim + ellm::WS_ML) * sizeof(float);
   if (need <= p->ws_bytes) return ELLM_OK;
   if (p->d_ws) {
     HIP_TRY(hipDeviceSynchronize(), "hipDeviceSynchronize(workspace growth)");
@@ -345,7 +345,7 @@ void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0
   a.tiles_extra = (int32_t)more;
   a.max_partials = most;
   a.ws_slot0 = (int32_t)ws_slot0;
-  a.pad = 0;
+  a.ws_slots = 0;
   a.use_wave_req = waves <= ellm::MAX_WAVE_REQ ? 1 : 0;
   if (a.use_wave_req) {
     std::memset(a.wave_req, 0, sizeof(a.wave_req));
@@ -607,6 +607,7 @@ static int decode_impl(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, c
   }
   rc = ensure_workspace(p, ws_slots);
   if (rc) return rc;
+  for (ellm::BatchArgs& la : launches) la.ws_slots = (int32_t)ws_slots;
 
   const ellm::PoolView pv = view_of(p);
   for (const ellm::BatchArgs& a : launches) {

@@ -440,17 +440,23 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
           }
           l[i] = wave_sum(l[i]);
         }
-        // [q head][D accumulators, m, l, 2 unused]
-        float* wout = ws + ((a.ws_slot0 + (int64_t)(b * pv.n_kv_heads + g) * a.max_partials + j) * pv.group + g_first) *
-                               (D + WS_ROW_PAD);
+        // accumulators: one row of D floats per (partial slot, q head), every row a whole number of
+        // cache lines; m and l of all partials sit together behind the rows, two floats each
+        const int64_t row0 = (a.ws_slot0 + (int64_t)(b * pv.n_kv_heads + g) * a.max_partials + j) * pv.group + g_first;
+        float* wout = ws + row0 * D;
+        float* wml = ws + (int64_t)a.ws_slots * pv.group * D + row0 * WS_ML;
         if (rg == 0) {
 #pragma unroll
           for (int i = 0; i < G; i++) {
-            float4* dst = reinterpret_cast<float4*>(wout + i * (D + WS_ROW_PAD) + sub * 8);
+            float4* dst = reinterpret_cast<float4*>(wout + i * D + sub * 8);
             dst[0] = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
             dst[1] = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
-            if (sub == 0) { wout[i * (D + WS_ROW_PAD) + D] = m[i]; wout[i * (D + WS_ROW_PAD) + D + 1] = l[i]; }
           }
+          float mm = m[0], ll = l[0];       // lane `sub` writes head sub's pair
+#pragma unroll
+          for (int i = 1; i < G; i++)
+            if (sub == i) { mm = m[i]; ll = l[i]; }
+          if (sub < G) *reinterpret_cast<float2*>(wml + sub * WS_ML) = make_float2(mm, ll);
         }
         if (more) {
           // the cursor is already in the next request, whose first tile this wave holds
@@ -491,11 +497,12 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const float* __restr
   const int b = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
   const int g = h / group;
   const int n_part = a.req[b].n_part;
-  const float* p0 = ws + ((a.ws_slot0 + (int64_t)(b * n_kv_heads + g) * a.max_partials) * group + (h - g * group)) *
-                             (D + WS_ROW_PAD);
-  const int64_t stride = (int64_t)group * (D + WS_ROW_PAD);
+  const int64_t row0 = (a.ws_slot0 + (int64_t)(b * n_kv_heads + g) * a.max_partials) * group + (h - g * group);
+  const float* p0 = ws + row0 * D;                                            // accumulator rows of this head
+  const float* q0 = ws + (int64_t)a.ws_slots * group * D + row0 * WS_ML;      // their (m, l) pairs
+  const int64_t stride = (int64_t)group * D, qstride = (int64_t)group * WS_ML;
   float M = NEG_BIG;
-  for (int j = lane; j < n_part; j += 64) M = fmaxf(M, p0[j * stride + D]);
+  for (int j = lane; j < n_part; j += 64) M = fmaxf(M, q0[j * qstride]);
   M = wave_max(M);
   float L = 0.f, A[DPL];
 #pragma unroll
@@ -505,8 +512,8 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const float* __restr
     const int jl = j0 + lane;
     float c = 0.f;
     if (jl < n_part) {
-      c = fast_exp2(p0[jl * stride + D] - M);
-      L += p0[jl * stride + D + 1] * c;
+      c = fast_exp2(q0[jl * qstride] - M);
+      L += q0[jl * qstride + 1] * c;
     }
     const int nb = min(64, n_part - j0);
     const float* p = p0 + j0 * stride + lane * DPL;

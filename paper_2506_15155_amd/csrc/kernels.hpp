@@ -10,7 +10,7 @@ constexpr int MAX_LAUNCH_REQ = 128;   // requests described by one launch's kern
 constexpr int MAX_WAVE_REQ = 512;     // waves per kv head that the request lookup table covers
 constexpr int MAX_PATCH = 448;        // table entries patched by one launch
 constexpr int TILE_TOKENS = 64;       // rows of K (and V) one wave handles at a time
-constexpr int WS_ROW_PAD = 4;         // a partial row is head_dim accumulators, m, l and 2 unused floats
+constexpr int WS_ML = 2;              // floats per partial and q head in the (m, l) region of the workspace
 
 // what a kernel needs to turn (tensor, token) into an address
 struct PoolView {
@@ -41,7 +41,7 @@ struct BatchArgs {
   int32_t max_partials;       // partial slots per (request, kv head) = most partials any request has
   int32_t ws_slot0;           // first partial slot of this launch in the workspace
   int32_t use_wave_req;       // wave_req is filled in (waves_per_head <= MAX_WAVE_REQ)
-  int32_t pad;
+  int32_t ws_slots;           // partial slots of the whole call: the (m, l) region starts behind that many accumulator rows
   // request that holds the first tile of wave w of a kv head, one byte each: lets a wave find its
   // request with one scalar load instead of a search through the prefix entries
   uint32_t wave_req[MAX_WAVE_REQ / 4];
