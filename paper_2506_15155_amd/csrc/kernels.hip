@@ -51,14 +51,23 @@ constexpr int DPP_QUAD_XOR2 = 0x4E;        // quad_perm [2,3,0,1]
 constexpr int DPP_ROW_HALF_MIRROR = 0x141; // lane i <-> 7 - i within each 8 lanes
 constexpr int DPP_ROW_MIRROR = 0x140;      // lane i <-> 15 - i within each 16 lanes
 
+__device__ __forceinline__ float max_xor16(float v) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float max_xor32(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// reductions over the 64 lanes, result in every lane: four steps inside the rows of 16 lanes (DPP),
+// then the two swaps across rows
 __device__ __forceinline__ float wave_max(float v) {
   v = fmaxf(v, dpp_f32<DPP_QUAD_XOR1>(v));
   v = fmaxf(v, dpp_f32<DPP_QUAD_XOR2>(v));
   v = fmaxf(v, dpp_f32<DPP_ROW_HALF_MIRROR>(v));
   v = fmaxf(v, dpp_f32<DPP_ROW_MIRROR>(v));
-  v = fmaxf(v, __shfl_xor(v, 16));
-  v = fmaxf(v, __shfl_xor(v, 32));
-  return v;
+  return max_xor32(max_xor16(v));
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -66,9 +75,7 @@ __device__ __forceinline__ float wave_sum(float v) {
   v += dpp_f32<DPP_QUAD_XOR2>(v);
   v += dpp_f32<DPP_ROW_HALF_MIRROR>(v);
   v += dpp_f32<DPP_ROW_MIRROR>(v);
-  v += __shfl_xor(v, 16);
-  v += __shfl_xor(v, 32);
-  return v;
+  return add_xor32(add_xor16(v));
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
