@@ -420,6 +420,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
         q_settled = true;
       }
       ELLM_TILE_SCORES(nv)
+      // where the next tile is: scalar work, done while V is still on its way
+      if (more) {
+        ELLM_NEXT_TILE()
+      }
       // V of this tile must have arrived now (it is the only load outstanding); then the K tile,
       // which has been consumed, is replaced by the next one while V is multiplied
       __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
@@ -429,7 +433,6 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
           if (RPW * u + rg >= nv - 1) vr[u] = vn;
       }
       if (more) {
-        ELLM_NEXT_TILE()
         ELLM_LOAD_K_TILE(kb, nv_c)
       }
       __builtin_amdgcn_sched_barrier(0);
