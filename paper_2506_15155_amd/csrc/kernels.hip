@@ -304,7 +304,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     _Pragma("unroll") for (int i = 0; i < G; i++) settle(s[i]);                                     \
     _Pragma("unroll") for (int i = 0; i < G; i++) {                                                 \
       const float sc = lane < (nvalid) ? s[i] * scale_log2 : -INFINITY;                             \
-      const float mn = fmaxf(m[i], wave_max(sc));                                                   \
+      /* the running maximum is the same in every lane: it lives in a scalar register */           \
+      const float mn = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(fmaxf(m[i], wave_max(sc))))); \
       const float alpha = fast_exp2(m[i] - mn);                                                     \
       m[i] = mn;                                                                                    \
       pu[i] = __float_as_uint(fast_exp2(sc - mn));                                                  \
