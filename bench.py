@@ -267,7 +267,7 @@ def main():
 def read_ceilings(E, torch, pool, dev, ids, partial_bytes, kv_bytes):
     """What plain reads reach on this GPU, for scale: one contiguous read of as many bytes as the
     partial pass moves, and a read-only kernel that walks the same K/V tiles through the same chunk
-    tables with the same cut into pieces (no arithmetic, nothing written)."""
+    tables with the same cut into per-wave shares (no arithmetic, nothing written)."""
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
 
     def timed(fn, n):

@@ -1,5 +1,5 @@
 """GPU parity at the full sizes of the configurations, in the launch configuration bench.py times
-(automatic cut into pieces): every output where the oracle finishes in seconds, otherwise sampled
+(automatic cut into per-wave shares): every output where the oracle finishes in seconds, otherwise sampled
 requests the oracle computes one by one, plus the elastic ten-step twin run."""
 import numpy as np
 import pytest

@@ -104,15 +104,15 @@ def test_other_group_sizes(Hq, Hkv, D):
     B.close()
 
 
-def test_more_pieces_per_head_than_the_lookup_table_holds():
-    """With 64-token pieces a batch of 40 requests makes about 900 pieces per kv head: more than the
-    byte table in the kernel arguments covers, so the waves find their request by searching the
-    prefix array instead."""
+def test_more_waves_per_head_than_the_lookup_table_holds():
+    """With one 64-token tile per wave a batch of 40 requests makes about 900 waves per kv head: more
+    than the byte table in the kernel arguments covers, so the waves find their request by searching
+    the tile prefix sums instead."""
     cfg = W.scaled(W.CONFIGS["llama8b"], batch=40, n_chunks=200, len_lo=1000, len_hi=2000, lognormal_median=1400)
     B, st, ids, out, ref = run_step(cfg, seed=61, split=64)
     n_split, S = E.ellm_decode_plan(B.pool, ids)
     assert S == 64 and int(n_split.sum()) > 512
-    H.check_close(out, ref, "piece search")
+    H.check_close(out, ref, "request search")
     E.ellm_pool_set_split_tokens(B.pool, 0)
     rc, auto = B.decode(ids, st.q)
     assert rc == 0
@@ -121,7 +121,7 @@ def test_more_pieces_per_head_than_the_lookup_table_holds():
 
 
 def test_batch_larger_than_one_launch():
-    """More requests than one launch's argument block describes (256)."""
+    """More requests than one launch's argument block describes (128)."""
     cfg = W.Config("wide", 8, 300, 8, 2, 64, 16 * (2 * 2 * 64 * 2), 700, 32, "uniform", 1, 32)
     B, st, ids, out, ref = run_step(cfg, seed=5)
     H.check_close(out, ref, "batch 300")
