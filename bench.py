@@ -48,6 +48,12 @@ def parse():
                          "offloaded every step, all at once and layer by layer under the attention")
     ap.add_argument("--turnover", action="store_true",
                     help="also time request turnover on the host: release + best-fit acquire against destroy + create + map")
+    ap.add_argument("--pool-memory", default="malloc", choices=["malloc", "vmm"],
+                    help="vmm: the pool's chunks are physical allocations of their own, mapped into one virtual range "
+                         "by the driver in a shuffled order (the paper's mechanism) instead of one plain allocation")
+    ap.add_argument("--placement", default="shuffled", choices=["shuffled", "contiguous"],
+                    help="contiguous: every tensor gets consecutive chunk ids (what a kernel sees under the paper's "
+                         "mechanism: contiguous virtual addresses)")
     ap.add_argument("--vmm-latency", action="store_true",
                     help="also time the driver's virtual-memory calls per 2 MiB chunk (the paper's mapping mechanism)")
     ap.add_argument("--prefill-append", type=int, default=0, metavar="N",
@@ -92,16 +98,22 @@ def main():
     owner = np.zeros(n_chunks, np.uint8)
     owner[rng.random(n_chunks) < 0.125] = 1
     kv_ids = np.flatnonzero(owner == 0).astype(np.int32)
-    rng.shuffle(kv_ids)
-    dev = torch.empty(n_chunks * cfg.chunk_bytes, dtype=torch.uint8, device="cuda")
-    dev.view(torch.int16).fill_(0x7FC0)                    # NaN poison everywhere that is not KV
+    if args.placement == "shuffled":
+        rng.shuffle(kv_ids)
+    dev_bytes = n_chunks * cfg.chunk_bytes
+    if args.pool_memory == "vmm":
+        dev, dev_bytes = E.ellm_debug_vmm_buffer_create(cfg.chunk_bytes, n_chunks, cfg.seed, 0x7FC0)   # an address
+    else:
+        dev = torch.empty(dev_bytes, dtype=torch.uint8, device="cuda")
+        dev.view(torch.int16).fill_(0x7FC0)                # NaN poison everywhere that is not KV
     n_host = 0
     host = None
     if args.migration:
         n_host = n_layers * sum(-(-(int(lens_final[b]) + 64) // Tc) for b in range(0, B, 4))
         host = torch.empty(n_host * cfg.chunk_bytes, dtype=torch.uint8, pin_memory=True)
     pool = E.ellm_pool_create(dev, host, cfg.chunk_bytes, Hq, Hkv, D,
-                              n_layers * B * (2 if args.prefill_append else 1), -(-max_tokens // Tc), owner)
+                              n_layers * B * (2 if args.prefill_append else 1), -(-max_tokens // Tc), owner,
+                              device_bytes=dev_bytes)
     if args.split:
         E.ellm_pool_set_split_tokens(pool, args.split)
 
@@ -213,7 +225,7 @@ def main():
                     "algorithmic_bytes_per_launch": int(partial_bytes)}
 
     if roofline is not None and not args.no_ceilings:
-        roofline.update(read_ceilings(E, torch, pool, dev, ids, partial_bytes, ab["kv"]))
+        roofline.update(read_ceilings(E, torch, pool, dev, dev_bytes, ids, partial_bytes, ab["kv"]))
         roofline["frac_of_measured_read_ceiling"] = round(ach / roofline["contiguous_read_GBps"], 4)
     if roofline is not None and args.config == "llama8b" and n_layers == 32 and not args.split:
         roofline["traffic"] = committed_traffic()
@@ -242,7 +254,11 @@ def main():
         "tokens_per_s_per_layer": round(B * n_layers / (ms_per_step * 1e-3), 1),
         "config": {"workload": f"{args.config}: {Hq}q/{Hkv}kv heads, head_dim {D}, batch {B}, {n_layers} layers, "
                                f"lengths {cfg.length_dist} {cfg.len_lo}..{cfg.len_hi} (mean {float(lens_mid.mean()):.0f}), "
-                               f"{cfg.chunk_bytes >> 10} KiB chunks shuffled in one pool of {n_chunks}, "
+                               f"{cfg.chunk_bytes >> 10} KiB chunks "
+                               + ("shuffled" if args.placement == "shuffled" else "in consecutive runs per tensor")
+                               + f" in one pool of {n_chunks}"
+                               + (" (each chunk a physical allocation of its own, driver-mapped)" if args.pool_memory == "vmm" else "")
+                               + ", "
                                "step = per layer map-ahead + append 1 token/request + decode"
                                + (" (one fused call)" if fused else " (two calls)"),
                    "global_batch": B, "layers": n_layers, "split_tokens": int(S), "work_items_per_layer": n_items,
@@ -261,10 +277,12 @@ def main():
                                     "release": round(us[3], 2), "chunks": 256} if rc == 0
                                    else {"error": E.ellm_last_error()})
     E.ellm_pool_destroy(pool)
+    if args.pool_memory == "vmm":
+        E.ellm_debug_vmm_buffer_destroy(dev)
     print(json.dumps(res))
 
 
-def read_ceilings(E, torch, pool, dev, ids, partial_bytes, kv_bytes):
+def read_ceilings(E, torch, pool, dev, dev_bytes, ids, partial_bytes, kv_bytes):
     """What plain reads reach on this GPU, for scale: one contiguous read of as many bytes as the
     partial pass moves, and a read-only kernel that walks the same K/V tiles through the same chunk
     tables with the same cut into per-wave shares (no arithmetic, nothing written)."""
@@ -281,7 +299,7 @@ def read_ceilings(E, torch, pool, dev, ids, partial_bytes, kv_bytes):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
-    nb = min(int(partial_bytes), dev.numel()) // 16 * 16
+    nb = min(int(partial_bytes), dev_bytes) // 16 * 16
     ms_c = timed(lambda i: E.ellm_debug_stream_read(dev, nb, sink), 40)
     ms_k = timed(lambda i: E.ellm_debug_kv_stream_read(pool, ids[i % len(ids)], sink), 4 * len(ids))
     # a plain copy of known size: the yardstick that scales the FETCH_SIZE / WRITE_SIZE counters

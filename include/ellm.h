@@ -344,6 +344,16 @@ int ellm_debug_set_waves(ellm_pool* pool, int32_t percent);
  * everything. us (host, 4 doubles) receives host microseconds per chunk for: create, map +
  * set-access, unmap, release. HIP when the driver refuses a call (text in ellm_last_error). */
 int ellm_debug_vmm_latency(uint64_t chunk_bytes, int32_t n_chunks, double* us);
+/* A device buffer of n_chunks pieces of chunk_bytes (a multiple of the driver's allocation
+ * granularity, 2 MiB here), each piece a physical allocation of its own, mapped into one reserved
+ * virtual range in an order shuffled by seed and filled with the 16-bit pattern fill16: the
+ * memory a pool sits in under the paper's mechanism, for bandwidth comparisons against one plain
+ * allocation (pass *base as ellm_pool_desc.device_base). The library owns the buffer until
+ * ellm_debug_vmm_buffer_destroy(base), which the caller invokes after destroying every pool in it.
+ * Errors: INVALID (arguments, unknown base), HIP. */
+int ellm_debug_vmm_buffer_create(uint64_t chunk_bytes, int32_t n_chunks, uint32_t seed, uint16_t fill16,
+                                 void** base, uint64_t* bytes);
+int ellm_debug_vmm_buffer_destroy(void* base);
 
 /* O(n) consistency scan of the host state (tables, chunk records, free lists, host slots agree;
  * no chunk backs two slots). Returns 0 when consistent, else a positive rule number. */

@@ -15,7 +15,7 @@ from .binding import (  # noqa: F401
     ellm_pool_sync, ellm_pool_get_geometry, ellm_tensor_get_table, ellm_pool_get_owner_state,
     ellm_pool_get_host_slots, ellm_decode_plan, ellm_pool_set_split_tokens, ellm_pool_self_check,
     ellm_pool_profile_enable, ellm_pool_profile_stride, ellm_pool_profile_collect,
-    ellm_debug_set_waves, ellm_debug_vmm_latency, ellm_debug_copy, ellm_debug_stream_read, ellm_debug_kv_stream_read,
+    ellm_debug_set_waves, ellm_debug_vmm_latency, ellm_debug_vmm_buffer_create, ellm_debug_vmm_buffer_destroy, ellm_debug_copy, ellm_debug_stream_read, ellm_debug_kv_stream_read,
     ellm_last_error,
     ELLM_OWNER_KV, ELLM_OWNER_ACT, ELLM_CHUNK_FREE, ELLM_CHUNK_MAPPED, ELLM_CHUNK_BUSY,
     ELLM_MAP_ALLOW_INFLATE, ELLM_POOL_METADATA_ONLY, ELLM_BF16,

@@ -65,6 +65,8 @@ _sigs = {
     "ellm_pool_get_logical_host_slots": [_vp, _i32p],
     "ellm_pool_slo_configure": [_vp, C.c_double, C.c_double, C.c_double, C.c_int32, C.c_int32],
     "ellm_pool_slo_observe": [_vp, C.c_double, C.c_double, _i32p],
+    "ellm_debug_vmm_buffer_create": [C.c_uint64, C.c_int32, C.c_uint32, C.c_uint16, C.POINTER(C.c_void_p), C.POINTER(C.c_uint64)],
+    "ellm_debug_vmm_buffer_destroy": [_vp],
     "ellm_debug_vmm_latency": [C.c_uint64, C.c_int32, C.POINTER(C.c_double)],
     "ellm_tensor_map_chunks": [_vp, C.c_int32, C.c_int32, C.c_int32, _i32p, C.c_uint32],
     "ellm_tensor_unmap_chunks": [_vp, C.c_int32, C.c_int32, C.c_int32],
@@ -241,6 +243,21 @@ def ellm_pool_slo_observe(pool, ttft, tpot, check=True):
         _ret(rc, True)
         return out.value
     return rc, out.value
+
+
+def ellm_debug_vmm_buffer_create(chunk_bytes, n_chunks, seed=0, fill16=0, check=True):
+    """Returns (base address, bytes); with check=False (rc, base, bytes)."""
+    base, nbytes = C.c_void_p(), C.c_uint64()
+    rc = lib.ellm_debug_vmm_buffer_create(int(chunk_bytes), int(n_chunks), int(seed), int(fill16), C.byref(base),
+                                          C.byref(nbytes))
+    if check:
+        _ret(rc, True)
+        return int(base.value), int(nbytes.value)
+    return rc, int(base.value or 0), int(nbytes.value)
+
+
+def ellm_debug_vmm_buffer_destroy(base, check=True):
+    return _ret(lib.ellm_debug_vmm_buffer_destroy(int(base)), check)
 
 
 def ellm_debug_vmm_latency(chunk_bytes, n_chunks, check=True):

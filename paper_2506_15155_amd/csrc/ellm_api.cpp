@@ -11,6 +11,7 @@
 #include <cstring>
 #include <memory>
 #include <string>
+#include <map>
 #include <vector>
 
 #include "kernels.hpp"
@@ -859,6 +860,86 @@ int ellm_debug_vmm_latency(uint64_t chunk_bytes, int32_t n_chunks, double* us) {
   (void)hipMemAddressFree(va, cb * n_chunks);
   if (e != hipSuccess) rc = hip_err(e, "virtual-memory call");
   return rc;
+}
+
+// A buffer whose 2 MiB (or chunk-sized) pieces are separate physical allocations mapped into one
+// reserved virtual range by the driver, in a shuffled order: what a pool looks like under the
+// paper's mechanism (Sec. 2.1.1, Sec. 3.2) once chunks have been mapped and unmapped for a while.
+namespace {
+struct VmmBuffer {
+  size_t piece = 0;
+  std::vector<hipMemGenericAllocationHandle_t> handles;
+  int mapped = 0;
+};
+std::map<void*, VmmBuffer> g_vmm_buffers;
+}  // namespace
+
+int ellm_debug_vmm_buffer_create(uint64_t chunk_bytes, int32_t n_chunks, uint32_t seed, uint16_t fill16, void** base,
+                                 uint64_t* bytes) {
+  if (!base || !bytes || n_chunks < 1 || n_chunks > (1 << 20) || chunk_bytes == 0)
+    return set_err(ELLM_ERR_INVALID, "vmm_buffer_create: bad argument");
+  *base = nullptr;
+  *bytes = 0;
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
+  hipMemAllocationProp prop = {};
+  prop.type = hipMemAllocationTypePinned;
+  prop.location.type = hipMemLocationTypeDevice;
+  prop.location.id = dev;
+  size_t gran = 0;
+  HIP_TRY(hipMemGetAllocationGranularity(&gran, &prop, hipMemAllocationGranularityMinimum), "hipMemGetAllocationGranularity");
+  if (chunk_bytes % gran)
+    return set_err(ELLM_ERR_INVALID, "vmm_buffer_create: chunk_bytes must be a multiple of the driver's allocation granularity");
+  const size_t cb = (size_t)chunk_bytes;
+  void* va = nullptr;
+  HIP_TRY(hipMemAddressReserve(&va, cb * n_chunks, 0, nullptr, 0), "hipMemAddressReserve");
+  VmmBuffer buf;
+  buf.piece = cb;
+  buf.handles.resize(n_chunks);
+  hipError_t e = hipSuccess;
+  int created = 0;
+  for (; created < n_chunks; created++)
+    if ((e = hipMemCreate(&buf.handles[created], cb, &prop, 0)) != hipSuccess) break;
+  // physical piece order[i] backs virtual piece i
+  std::vector<int32_t> order(n_chunks);
+  for (int32_t i = 0; i < n_chunks; i++) order[i] = i;
+  uint64_t x = 0x9E3779B97F4A7C15ull ^ seed;
+  for (int32_t i = n_chunks - 1; i > 0; i--) {
+    x = x * 6364136223846793005ull + 1442695040888963407ull;
+    std::swap(order[i], order[(int32_t)((x >> 33) % (uint64_t)(i + 1))]);
+  }
+  hipMemAccessDesc acc = {};
+  acc.location = prop.location;
+  acc.flags = hipMemAccessFlagsProtReadWrite;
+  if (e == hipSuccess)
+    for (; buf.mapped < n_chunks; buf.mapped++)
+      if ((e = hipMemMap((char*)va + (size_t)buf.mapped * cb, cb, 0, buf.handles[order[buf.mapped]], 0)) != hipSuccess) break;
+  if (e == hipSuccess) e = hipMemSetAccess(va, cb * n_chunks, &acc, 1);
+  if (e == hipSuccess) e = hipMemsetD16(va, fill16, cb * n_chunks / 2);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    for (int i = 0; i < buf.mapped; i++) (void)hipMemUnmap((char*)va + (size_t)i * cb, cb);
+    for (int i = 0; i < created; i++) (void)hipMemRelease(buf.handles[i]);
+    (void)hipMemAddressFree(va, cb * n_chunks);
+    return hip_err(e, "virtual-memory call");
+  }
+  g_vmm_buffers[va] = std::move(buf);
+  *base = va;
+  *bytes = cb * n_chunks;
+  return ELLM_OK;
+}
+
+int ellm_debug_vmm_buffer_destroy(void* base) {
+  auto it = g_vmm_buffers.find(base);
+  if (it == g_vmm_buffers.end()) return set_err(ELLM_ERR_INVALID, "vmm_buffer_destroy: not a buffer of vmm_buffer_create");
+  HIP_TRY(hipDeviceSynchronize(), "hipDeviceSynchronize");
+  VmmBuffer& b = it->second;
+  const size_t n = b.handles.size();
+  for (int i = 0; i < b.mapped; i++) (void)hipMemUnmap((char*)base + (size_t)i * b.piece, b.piece);
+  for (size_t i = 0; i < n; i++) (void)hipMemRelease(b.handles[i]);
+  (void)hipMemAddressFree(base, b.piece * n);
+  g_vmm_buffers.erase(it);
+  return ELLM_OK;
 }
 
 int ellm_pool_self_check(ellm_pool* p) {

@@ -29,21 +29,29 @@ def out_f64(t: torch.Tensor) -> np.ndarray:
 
 
 class Both:
-    def __init__(self, cfg: W.Config, owner=None, oracle=True, keep_twin=False, poison=True, max_tensors=None):
+    def __init__(self, cfg: W.Config, owner=None, oracle=True, keep_twin=False, poison=True, max_tensors=None,
+                 driver_mapped=False):
         self.cfg = cfg
         nbytes = cfg.n_chunks * cfg.chunk_bytes
-        self.dev = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-        if poison:
-            self.dev.view(torch.int16).fill_(POISON)
+        self.vmm_base = None
+        if driver_mapped:
+            # every chunk a physical allocation of its own, mapped into one virtual range by the driver
+            self.vmm_base, got = E.ellm_debug_vmm_buffer_create(cfg.chunk_bytes, cfg.n_chunks, 5, POISON if poison else 0)
+            assert got == nbytes
+            self.dev = self.vmm_base
         else:
-            self.dev.zero_()
+            self.dev = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+            if poison:
+                self.dev.view(torch.int16).fill_(POISON)
+            else:
+                self.dev.zero_()
         self.host = None
         if cfg.host_slots:
             self.host = torch.empty(cfg.host_slots * cfg.chunk_bytes, dtype=torch.uint8, pin_memory=True)
             self.host.zero_()
         mt = max_tensors or cfg.batch
         self.pool = E.ellm_pool_create(self.dev, self.host, cfg.chunk_bytes, cfg.n_q_heads, cfg.n_kv_heads,
-                                       cfg.head_dim, mt, cfg.max_slots, owner)
+                                       cfg.head_dim, mt, cfg.max_slots, owner, device_bytes=nbytes)
         self.orc = None
         if oracle:
             self.orc = OraclePool(cfg.n_chunks, cfg.chunk_bytes, cfg.host_slots, cfg.n_q_heads, cfg.n_kv_heads,
@@ -53,6 +61,9 @@ class Both:
     def close(self):
         torch.cuda.synchronize()
         E.ellm_pool_destroy(self.pool)
+        if self.vmm_base is not None:
+            E.ellm_debug_vmm_buffer_destroy(self.vmm_base)
+            self.vmm_base = None
         if self.orc:
             self.orc.close()
 
@@ -133,6 +144,11 @@ class Both:
 
     def chunk_bytes_dev(self, c) -> np.ndarray:
         cb = self.cfg.chunk_bytes
+        if self.vmm_base is not None:
+            tmp = torch.empty(cb, dtype=torch.uint8, device="cuda")
+            E.ellm_debug_copy(tmp, self.vmm_base + c * cb, cb)
+            torch.cuda.synchronize()
+            return tmp.cpu().numpy()
         return self.dev[c * cb:(c + 1) * cb].cpu().numpy()
 
     def host_slot_bytes(self, s) -> np.ndarray:

@@ -120,6 +120,36 @@ def test_more_waves_per_head_than_the_lookup_table_holds():
     B.close()
 
 
+def test_pool_in_driver_mapped_memory():
+    """The paper's own mechanism underneath (Sec. 2.1.1, Sec. 3.2): every 2 MiB chunk of the pool is a
+    physical allocation of its own, mapped by the driver into one virtual range in a shuffled order.
+    The library sees one buffer, as always: append, fused append + decode and an offload / fetch
+    round trip must behave exactly as in a plain allocation."""
+    cfg = W.scaled(W.CONFIGS["llama8b"], batch=6, n_chunks=40, len_lo=300, len_hi=1500, lognormal_median=700,
+                   host_slots=4)
+    st = W.draw_step(cfg, 31)
+    B = H.Both(cfg, owner=st.placement.owner if cfg.act_fraction > 0 else None, driver_mapped=True)
+    poison = np.full(cfg.chunk_bytes // 2, H.POISON, np.uint16).view(np.uint8)
+    for c in range(cfg.n_chunks):
+        B.orc.chunk_set_bytes(c, poison)
+    ids = H.load_step(B, st)
+    rc, out, ref = B.append_decode(ids, st.k_new, st.v_new, st.q)
+    assert rc == 0
+    H.check_close(out, ref, "driver-mapped pool, fused call")
+    B.compare_state()
+    tab, _ = E.ellm_tensor_get_table(B.pool, ids[0])
+    resident = [int(c) for c in tab if c >= 0]
+    for c in resident:     # bytes of the chunks, history and new rows, as the oracle has them
+        assert np.array_equal(B.chunk_bytes_dev(c), B.orc.chunk_bytes_of(c)), c
+    assert B.offload(ids[0], 0, 1) == 0
+    assert B.fetch(ids[0], 0, 1) == 0
+    assert E.ellm_pool_sync(B.pool) == 0
+    B.compare_state()
+    rc, again = B.decode(ids, st.q)
+    assert rc == 0 and torch.equal(out, again)
+    B.close()
+
+
 def test_batch_larger_than_one_launch():
     """More requests than one launch's argument block describes (128)."""
     cfg = W.Config("wide", 8, 300, 8, 2, 64, 16 * (2 * 2 * 64 * 2), 700, 32, "uniform", 1, 32)
