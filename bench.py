@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--config", default="llama8b", choices=["llama8b", "mha13b", "long70b", "tiny"])
     ap.add_argument("--layers", type=int, default=0, help="0 = the model's layer count for the shape")
     ap.add_argument("--split", type=int, default=0, help="override tokens per work item (0 = automatic)")
+    ap.add_argument("--waves-percent", type=int, default=0,
+                    help="waves per decode launch as a percentage of what the GPU holds at once (0 = the library's choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--event-stride", type=int, default=7, help="time every n-th attention launch with HIP events")
@@ -116,6 +118,8 @@ def main():
                               device_bytes=dev_bytes)
     if args.split:
         E.ellm_pool_set_split_tokens(pool, args.split)
+    if args.waves_percent:
+        E.ellm_debug_set_waves(pool, args.waves_percent)
 
     gen = torch.Generator(device="cuda")
     gen.manual_seed(cfg.seed)
