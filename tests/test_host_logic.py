@@ -285,6 +285,12 @@ def test_pool_create_rejects_bad_geometry():
     assert E.ellm_pool_create(**bad, check=False)[0] == E.ERR.INVALID
 
 
+def test_driver_mapped_buffer_rejects_bad_arguments_before_any_device_call():
+    assert E.ellm_debug_vmm_buffer_create(0, 4, check=False)[0] == E.ERR.INVALID
+    assert E.ellm_debug_vmm_buffer_create(2 << 20, 0, check=False)[0] == E.ERR.INVALID
+    assert E.ellm_debug_vmm_buffer_destroy(4096, check=False) == E.ERR.INVALID
+
+
 def test_library_exports_every_declared_symbol():
     """Every function include/ellm.h declares is exported by the built library and bound in Python."""
     text = open(os.path.join(ROOT, "include", "ellm.h")).read()
