@@ -307,7 +307,7 @@ int ellm_pool_get_host_slots(ellm_pool* pool, int32_t* tensor, int32_t* slot);
 int ellm_decode_plan(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch,
                      int32_t* n_split, int32_t* split_tokens);
 /* Override the tokens per wave (rounded down to whole 64-token tiles, at least one; 0 = automatic:
- * as many waves as the GPU holds at once). For tests that compare partitions. */
+ * one wave per SIMD of the GPU). For tests that compare partitions. */
 int ellm_pool_set_split_tokens(ellm_pool* pool, int32_t split_tokens);
 
 /* Measurement hooks. profile_enable(max_records > 0) makes each decode launch record a pair of
@@ -333,8 +333,9 @@ int ellm_debug_copy(void* dst, const void* src, uint64_t bytes, void* stream);
 int ellm_debug_stream_read(const void* src, uint64_t bytes, void* sink, void* stream);
 int ellm_debug_kv_stream_read(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, void* sink, void* stream);
 
-/* Waves of a decode launch as a percentage (1..1600, default 100) of the waves the GPU holds at
- * once, for measurements of the work partition. Results do not depend on it beyond rounding order. */
+/* Waves of a decode launch as a percentage (1..1600, default 100) of the library's choice, one
+ * wave per SIMD of the GPU; for measurements of the work partition. Results do not depend on it
+ * beyond rounding order. */
 int ellm_debug_set_waves(ellm_pool* pool, int32_t percent);
 
 /* Measurement only: what the paper's own mechanism costs on this GPU (Sec. 2.1.1, Sec. 3.2: chunks

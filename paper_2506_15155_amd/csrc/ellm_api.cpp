@@ -77,7 +77,7 @@ struct ellm_pool {
   int64_t in_waits_compute = 0, in_waits_out = 0;
   int64_t out_waits_compute = 0, out_waits_in = 0;
   int32_t split_override = 0;
-  int32_t wave_slots = 0;              // resident partial-pass waves on the whole GPU (0 = not asked yet)
+  int32_t wave_slots = 0;              // waves of a decode launch: one per SIMD of the GPU (0 = not asked yet)
   int32_t waves_percent = 100;         // waves of a launch, as a share of what the GPU holds at once
   int64_t plan_total_tiles = 0;        // tiles per kv head of the launch planned last
 
@@ -276,16 +276,19 @@ int ensure_workspace(ellm_pool* p, int64_t n_slots) {
   return ELLM_OK;
 }
 
-// Resident waves of the partial-pass kernel on the whole GPU. Without a device (metadata-only pools,
-// planning calls on a host without GPU) a nominal MI355X figure is used: 256 compute units x 8 waves.
+// Waves of a decode launch: one for every SIMD of the GPU (fewer if the kernel's resources allow
+// fewer). Two waves per SIMD, which the kernel's registers and LDS would allow, measured slower on
+// every workload: the second wave of a SIMD gets its loads served 15 to 50 % more slowly than the
+// first, and it takes bandwidth from it. Without a device (metadata-only pools, planning calls on
+// a host without GPU) a nominal MI355X figure is used: 256 compute units x 4 SIMDs.
 int32_t wave_slots(ellm_pool* p) {
   if (p->wave_slots > 0) return p->wave_slots;
-  int32_t slots = 256 * 8;
+  int32_t slots = 256 * ellm::SIMDS_PER_CU;
   if (!p->metadata_only) {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
-      slots = cus * ellm::partial_waves_per_cu(p->geom.head_dim, p->geom.group);
+      slots = cus * std::min(ellm::SIMDS_PER_CU, ellm::partial_waves_per_cu(p->geom.head_dim, p->geom.group));
     else
       (void)hipGetLastError();
   }
@@ -294,7 +297,7 @@ int32_t wave_slots(ellm_pool* p) {
 }
 
 // The partition of one launch (at most MAX_LAUNCH_REQ requests). For each kv head the tiles of all
-// requests form one sequence, dealt out evenly to as many waves as the GPU holds at once (all kv
+// requests form one sequence, dealt out evenly to as many waves as the GPU has SIMDs (all kv
 // heads together): every wave reads the same amount, all are resident from the start, and a wave
 // whose share crosses from one request into the next writes one partial result for each. The cut
 // depends only on the batch's lengths, the pool geometry and the device's wave capacity, never on

@@ -10,6 +10,7 @@ constexpr int MAX_LAUNCH_REQ = 128;   // requests described by one launch's kern
 constexpr int MAX_WAVE_REQ = 512;     // waves per kv head that the request lookup table covers
 constexpr int MAX_PATCH = 448;        // table entries patched by one launch
 constexpr int TILE_TOKENS = 64;       // rows of K (and V) one wave handles at a time
+constexpr int SIMDS_PER_CU = 4;       // a decode launch runs one wave on each SIMD
 constexpr int WS_ML = 2;              // floats per partial and q head in the (m, l) region of the workspace
 
 // what a kernel needs to turn (tensor, token) into an address
@@ -29,9 +30,10 @@ struct PoolView {
 // tiles_each tiles, the first tiles_extra waves one more, each from where the wave before it
 // stopped. A wave whose share runs from one request into the next writes a partial result for
 // each; so request b gets n_part partials per kv head, numbered from the wave that holds its first
-// tile (wave_first). All waves of a launch are resident at once and have the same amount to read,
-// so none waits for a slot and none is left over at the end. The cut is fixed by the plan, so
-// results do not depend on which wave ran when.
+// tile (wave_first). A launch has one wave for every SIMD of the GPU (a second wave on a SIMD is
+// served markedly worse than the first and slows both down): all are resident at once and have
+// the same amount to read, so none waits for a slot and none is left over at the end. The cut is
+// fixed by the plan, so results do not depend on which wave ran when.
 struct BatchArgs {
   int32_t n_req;
   int32_t q_row0;             // row of the first request in q / out

@@ -321,12 +321,12 @@ def test_split_plan_depends_only_on_lengths():
             ids.append(t)
         ns, S = E.ellm_decode_plan(P, ids)
         plans.append((list(ns), S))
-        # tiles are dealt out evenly to at most 2048 / 8 waves per kv head (the figure assumed without a
-        # device); a wave holds at most S / 64 of them, and each request boundary adds at most one partial
+        # tiles are dealt out evenly to at most 1024 / 8 waves per kv head (one per SIMD; the figure assumed
+        # without a device); a wave holds at most S / 64 of them, and each request boundary adds at most one partial
         tiles = [-(-L // 64) for L in (64, 700, 3000, 8192)]
-        assert S > 0 and S % 64 == 0 and S // 64 == -(-sum(tiles) // 256)
+        assert S > 0 and S % 64 == 0 and S // 64 == -(-sum(tiles) // 128)
         assert all(n >= -(-t // (S // 64)) for n, t in zip(ns, tiles))
-        assert sum(ns) <= 256 + len(tiles) - 1
+        assert sum(ns) <= 128 + len(tiles) - 1
         E.ellm_pool_set_split_tokens(P, 64)
         ns1, S1 = E.ellm_decode_plan(P, ids)
         assert S1 == 64 and list(ns1) == tiles
