@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="0 = the model's layer count for the shape")
     ap.add_argument("--split", type=int, default=0, help="override tokens per work item (0 = automatic)")
     ap.add_argument("--waves-percent", type=int, default=0,
-                    help="waves per decode launch as a percentage of what the GPU holds at once (0 = the library's choice)")
+                    help="waves per decode launch as a percentage of the library's choice, one wave per SIMD (0 = leave it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--event-stride", type=int, default=7, help="time every n-th attention launch with HIP events")
