@@ -111,6 +111,15 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
+// 16-byte load of data that is read once (the K/V stream): marked non-temporal, so that it does not
+// displace what is reused (partials, queries, tables) from the caches on its way through
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+constexpr int CPOL_NT = 2;    // cache-policy operand of the load-to-LDS builtin: non-temporal
+
 typedef const __attribute__((address_space(1))) void* global_cptr_t;
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const int32_t __attribute__((address_space(4)))* const_i32_ptr;
@@ -255,12 +264,12 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     const uint32_t off_ = (uint32_t)min(RPW * u + rg, (nvalid) - 1) * ROWB +                        \
                           (uint32_t)((sx ^ ((RPW * u) % LPR)) * 16);                                \
     __builtin_amdgcn_global_load_lds((global_cptr_t)((base) + off_),                                \
-                                     (lds_ptr_t)(sm_k + u * (RPW * ROWB)), 16, 0, 0);               \
+                                     (lds_ptr_t)(sm_k + u * (RPW * ROWB)), 16, 0, CPOL_NT);         \
   }
 #define ELLM_LOAD_TILE(dst, base, nvalid)                                                           \
   _Pragma("unroll") for (int u = 0; u < NL; u++) {                                                  \
     const uint32_t off_ = (uint32_t)min(RPW * u + rg, (nvalid) - 1) * ROWB + sub * 16;              \
-    dst[u] = *reinterpret_cast<const uint4*>((base) + off_);                                        \
+    dst[u] = load_stream16((base) + off_);                                                          \
   }
 // Move the cursor to the next tile of the share and compute its address and valid rows. `left`
 // counts the tiles of the cursor's request from the cursor tile on; when it is 1 the next tile is
@@ -579,7 +588,7 @@ __global__ __launch_bounds__(256) void read_kernel(const uint4* __restrict__ src
   for (int64_t i = (int64_t)blockIdx.x * 256 * 8 + threadIdx.x; i < n; i += stride) {
     uint4 v[8];
 #pragma unroll
-    for (int u = 0; u < 8; u++) { v[u] = make_uint4(0, 0, 0, 0); if (i + u * 256 < n) v[u] = src[i + u * 256]; }
+    for (int u = 0; u < 8; u++) { v[u] = make_uint4(0, 0, 0, 0); if (i + u * 256 < n) v[u] = load_stream16(src + i + u * 256); }
 #pragma unroll
     for (int u = 0; u < 8; u++) x ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
   }
@@ -613,8 +622,8 @@ __global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __
 #pragma unroll
       for (int u = 0; u < NL; u++) {
         const uint32_t off = (uint32_t)min(RPW * u + rg, nv - 1) * ROWB + sub * 16;
-        kr[u] = *reinterpret_cast<const uint4*>(kb + off);
-        vr[u] = *reinterpret_cast<const uint4*>(vb + off);
+        kr[u] = load_stream16(kb + off);
+        vr[u] = load_stream16(vb + off);
       }
 #pragma unroll
       for (int u = 0; u < NL; u++) x ^= kr[u].x ^ kr[u].y ^ kr[u].z ^ kr[u].w ^ vr[u].x ^ vr[u].y ^ vr[u].z ^ vr[u].w;
