@@ -118,6 +118,10 @@ __device__ __forceinline__ uint4 load_stream16(const void* p) {
   const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
   return make_uint4(t.x, t.y, t.z, t.w);
 }
+__device__ __forceinline__ void store_stream16(void* p, uint4 v) {
+  const u32x4_t t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t*>(p));
+}
 constexpr int CPOL_NT = 2;    // cache-policy operand of the load-to-LDS builtin: non-temporal
 
 typedef const __attribute__((address_space(1))) void* global_cptr_t;
@@ -166,9 +170,9 @@ __global__ __launch_bounds__(256) void kv_append_kernel(PoolView pv, const uint4
   for (int i = threadIdx.x; i < n16; i += 256) {
     const int h = i / LPR, sub = i - h * LPR;
     char* dst = chunk + (uint64_t)(h * 2) * plane_bytes + sub * 16;
-    const uint4 kv = ks[i], vv = vs[i];
-    *reinterpret_cast<uint4*>(dst) = kv;
-    *reinterpret_cast<uint4*>(dst + plane_bytes) = vv;
+    const uint4 kv = load_stream16(ks + i), vv = load_stream16(vs + i);     // read once, written once
+    store_stream16(dst, kv);
+    store_stream16(dst + plane_bytes, vv);
   }
 }
 
