@@ -259,9 +259,17 @@ int orc_tensor_unmap_chunks(orc_pool* p, int32_t id, int32_t first, int32_t n) {
   if (n == 0) return ORC_OK;
   if (first < 0 || (int64_t)first + n > t->n_slots) return ORC_RANGE;
   int64_t live = (t->len + p->tokens_per_chunk - 1) / p->tokens_per_chunk;
+#if ORC_MUTANT == 14
+  live = t->len / p->tokens_per_chunk;                                       /* partly filled slot not counted */
+#endif
   if (first < live) return ORC_INVALID;
   for (int32_t i = 0; i < n; i++) if (t->table[first + i] == ENTRY_NONE) return ORC_UNMAPPED;
-  for (int32_t i = 0; i < n; i++) { release_entry(p, t->table[first + i]); t->table[first + i] = ENTRY_NONE; }
+  for (int32_t i = 0; i < n; i++) {
+#if ORC_MUTANT != 15
+    release_entry(p, t->table[first + i]);
+#endif
+    t->table[first + i] = ENTRY_NONE;
+  }
   return ORC_OK;
 }
 
@@ -485,6 +493,9 @@ int orc_pool_set_act_busy(orc_pool* p, const int32_t* ids, int32_t n, int busy) 
     else { if (p->state[c] != ST_BUSY) return ORC_INVALID; }
     for (int32_t j = 0; j < i; j++) if (ids[j] == c) return ORC_INVALID;
   }
+#if ORC_MUTANT == 16
+  if (!busy) return ORC_OK;                                                  /* chunks never given back */
+#endif
   for (int32_t i = 0; i < n; i++) p->state[ids[i]] = busy ? ST_BUSY : ST_FREE;
   return ORC_OK;
 }

@@ -314,6 +314,81 @@ def pin_allocator_order_and_inflation(lib):
     pool.close()
 
 
+def pin_unmap_rules(lib):
+    """Unmapping undoes a speculative pre-map (Sec. 3.1): only slots behind the live tokens may go;
+    their chunks are FREE again, their entries empty, a host copy in the tail gives its host slot
+    back. A refused call changes nothing."""
+    Tc = 16
+    pool = make_pool(lib, 8, 8, 64, Tc, n_chunks=8, n_host=2, max_tensors=2, max_slots=6)
+    _, t = pool.tensor_create(6 * Tc)
+    assert pool.map_chunks(t, 0, 4, [5, 1, 6, 2]) == 0              # slots 0..3 -> chunks 5, 1, 6, 2
+    tok = np.zeros((Tc + 1, 8, 64), np.uint16)
+    assert pool.append([t], tok, tok, [Tc + 1]) == 0                 # 17 tokens: slots 0 and 1 are live
+    before = [a.copy() for a in pool.owner_state()], pool.table(t)[0].copy()
+
+    def unchanged():
+        now = pool.owner_state()
+        return all(np.array_equal(a, b) for a, b in zip(before[0], now)) and np.array_equal(before[1], pool.table(t)[0])
+
+    assert pool.unmap_chunks(t, 1, 2) == -1 and unchanged()          # slot 1 holds token 16
+    assert pool.unmap_chunks(t, 0, 1) == -1 and unchanged()
+    assert pool.unmap_chunks(t, 3, 2) == -4 and unchanged()          # slot 4 has no chunk
+    assert pool.unmap_chunks(t, 4, 3) == -6 and unchanged()          # past the tensor's 6 slots
+    assert pool.unmap_chunks(t, 2, -1) == -1 and pool.unmap_chunks(7, 2, 1) == -1
+    assert pool.unmap_chunks(t, 5, 0) == 0 and unchanged()
+    # the pre-mapped tail goes: slot 3 (chunk 2) first, then slot 2 (chunk 6) after a trip to the host
+    assert pool.unmap_chunks(t, 3, 1) == 0
+    o, s, mt, ms = pool.owner_state()
+    assert s[2] == 0 and mt[2] == -1 and ms[2] == -1 and o[2] == 0
+    assert list(pool.table(t)[0]) == [5, 1, 6, -1, -1, -1] and pool.table(t)[1] == Tc + 1
+    assert pool.offload(t, 2, 1) == 0
+    assert list(pool.table(t)[0])[2] == -2 and pool.host_slots()[0][0] == t and pool.owner_state()[1][6] == 0
+    assert pool.unmap_chunks(t, 2, 1) == 0
+    assert list(pool.table(t)[0]) == [5, 1, -1, -1, -1, -1]
+    th, ts = pool.host_slots()
+    assert (th == -1).all() and (ts == -1).all()                     # the host slot is free again
+    o, s, mt, ms = pool.owner_state()
+    assert list(s) == [0, 1, 0, 0, 0, 1, 0, 0] and mt[5] == t and ms[1] == 1
+    # the freed chunks are what the pool hands out next (lowest id first), so they really are FREE
+    assert pool.map_chunks(t, 2, 2) == 0 and list(pool.table(t)[0])[2:4] == [0, 2]
+    # a tensor with no token may lose every slot
+    _, u = pool.tensor_create(2 * Tc)
+    assert pool.map_chunks(u, 0, 2) == 0 and pool.unmap_chunks(u, 0, 2) == 0
+    assert list(pool.table(u)[0]) == [-1, -1]
+    assert pool.check_invariants() == 0
+    pool.close()
+
+
+def pin_act_busy_both_ways(lib):
+    """The stand-in for live activations (Sec. 2.2.1 step 2: only chunks of inactive activation
+    tensors can be lent): busy = 1 takes FREE activation chunks out of reach, busy = 0 gives BUSY
+    ones back, after which they can change sides and be mapped. Wrong state or owner: refused,
+    nothing changed."""
+    owner = np.array([0, 1, 1, 1, 0, 1], np.uint8)
+    pool = make_pool(lib, 8, 8, 64, 16, n_chunks=6, owner=owner, max_tensors=2, max_slots=6)
+    assert pool.set_act_busy([1, 3], 1) == 0
+    assert list(pool.owner_state()[1]) == [0, 2, 0, 2, 0, 0]
+    assert pool.set_act_busy([2], 0) == -1                           # FREE, not BUSY
+    assert pool.set_act_busy([1, 2], 0) == -1                        # second id is not BUSY: nothing changes
+    assert list(pool.owner_state()[1]) == [0, 2, 0, 2, 0, 0]
+    assert pool.set_act_busy([0], 0) == -3 and pool.set_act_busy([0], 1) == -3   # KV-owned
+    assert pool.set_act_busy([6], 0) == -6 and pool.set_act_busy([-1], 1) == -6
+    assert pool.set_act_busy([1, 1], 0) == -1                        # the same id twice
+    assert pool.set_act_busy([1], 1) == -3                           # already BUSY
+    assert pool.transfer([1], 0) == -3                               # a BUSY chunk cannot change sides
+    _, t = pool.tensor_create(6 * 16)
+    assert pool.map_chunks(t, 0, 5, None, 1) == -2                   # free: 0, 4 (KV), 2, 5 (ACT) = 4 < 5
+    assert pool.set_act_busy([3, 1], 0) == 0
+    o, s, mt, ms = pool.owner_state()
+    assert list(s) == [0, 0, 0, 0, 0, 0] and list(o) == [0, 1, 1, 1, 0, 1] and (mt == -1).all()
+    assert pool.transfer([1], 0) == 0 and pool.owner_state()[0][1] == 0          # now it can
+    assert pool.map_chunks(t, 0, 5, None, 1) == 0                    # KV 0, 1, 4, then ACT 2, 3
+    assert list(pool.table(t)[0])[:5] == [0, 1, 4, 2, 3]
+    assert pool.set_act_busy([2], 0) == -3                           # lent to KV: no longer on the activation side
+    assert pool.check_invariants() == 0
+    pool.close()
+
+
 def pin_inflation_walkthrough(lib, path):
     """Replays the inflation / deflation walk-through restated in tests/golden."""
     owner = np.array([0, 0, 0, 0, 1, 1, 1, 1], np.uint8)
@@ -485,4 +560,4 @@ ALL_PINS = [pin_sdpa_library, pin_single_token, pin_zero_query_is_mean, pin_cons
             pin_weights_sum_to_one, pin_two_token_logistic, pin_dominant_key, pin_shift_invariance,
             pin_gqa_grouping, pin_chunked_equals_twin_and_online, pin_layout_bytes,
             pin_remap_and_roundtrip_invariance, pin_allocator_order_and_inflation, pin_best_fit_is_the_arg_min,
-            pin_release_acquire_premap_rules]
+            pin_release_acquire_premap_rules, pin_unmap_rules, pin_act_busy_both_ways]

@@ -1,8 +1,9 @@
 """Each planted mistake in the oracle (built as a separate, deliberately wrong library on the CPU)
 must fail at least one pin. This shows the pins are sharp enough to notice a dropped term, a wrong
 head mapping, swapped planes, a transposed layout, a missing normalisation, a stale newest token,
-a wrong allocation order, broken migration bookkeeping, a worst-fit choice and a release that
-retains nothing."""
+a wrong allocation order, broken migration bookkeeping, a worst-fit choice, a release that
+retains nothing, an unmap with the wrong bound or without the release, and activation chunks that
+never become idle again."""
 import os
 
 import pytest
@@ -27,6 +28,9 @@ MUTANTS = {
     11: "acquire takes the largest fitting available tensor instead of the smallest",
     12: "release unmaps everything instead of keeping the mapping",
     13: "SLO window counts every iteration since the last change instead of the last five",
+    14: "unmap treats a partly filled slot as empty",
+    15: "unmap clears the table entry but leaves the chunk (and host slot) taken",
+    16: "busy = 0 leaves the activation chunks busy",
 }
 
 
