@@ -23,7 +23,16 @@
  * All pointers say "host" or "device" below. No call allocates memory the caller has to free
  * except ellm_pool_create (freed by ellm_pool_destroy). A pool is NOT thread-safe: one host
  * thread drives it. Every call validates its whole argument set on the host before it changes any
- * state or launches anything; a call that returns an error has changed nothing.
+ * state or launches anything; a call that returns an error from these checks has changed nothing.
+ * The one error that can come later is ELLM_ERR_HIP from a kernel launch the runtime refuses: a
+ * call that works in several launches (more than 128 requests) has then done the work of the
+ * launches before it, completely, and nothing of the rest (see ellm_kv_append).
+ *
+ * Device memory of the library: the mirror of the chunk tables and the workspace for partial
+ * attention results, both allocated once by the first call that needs the device (or by
+ * ellm_pool_prepare) and freed by ellm_pool_destroy; ellm_workspace_bytes tells the size of the
+ * second. After that first call ellm_kv_append, ellm_decode_attention and ellm_kv_append_decode
+ * neither allocate nor wait for the device.
  */
 #ifndef ELLM_H
 #define ELLM_H
@@ -115,6 +124,22 @@ int ellm_pool_create(const ellm_pool_desc* desc, ellm_pool** out);
 /* Drains the library's streams, frees its metadata. Caller buffers are untouched. */
 int ellm_pool_destroy(ellm_pool* pool);
 
+/* Bytes of device workspace a pool of this geometry allocates for the partial results of split
+ * decode attention (Sec. 5 "Efficient Kernels": the sequence is split and partial softmax results
+ * are combined), for batches of up to max_batch requests: a decode launch covers at most 128
+ * requests and runs one wave per SIMD of the GPU; every wave writes at most one partial result per
+ * request its share touches, so a launch needs at most SIMDs + n_kv_heads * (min(max_batch, 128) - 1)
+ * partial slots of G * (head_dim + 2) floats, and the launches of one call reuse the same slots.
+ * Uses the current HIP device's SIMD count (a nominal 1024 without a device). Only the head
+ * counts and head_dim of desc are read. 0 for a bad argument. */
+uint64_t ellm_workspace_bytes(const ellm_pool_desc* desc, int32_t max_batch);
+
+/* Create the device-side metadata now (table mirror, workspace, side streams, events) and bring
+ * the table mirror up to date on `stream`, instead of leaving it to the first append / decode /
+ * migration call. The only call besides that first one that allocates device memory. No-op on a
+ * metadata-only pool. Errors: HIP. */
+int ellm_pool_prepare(ellm_pool* pool, void* stream);
+
 /* Reserve a virtual tensor of max_tokens tokens (Sec. 2.1.1: virtual range = maximum context,
  * no physical chunk yet). n_slots = ceil(max_tokens / T_c). Returns the lowest unused handle.
  * Errors: INVALID (max_tokens < 1), RANGE (n_slots > max_slots_per_tensor), OOM (no handle). */
@@ -182,20 +207,28 @@ int ellm_kv_premap_next(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batc
 
 /* Push the table changes made so far to the device mirror now, ordered on `stream`, instead of at
  * the start of the next append / decode call: with ellm_kv_premap_next this moves the mapping
- * work of the next step out of its way (Sec. 3.1). No-op on a metadata-only pool. */
+ * work of the next step out of its way (Sec. 3.1). The changed entries travel in the arguments of
+ * small kernels (448 per launch); the call does not wait for the device. No-op on a metadata-only
+ * pool. */
 int ellm_pool_flush_tables(ellm_pool* pool, void* stream);
 
 /* Ownership transfer of FREE chunks between the two sides of the pool (Sec. 2.2.1 step 3 for
  * new_owner = KV, "deflation" for new_owner = ACT). A chunk that already has new_owner is left
  * as it is. Checks: n < 0 or bad owner -> INVALID; per id in order: outside pool -> RANGE,
- * not FREE -> OWNED, repeated -> INVALID. */
+ * not FREE -> OWNED, repeated -> INVALID.
+ * A chunk that an offload has just freed may still be read by its copy, and one whose tensor was
+ * destroyed right after a fetch may still be written: with new_owner = ACT the call returns only
+ * when the library's copies through the listed chunks have finished (the host waits), so whoever
+ * fills them next cannot race with a copy. Kernels of append / decode calls that still read a
+ * chunk are the caller's to order: they run on the caller's stream. */
 int ellm_pool_transfer(ellm_pool* pool, const int32_t* chunk_ids, int32_t n, int new_owner);
 
 /* Stand-in for live activation tensors (the paper's activation allocator and its garbage
  * collection, Sec. 2.2.1 step 2, are outside this library): mark ACT-owned chunks BUSY (busy = 1,
  * they must be FREE) or FREE again (busy = 0, they must be BUSY).
  * Checks per id in order: outside pool -> RANGE, not ACT-owned -> OWNED, wrong state -> OWNED for
- * busy = 1 / INVALID for busy = 0, repeated -> INVALID. */
+ * busy = 1 / INVALID for busy = 0, repeated -> INVALID.
+ * busy = 1 waits for the library's copies through the listed chunks like ellm_pool_transfer. */
 int ellm_pool_set_act_busy(ellm_pool* pool, const int32_t* chunk_ids, int32_t n, int busy);
 
 /* Append new tokens to a batch of tensors (Sec. 3.1: one token per sequence per decode iteration;
@@ -206,7 +239,10 @@ int ellm_pool_set_act_busy(ellm_pool* pool, const int32_t* chunk_ids, int32_t n,
  *   len_b += n_new[b]. Enqueued on `stream` (a hipStream_t); returns without waiting.
  * Checks: batch < 0 -> INVALID; per request in order: bad or repeated handle, n_new < 0 -> INVALID;
  * len + n_new > max_tokens -> RANGE; slots covering the new tokens in ascending order: empty ->
- * UNMAPPED, on host -> NOT_RESIDENT. NULL k_new / v_new with tokens to write -> INVALID. */
+ * UNMAPPED, on host -> NOT_RESIDENT. NULL k_new / v_new with tokens to write -> INVALID.
+ * More than 128 requests are written by one launch per 128; the lengths of a group advance when
+ * its launch has been accepted. If the runtime refuses a launch (HIP), the groups before it have
+ * been appended completely, rows and lengths, and the refused group and those after it not at all. */
 int ellm_kv_append(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, const int32_t* n_new,
                    const void* k_new, const void* v_new, void* stream);
 
@@ -234,7 +270,9 @@ int ellm_decode_attention(ellm_pool* pool, const ellm_tensor_id* ids, int32_t ba
  *   k_new, v_new (device): [batch][n_kv_heads][head_dim] bf16; q, out (device): [batch][n_q_heads][head_dim].
  * Checks: batch < 0, NULL q / out, non-finite scale -> INVALID; then the checks of ellm_kv_append
  * with one token per request; NULL k_new / v_new with batch > 0 -> INVALID; then the checks of
- * ellm_decode_attention on the lengths after the append. A call that fails has changed nothing. */
+ * ellm_decode_attention on the lengths after the append. A call that fails these checks has changed
+ * nothing; a refused launch (HIP) leaves the groups of 128 requests before it appended and decoded
+ * and the rest untouched, as in ellm_kv_append. */
 int ellm_kv_append_decode(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, const void* k_new,
                           const void* v_new, const void* q, void* out, float scale, void* stream);
 
@@ -245,8 +283,9 @@ int ellm_kv_append_decode(ellm_pool* pool, const ellm_tensor_id* ids, int32_t ba
  * slot: a copy waits for the append / decode calls already enqueued that touch its chunks (not
  * for others: a copy for one tensor runs under the attention of another), and for earlier copies
  * in the other direction through the same chunk or host slot; a later append / decode call waits,
- * on its own stream, for the copies that touched its tensors' chunks. All append / decode calls
- * of a pool are expected on one stream, or on streams the caller orders.
+ * on its own stream, for the copies that touched its tensors' chunks. The append / decode calls
+ * of a pool form one sequence: a call on another stream than the call before it is first made to
+ * wait, on its stream, for everything that call enqueued.
  * Checks: bad handle, n_slots < 0 -> INVALID; range -> RANGE; slots ascending: empty -> UNMAPPED,
  * already on host -> NOT_RESIDENT; fewer than n_slots free host slots, or more occupied host slots
  * than the logical host buffer allows -> HOST_FULL. */
@@ -307,7 +346,10 @@ int ellm_pool_get_host_slots(ellm_pool* pool, int32_t* tensor, int32_t* slot);
 int ellm_decode_plan(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch,
                      int32_t* n_split, int32_t* split_tokens);
 /* Override the tokens per wave (rounded down to whole 64-token tiles, at least one; 0 = automatic:
- * one wave per SIMD of the GPU). For tests that compare partitions. */
+ * one wave per SIMD of the GPU). For tests that compare partitions. While an override (this one or
+ * ellm_debug_set_waves) is in force, a decode call whose partition needs more partial results than
+ * the workspace holds replaces the workspace, which waits for the device; without an override that
+ * cannot happen. */
 int ellm_pool_set_split_tokens(ellm_pool* pool, int32_t split_tokens);
 
 /* Measurement hooks. profile_enable(max_records > 0) makes each decode launch record a pair of
@@ -355,6 +397,12 @@ int ellm_debug_vmm_latency(uint64_t chunk_bytes, int32_t n_chunks, double* us);
 int ellm_debug_vmm_buffer_create(uint64_t chunk_bytes, int32_t n_chunks, uint32_t seed, uint16_t fill16,
                                  void** base, uint64_t* bytes);
 int ellm_debug_vmm_buffer_destroy(void* base);
+
+/* Test hook for the error path of calls that work in several launches: the nth kernel launch of
+ * ellm_kv_append / ellm_decode_attention / ellm_kv_append_decode from now on (1 = the next one) is
+ * refused as if the runtime had returned an error: nothing is launched, the call returns HIP. Also
+ * on metadata-only pools, where it applies to the launches a device pool would make. 0 = off. */
+int ellm_debug_fail_launch(ellm_pool* pool, int32_t nth);
 
 /* O(n) consistency scan of the host state (tables, chunk records, free lists, host slots agree;
  * no chunk backs two slots). Returns 0 when consistent, else a positive rule number. */

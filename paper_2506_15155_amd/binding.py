@@ -78,6 +78,8 @@ _sigs = {
     "ellm_chunk_deflate_to_host": [_vp, C.c_int32, C.c_int32, C.c_int32],
     "ellm_chunk_inflate_from_host": [_vp, C.c_int32, C.c_int32, C.c_int32, _i32p],
     "ellm_pool_sync": [_vp],
+    "ellm_pool_prepare": [_vp, _vp],
+    "ellm_debug_fail_launch": [_vp, C.c_int32],
     "ellm_pool_get_geometry": [_vp, _i32p, _i32p, _i32p, C.POINTER(C.c_uint64)],
     "ellm_tensor_get_table": [_vp, C.c_int32, _i32p, C.c_int32, _i32p, C.POINTER(C.c_int64)],
     "ellm_pool_get_owner_state": [_vp, _vp, _vp, _i32p, _i32p],
@@ -98,8 +100,10 @@ for _n, _a in _sigs.items():
     getattr(lib, _n).restype = C.c_int
 lib.ellm_last_error.restype = C.c_char_p
 lib.ellm_last_error.argtypes = []
+lib.ellm_workspace_bytes.restype = C.c_uint64
+lib.ellm_workspace_bytes.argtypes = [C.POINTER(_Desc), C.c_int32]
 
-EXPORTED = sorted(list(_sigs) + ["ellm_last_error"])
+EXPORTED = sorted(list(_sigs) + ["ellm_last_error", "ellm_workspace_bytes"])
 
 
 def ellm_last_error() -> str:
@@ -319,6 +323,20 @@ def ellm_chunk_inflate_from_host(pool, tid, first_slot, n_slots, chunk_ids=None,
 
 def ellm_pool_sync(pool, check=True):
     return _ret(lib.ellm_pool_sync(pool), check)
+
+
+def ellm_pool_prepare(pool, stream=None, check=True):
+    return _ret(lib.ellm_pool_prepare(pool, _stream(stream)), check)
+
+
+def ellm_workspace_bytes(n_q_heads, n_kv_heads, head_dim, max_batch):
+    d = _Desc()
+    d.n_q_heads, d.n_kv_heads, d.head_dim, d.dtype = n_q_heads, n_kv_heads, head_dim, ELLM_BF16
+    return int(lib.ellm_workspace_bytes(C.byref(d), int(max_batch)))
+
+
+def ellm_debug_fail_launch(pool, nth, check=True):
+    return _ret(lib.ellm_debug_fail_launch(pool, int(nth)), check)
 
 
 def ellm_pool_get_geometry(pool):

@@ -50,13 +50,14 @@ struct ellm_pool {
   // device-side metadata, created by the first call that needs the device
   bool dev_ready = false;
   int32_t* d_table = nullptr;
-  float* d_ws = nullptr;
-  size_t ws_bytes = 0;
+  float* d_ws = nullptr;               // partial results of one decode launch (see BatchArgs)
+  int64_t ws_cap_slots = 0;            // partial slots it holds
   hipStream_t side_in = nullptr;       // fetches (host -> device)
   hipStream_t side_out = nullptr;      // offloads (device -> host): a stream of its own, so that the two
                                        // directions use their own copy engines and run at the same time
   hipStream_t last_stream = nullptr;   // last stream given to append / decode
   bool have_last_stream = false;
+  hipEvent_t ev_switch = nullptr;      // orders a new compute stream behind the one used before
 
   // Ordering between the compute stream and the two side streams is kept per chunk and per host
   // slot, so that a copy waits only for the kernels and copies that touched its chunks and a
@@ -68,6 +69,7 @@ struct ellm_pool {
   struct Ring {
     std::vector<hipEvent_t> ev;
     int64_t seq = 0;                   // calls of this kind so far = seq of the newest event
+    int64_t done = 0;                  // highest seq the host has seen finished
   };
   Ring r_compute, r_in, r_out;
   std::vector<int64_t> chunk_compute, chunk_in, chunk_out;   // per chunk: seq of the last call of a kind, 0 = none
@@ -76,10 +78,17 @@ struct ellm_pool {
   int64_t compute_waits_in = 0, compute_waits_out = 0;
   int64_t in_waits_compute = 0, in_waits_out = 0;
   int64_t out_waits_compute = 0, out_waits_in = 0;
+  // Per tensor: the newest fetch / offload that touched one of its chunks, valid while its table
+  // row is unchanged (a copy that touches a chunk of a tensor always changes that tensor's row), so
+  // that a compute call walks a tensor's slots once per change and not once per call.
+  struct CopySeen { uint32_t row_version = 0; bool valid = false; int64_t in = 0, out = 0; };
+  std::vector<CopySeen> copy_seen;
+  int32_t fail_launch_in = 0;          // debug: the n-th launch from now fails without launching (0 = off)
   int32_t split_override = 0;
   int32_t wave_slots = 0;              // waves of a decode launch: one per SIMD of the GPU (0 = not asked yet)
   int32_t waves_percent = 100;         // waves of a launch, as a share of what the GPU holds at once
-  int64_t plan_total_tiles = 0;        // tiles per kv head of the launch planned last
+  int64_t plan_total_tiles = 0;        // of the launch planned last: tiles per kv head,
+  int64_t plan_waves = 0, plan_slots = 0;   // waves per kv head, partial slots
 
   // optional timing of the partial (dominant) kernel with events on the caller's stream
   std::vector<hipEvent_t> prof_ev;     // 2 per record
@@ -117,20 +126,44 @@ ellm::PoolView view_of(const ellm_pool* p) {
   return v;
 }
 
+// SIMDs of the current device (4 per compute unit); without a device, those of a nominal MI355X
+int32_t device_simds() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+    return cus * ellm::SIMDS_PER_CU;
+  (void)hipGetLastError();
+  return 256 * ellm::SIMDS_PER_CU;
+}
+
+// Partial slots one decode launch can need under the automatic partition: every wave writes one
+// partial, and one more for every request boundary inside its share; the waves of all kv heads
+// together are at most one per SIMD, and each kv head's sequence has n_req - 1 inner boundaries.
+int64_t launch_slot_bound(int32_t simds, int32_t n_kv_heads, int32_t n_req) {
+  return (int64_t)simds + (int64_t)n_kv_heads * (std::max(n_req, 1) - 1);
+}
+
+size_t slot_bytes(int32_t group, int32_t head_dim) { return (size_t)group * (head_dim + ellm::WS_ML) * sizeof(float); }
+
 int ensure_device(ellm_pool* p) {
   if (p->dev_ready) return ELLM_OK;
   const size_t bytes = p->core->table().size() * sizeof(int32_t);
   HIP_TRY(hipMalloc((void**)&p->d_table, bytes), "hipMalloc(table mirror)");
   HIP_TRY(hipMemcpy(p->d_table, p->core->table().data(), bytes, hipMemcpyHostToDevice), "hipMemcpy(table mirror)");
   (void)p->core->take_dirty();   // the full upload covers everything so far
+  // the workspace is sized once, for the largest launch the automatic partition can produce
+  p->ws_cap_slots = launch_slot_bound(device_simds(), p->geom.n_kv_heads, std::min<int32_t>(p->geom.max_tensors, ellm::MAX_LAUNCH_REQ));
+  HIP_TRY(hipMalloc((void**)&p->d_ws, (size_t)p->ws_cap_slots * slot_bytes(p->geom.group, p->geom.head_dim)), "hipMalloc(workspace)");
   HIP_TRY(hipStreamCreateWithFlags(&p->side_in, hipStreamNonBlocking), "hipStreamCreate(side)");
   HIP_TRY(hipStreamCreateWithFlags(&p->side_out, hipStreamNonBlocking), "hipStreamCreate(side)");
+  HIP_TRY(hipEventCreateWithFlags(&p->ev_switch, hipEventDisableTiming), "hipEventCreate");
   if (p->geom.n_host_slots > 0) {
     p->chunk_compute.assign(p->geom.n_chunks, 0);
     p->chunk_in.assign(p->geom.n_chunks, 0);
     p->chunk_out.assign(p->geom.n_chunks, 0);
     p->host_in.assign(p->geom.n_host_slots, 0);
     p->host_out.assign(p->geom.n_host_slots, 0);
+    p->copy_seen.assign(p->geom.max_tensors, ellm_pool::CopySeen());
     for (ellm_pool::Ring* r : {&p->r_compute, &p->r_in, &p->r_out})
       for (int i = 0; i < ellm_pool::EV_RING; i++) {
         hipEvent_t e;
@@ -142,18 +175,13 @@ int ensure_device(ellm_pool* p) {
   return ELLM_OK;
 }
 
-// push host-side table changes to the device mirror, ordered on `stream`
+// push host-side table changes to the device mirror, ordered on `stream`: the changed entries
+// travel in the arguments of small patch kernels, MAX_PATCH per launch, so nothing here waits for
+// the device and no staging buffer has to outlive the call
 int flush_table(ellm_pool* p, hipStream_t stream) {
   if (!p->core->has_dirty()) return ELLM_OK;
   std::vector<int64_t> dirty = p->core->take_dirty();
   const std::vector<int32_t>& tab = p->core->table();
-  if (dirty.size() > 16 * (size_t)ellm::MAX_PATCH) {
-    // bulk change (initial mapping of a large batch): one blocking copy of the whole mirror
-    HIP_TRY(hipStreamSynchronize(stream), "hipStreamSynchronize(table upload)");
-    HIP_TRY(hipMemcpy(p->d_table, tab.data(), tab.size() * sizeof(int32_t), hipMemcpyHostToDevice),
-            "hipMemcpy(table upload)");
-    return ELLM_OK;
-  }
   ellm::PatchArgs a;
   size_t i = 0;
   while (i < dirty.size()) {
@@ -170,13 +198,26 @@ int flush_table(ellm_pool* p, hipStream_t stream) {
 
 bool tracks_chunks(const ellm_pool* p) { return p->geom.n_host_slots > 0; }
 
-// `waiter` waits for call `need` of ring r unless it already waits for that much. A seq the ring
-// no longer holds an event for is covered by the newest event of the same (in-order) stream.
-int wait_for(hipStream_t waiter, const ellm_pool::Ring& r, int64_t need, int64_t& waited) {
-  if (need <= waited) return ELLM_OK;
+// the event that covers call `need` of ring r: its own, or, once the ring has gone round, the
+// newest one of the same (in-order) stream
+hipEvent_t event_of(const ellm_pool::Ring& r, int64_t& need) {
   if (need <= r.seq - ellm_pool::EV_RING) need = r.seq;
-  HIP_TRY(hipStreamWaitEvent(waiter, r.ev[need % ellm_pool::EV_RING], 0), "hipStreamWaitEvent");
+  return r.ev[need % ellm_pool::EV_RING];
+}
+
+// `waiter` waits for call `need` of ring r unless it already waits for that much
+int wait_for(hipStream_t waiter, const ellm_pool::Ring& r, int64_t need, int64_t& waited) {
+  if (need <= waited || need <= r.done) return ELLM_OK;
+  HIP_TRY(hipStreamWaitEvent(waiter, event_of(r, need), 0), "hipStreamWaitEvent");
   waited = need;
+  return ELLM_OK;
+}
+
+// the host waits until call `need` of ring r has finished
+int host_wait(ellm_pool::Ring& r, int64_t need) {
+  if (need <= r.done) return ELLM_OK;
+  HIP_TRY(hipEventSynchronize(event_of(r, need)), "hipEventSynchronize");
+  r.done = need;
   return ELLM_OK;
 }
 
@@ -188,21 +229,36 @@ int record_on(ellm_pool::Ring& r, hipStream_t stream, int64_t* seq) {
 }
 
 // Things every compute call does before launching on `stream`: wait for the copies that touched
-// the chunks of the tensors it works on, bring the device table up to date.
+// the chunks of the tensors it works on, bring the device table up to date. The ordering state
+// treats the compute calls as one in-order sequence; a call on another stream than the one before
+// is therefore first put behind that one.
 int enter_compute(ellm_pool* p, hipStream_t stream, const int32_t* ids, int32_t batch) {
   int rc = ensure_device(p);
   if (rc) return rc;
-  if (p->have_last_stream && stream != p->last_stream) p->compute_waits_in = p->compute_waits_out = 0;
+  if (p->have_last_stream && stream != p->last_stream) {
+    HIP_TRY(hipEventRecord(p->ev_switch, p->last_stream), "hipEventRecord(stream change)");
+    HIP_TRY(hipStreamWaitEvent(stream, p->ev_switch, 0), "hipStreamWaitEvent(stream change)");
+    p->compute_waits_in = p->compute_waits_out = 0;   // what the old stream waited for, the new one has yet to
+  }
   if (tracks_chunks(p) && (p->r_in.seq > p->compute_waits_in || p->r_out.seq > p->compute_waits_out)) {
     int64_t need_in = 0, need_out = 0;
     for (int32_t b = 0; b < batch; b++) {
-      const ellm::TensorRec* t = p->core->tensor(ids[b]);
-      const int32_t* r = p->core->row(ids[b]);
-      for (int32_t s = 0; s < t->n_slots; s++)
-        if (r[s] >= 0) {
-          need_in = std::max(need_in, p->chunk_in[r[s]]);
-          need_out = std::max(need_out, p->chunk_out[r[s]]);
-        }
+      ellm_pool::CopySeen& cs = p->copy_seen[ids[b]];
+      const uint32_t ver = p->core->row_version(ids[b]);
+      if (!cs.valid || cs.row_version != ver) {
+        const ellm::TensorRec* t = p->core->tensor(ids[b]);
+        const int32_t* r = p->core->row(ids[b]);
+        cs.in = cs.out = 0;
+        for (int32_t s = 0; s < t->n_slots; s++)
+          if (r[s] >= 0) {
+            cs.in = std::max(cs.in, p->chunk_in[r[s]]);
+            cs.out = std::max(cs.out, p->chunk_out[r[s]]);
+          }
+        cs.row_version = ver;
+        cs.valid = true;
+      }
+      need_in = std::max(need_in, cs.in);
+      need_out = std::max(need_out, cs.out);
     }
     if ((rc = wait_for(stream, p->r_in, need_in, p->compute_waits_in))) return rc;
     if ((rc = wait_for(stream, p->r_out, need_out, p->compute_waits_out))) return rc;
@@ -261,18 +317,35 @@ int leave_migration(ellm_pool* p, const std::vector<ellm::Move>& moves, bool fet
   return ELLM_OK;
 }
 
-int ensure_workspace(ellm_pool* p, int64_t n_slots) {
-  const size_t need = (size_t)n_slots * p->geom.group * (p->geom.head_dim + ellm::WS_ML) * sizeof(float);
-  if (need <= p->ws_bytes) return ELLM_OK;
-  if (p->d_ws) {
-    HIP_TRY(hipDeviceSynchronize(), "hipDeviceSynchronize(workspace growth)");
-    HIP_TRY(hipFree(p->d_ws), "hipFree(workspace)");
-    p->d_ws = nullptr;
-    p->ws_bytes = 0;
+// Chunks are about to leave the KV side's care (handed to the activation side, or marked busy
+// there): copies of this library that still read or write them must have finished first, because
+// whoever uses the chunks next runs on streams the library does not see. The host waits.
+int settle_copies(ellm_pool* p, const int32_t* chunk_ids, int32_t n) {
+  if (!p->dev_ready || !tracks_chunks(p)) return ELLM_OK;
+  int64_t need_in = 0, need_out = 0;
+  for (int32_t i = 0; i < n; i++) {
+    need_in = std::max(need_in, p->chunk_in[chunk_ids[i]]);
+    need_out = std::max(need_out, p->chunk_out[chunk_ids[i]]);
   }
-  const size_t grow = need + need / 4;
-  HIP_TRY(hipMalloc((void**)&p->d_ws, grow), "hipMalloc(workspace)");
-  p->ws_bytes = grow;
+  int rc = host_wait(p->r_out, need_out);
+  if (rc) return rc;
+  return host_wait(p->r_in, need_in);
+}
+
+// Under the automatic partition a launch never needs more partial slots than the workspace was
+// sized for. With a partition override in force (tests and measurements) it may: then, and only
+// then, the workspace is replaced by a larger one, which waits for the device.
+int ensure_workspace(ellm_pool* p, int64_t n_slots) {
+  if (n_slots <= p->ws_cap_slots) return ELLM_OK;
+  if (p->split_override <= 0 && p->waves_percent == 100)
+    return set_err(ELLM_ERR_RANGE, "decode_attention: launch needs more partial slots than ellm_workspace_bytes allows for");
+  HIP_TRY(hipDeviceSynchronize(), "hipDeviceSynchronize(workspace growth)");
+  HIP_TRY(hipFree(p->d_ws), "hipFree(workspace)");
+  p->d_ws = nullptr;
+  p->ws_cap_slots = 0;
+  const int64_t grow = n_slots + n_slots / 4;
+  HIP_TRY(hipMalloc((void**)&p->d_ws, (size_t)grow * slot_bytes(p->geom.group, p->geom.head_dim)), "hipMalloc(workspace)");
+  p->ws_cap_slots = grow;
   return ELLM_OK;
 }
 
@@ -299,13 +372,12 @@ int32_t wave_slots(ellm_pool* p) {
 // The partition of one launch (at most MAX_LAUNCH_REQ requests). For each kv head the tiles of all
 // requests form one sequence, dealt out evenly to as many waves as the GPU has SIMDs (all kv
 // heads together): every wave reads the same amount, all are resident from the start, and a wave
-// whose share crosses from one request into the next writes one partial result for each. The cut
+// whose share crosses from one request into the next finishes a result for each. The cut
 // depends only on the batch's lengths, the pool geometry and the device's wave capacity, never on
 // physical chunk ids or on which wave runs when: every rounding is reproducible and invariant
 // under remapping.
 // With an override (tests) every wave gets the given number of tokens' worth of tiles.
-void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0, int64_t ws_slot0, ellm::BatchArgs& a,
-                 int32_t extra = 0) {
+void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0, ellm::BatchArgs& a, int32_t extra = 0) {
   const int32_t Tc = p->geom.tokens_per_chunk;
   const int32_t tpc = (Tc + ellm::TILE_TOKENS - 1) / ellm::TILE_TOKENS;
   int64_t total = 0;
@@ -318,7 +390,6 @@ void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0
     a.req[i].tensor = ids[i];
     a.req[i].len = (int32_t)len;
     a.req[i].tile_prefix = (int32_t)std::min<int64_t>(total, 0x7fffffff);
-    a.req[i].pad = 0;
     total += tiles[i];
   }
   int64_t waves;
@@ -332,24 +403,31 @@ void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0
   const int64_t each = total / waves, more = total - each * waves;
   // wave that holds tile x: the first `more` waves hold each + 1 tiles, the others each
   auto wave_of = [&](int64_t x) { return x < more * (each + 1) ? x / (each + 1) : more + (x - more * (each + 1)) / each; };
-  int32_t most = 0;
-  int64_t at = 0;
+  std::memset(a.split_req, 0, sizeof(a.split_req));
+  int64_t at = 0, parts = 0;
+  int32_t n_split = 0;
   for (int32_t i = 0; i < n_req; i++) {
     const int64_t w0 = wave_of(at), w1 = wave_of(at + tiles[i] - 1);
     a.req[i].wave_first = (int32_t)w0;
     a.req[i].n_part = (int32_t)(w1 - w0 + 1);
-    most = std::max<int32_t>(most, a.req[i].n_part);
+    a.req[i].part0 = 0;
+    if (w1 > w0) {               // a request shared by several waves: partial results and a combine pass
+      a.req[i].part0 = (int32_t)std::min<int64_t>(parts, 0x7fffffff);
+      parts += w1 - w0 + 1;
+      a.split_req[n_split >> 2] |= (uint32_t)i << ((n_split & 3) * 8);
+      n_split++;
+    }
     at += tiles[i];
   }
   a.n_req = n_req;
   a.q_row0 = q_row0;
   a.tiles_per_head = (int32_t)std::min<int64_t>(total, 0x7fffffff);
-  a.waves_per_head = (int32_t)waves;
+  a.waves_per_head = (int32_t)std::min<int64_t>(waves, 0x7fffffff);
   a.tiles_each = (int32_t)each;
   a.tiles_extra = (int32_t)more;
-  a.max_partials = most;
-  a.ws_slot0 = (int32_t)ws_slot0;
-  a.ws_slots = 0;
+  a.parts_per_head = (int32_t)std::min<int64_t>(parts, 0x7fffffff);
+  a.ws_slots = (int32_t)std::min<int64_t>(parts * p->geom.n_kv_heads, 0x7fffffff);
+  a.n_split_req = n_split;
   a.use_wave_req = waves <= ellm::MAX_WAVE_REQ ? 1 : 0;
   if (a.use_wave_req) {
     std::memset(a.wave_req, 0, sizeof(a.wave_req));
@@ -361,11 +439,12 @@ void plan_launch(ellm_pool* p, const int32_t* ids, int32_t n_req, int32_t q_row0
     }
   }
   p->plan_total_tiles = total;
+  p->plan_waves = waves;
+  p->plan_slots = parts * p->geom.n_kv_heads;
 }
 
-int64_t launch_ws_slots(const ellm_pool* p, const ellm::BatchArgs& a) {
-  return (int64_t)a.n_req * p->geom.n_kv_heads * a.max_partials;
-}
+// a debug hook can make the n-th launch from now fail as if the runtime had refused it
+bool launch_refused(ellm_pool* p) { return p->fail_launch_in > 0 && --p->fail_launch_in == 0; }
 
 }  // namespace
 
@@ -432,6 +511,7 @@ int ellm_pool_destroy(ellm_pool* p) {
     for (ellm_pool::Ring* r : {&p->r_compute, &p->r_in, &p->r_out})
       for (hipEvent_t e : r->ev) (void)hipEventDestroy(e);
     (void)hipFree(p->d_table);
+    if (p->ev_switch) (void)hipEventDestroy(p->ev_switch);
     for (hipEvent_t e : p->prof_ev) (void)hipEventDestroy(e);
     if (p->d_ws) (void)hipFree(p->d_ws);
   }
@@ -462,12 +542,16 @@ int ellm_tensor_unmap_chunks(ellm_pool* p, ellm_tensor_id id, int32_t first_slot
 
 int ellm_pool_transfer(ellm_pool* p, const int32_t* chunk_ids, int32_t n, int new_owner) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
-  return core_err(p, p->core->transfer(chunk_ids, n, new_owner));
+  int rc = core_err(p, p->core->transfer(chunk_ids, n, new_owner));
+  if (rc || new_owner != ELLM_OWNER_ACT) return rc;
+  return settle_copies(p, chunk_ids, n);     // an offload may still be reading a chunk it has just freed
 }
 
 int ellm_pool_set_act_busy(ellm_pool* p, const int32_t* chunk_ids, int32_t n, int busy) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
-  return core_err(p, p->core->set_act_busy(chunk_ids, n, busy));
+  int rc = core_err(p, p->core->set_act_busy(chunk_ids, n, busy));
+  if (rc || !busy) return rc;
+  return settle_copies(p, chunk_ids, n);
 }
 
 int ellm_kv_append(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const int32_t* n_new,
@@ -478,35 +562,41 @@ int ellm_kv_append(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const
   if (rc) return rc;
   if (total > 0 && (!k_new || !v_new)) return set_err(ELLM_ERR_INVALID, "kv_append: NULL k_new / v_new");
   if (total > 0x7fffffffll / (2 * p->geom.n_kv_heads)) return set_err(ELLM_ERR_RANGE, "kv_append: too many tokens in one call");
-  if (total > 0 && !p->metadata_only) {
-    hipStream_t stream = (hipStream_t)stream_;
-    rc = enter_compute(p, stream, ids, batch);
-    if (rc) return rc;
-    const ellm::PoolView pv = view_of(p);
-    const size_t tok_bytes = (size_t)p->geom.n_kv_heads * p->geom.head_dim * 2;
-    ellm::AppendArgs a;
-    int64_t row0 = 0;
-    for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
-      const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
-      a.n_req = nb;
-      int32_t t = 0;
-      for (int32_t i = 0; i < nb; i++) {
-        a.tensor[i] = ids[b0 + i];
-        a.len_before[i] = (int32_t)p->core->tensor(ids[b0 + i])->len;
-        a.tok0[i] = t;
-        t += p->n_eff[b0 + i];
-      }
-      a.total_new = t;
-      int e = ellm::launch_kv_append(pv, (const char*)k_new + row0 * tok_bytes, (const char*)v_new + row0 * tok_bytes,
-                                     a, stream);
-      if (e) return hip_err((hipError_t)e, "kv_append launch");
-      row0 += t;
+  if (total == 0) return ELLM_OK;
+  hipStream_t stream = (hipStream_t)stream_;
+  if (!p->metadata_only && (rc = enter_compute(p, stream, ids, batch))) return rc;
+  // One launch per group of MAX_LAUNCH_REQ requests; a group's lengths advance as soon as its launch
+  // has been accepted, so rows written and lengths agree at every point, also when the runtime
+  // refuses a later launch.
+  const size_t tok_bytes = (size_t)p->geom.n_kv_heads * p->geom.head_dim * 2;
+  ellm::AppendArgs a;
+  int64_t row0 = 0;
+  int err = ELLM_OK;
+  int32_t done = 0;
+  for (int32_t b0 = 0; b0 < batch && !err; b0 += ellm::MAX_LAUNCH_REQ) {
+    const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
+    a.n_req = nb;
+    int32_t t = 0;
+    for (int32_t i = 0; i < nb; i++) {
+      a.tensor[i] = ids[b0 + i];
+      a.len_before[i] = (int32_t)p->core->tensor(ids[b0 + i])->len;
+      a.tok0[i] = t;
+      t += p->n_eff[b0 + i];
     }
-    rc = leave_compute(p, stream, ids, batch);
-    if (rc) return rc;
+    a.total_new = t;
+    if (t > 0 && launch_refused(p)) err = set_err(ELLM_ERR_HIP, "kv_append launch: refused (debug hook)");
+    else if (t > 0 && !p->metadata_only) {
+      const int e = ellm::launch_kv_append(view_of(p), (const char*)k_new + row0 * tok_bytes,
+                                           (const char*)v_new + row0 * tok_bytes, a, stream);
+      if (e) err = hip_err((hipError_t)e, "kv_append launch");
+    }
+    if (err) break;
+    p->core->append_commit(ids + b0, nb, p->n_eff.data() + b0);
+    done = b0 + nb;
+    row0 += t;
   }
-  p->core->append_commit(ids, batch, p->n_eff);
-  return ELLM_OK;
+  if (!p->metadata_only && done > 0 && (rc = leave_compute(p, stream, ids, done))) return rc;
+  return err;
 }
 
 int ellm_tensor_release(ellm_pool* p, ellm_tensor_id id) {
@@ -570,7 +660,7 @@ int ellm_decode_plan(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, int
   int32_t per_wave = 0;
   for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
     const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
-    plan_launch(p, ids + b0, nb, b0, 0, a);
+    plan_launch(p, ids + b0, nb, b0, a);
     per_wave = std::max(per_wave, a.tiles_each + (a.tiles_extra > 0 ? 1 : 0));
     if (n_split)
       for (int32_t i = 0; i < nb; i++)
@@ -586,51 +676,55 @@ int ellm_pool_set_split_tokens(ellm_pool* p, int32_t split_tokens) {
   return ELLM_OK;
 }
 
-// decode over `ids`; with k_new / v_new the one-token append is fused into the same launches
+// decode over `ids`; with k_new / v_new the one-token append is fused into the same launches.
+// ws / ws_cap_slots: where the partial results go. The launches of a call run one after the other
+// on one stream, each followed by its combine pass, so all of them use the same workspace.
 static int decode_impl(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const void* q, const void* k_new,
-                       const void* v_new, void* out, float scale, hipStream_t stream) {
+                       const void* v_new, void* out, float scale, hipStream_t stream, int32_t* n_launched,
+                       float* ws_fixed = nullptr, int64_t ws_fixed_slots = 0) {
   const int32_t extra = k_new ? 1 : 0;
-  int rc = enter_compute(p, stream, ids, batch);
-  if (rc) return rc;
-  if (scale == 0.f) scale = 1.0f / std::sqrt((float)p->geom.head_dim);
-  const float scale_log2 = scale * 1.4426950408889634f;
-
-  // plan every launch first: the workspace must hold all of them
+  *n_launched = 0;               // requests whose launches the runtime has accepted
+  // plan every launch first: a call that cannot run must not have launched anything
   std::vector<ellm::BatchArgs>& launches = p->launches;
   launches.clear();
-  int64_t ws_slots = 0;
+  int64_t most_slots = 0;
   for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
     const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
     launches.emplace_back();
-    plan_launch(p, ids + b0, nb, b0, ws_slots, launches.back(), extra);
-    ws_slots += launch_ws_slots(p, launches.back());
-    const ellm::BatchArgs& la = launches.back();
-    if (p->plan_total_tiles > 0x7fffffffll || (int64_t)la.waves_per_head * p->geom.n_kv_heads > 0x7fffffffll ||
-        ws_slots > 0x7fffffffll)
+    plan_launch(p, ids + b0, nb, b0, launches.back(), extra);
+    if (p->plan_total_tiles > 0x7fffffffll || p->plan_waves * p->geom.n_kv_heads > 0x7fffffffll || p->plan_slots > 0x7fffffffll)
       return set_err(ELLM_ERR_RANGE, "decode_attention: too much work for one call");
+    most_slots = std::max(most_slots, p->plan_slots);
   }
-  rc = ensure_workspace(p, ws_slots);
+  if (ws_fixed && most_slots > ws_fixed_slots)
+    return set_err(ELLM_ERR_RANGE, "decode_attention: the batch needs more partial results than the fixed workspace holds");
+  int rc = enter_compute(p, stream, ids, batch);
   if (rc) return rc;
-  for (ellm::BatchArgs& la : launches) la.ws_slots = (int32_t)ws_slots;
+  if (!ws_fixed && (rc = ensure_workspace(p, most_slots))) return rc;
+  float* ws = ws_fixed ? ws_fixed : p->d_ws;
+  if (scale == 0.f) scale = 1.0f / std::sqrt((float)p->geom.head_dim);
+  const float scale_log2 = scale * 1.4426950408889634f;
 
   const ellm::PoolView pv = view_of(p);
+  int err = ELLM_OK;
   for (const ellm::BatchArgs& a : launches) {
     bool prof = (size_t)(p->prof_used + 1) * 2 <= p->prof_ev.size();
     if (prof && p->prof_stride > 1) {
       prof = p->prof_phase == 0;
       p->prof_phase = (p->prof_phase + 1) % p->prof_stride;
     }
-    if (prof) HIP_TRY(hipEventRecord(p->prof_ev[2 * p->prof_used], stream), "hipEventRecord(profile)");
-    int e = ellm::launch_decode_partial(pv, q, k_new, v_new, p->d_ws, scale_log2, a, stream);
-    if (e) return hip_err((hipError_t)e, "decode partial launch");
-    if (prof) {
-      HIP_TRY(hipEventRecord(p->prof_ev[2 * p->prof_used + 1], stream), "hipEventRecord(profile)");
-      p->prof_used++;
-    }
-    e = ellm::launch_decode_combine(pv, p->d_ws, out, a, stream);
-    if (e) return hip_err((hipError_t)e, "decode combine launch");
+    if (launch_refused(p)) { err = set_err(ELLM_ERR_HIP, "decode partial launch: refused (debug hook)"); break; }
+    if (prof && hipEventRecord(p->prof_ev[2 * p->prof_used], stream) != hipSuccess) prof = false;
+    int e = ellm::launch_decode_partial(pv, q, k_new, v_new, ws, out, scale_log2, a, stream);
+    if (e) { err = hip_err((hipError_t)e, "decode partial launch"); break; }
+    *n_launched += a.n_req;
+    if (prof && hipEventRecord(p->prof_ev[2 * p->prof_used + 1], stream) == hipSuccess) p->prof_used++;
+    e = ellm::launch_decode_combine(pv, ws, out, a, stream);
+    if (e) { err = hip_err((hipError_t)e, "decode combine launch"); break; }
   }
-  return leave_compute(p, stream, ids, batch);
+  // also after a refused launch: the chunks of the requests already launched are in use on the stream
+  if (*n_launched > 0 && (rc = leave_compute(p, stream, ids, *n_launched)) && !err) err = rc;
+  return err;
 }
 
 int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const void* q, void* out,
@@ -641,7 +735,8 @@ int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch
   if (rc) return rc;
   if (batch == 0) return ELLM_OK;
   if (p->metadata_only) return set_err(ELLM_ERR_NO_DEVICE, "decode_attention: pool has no device");
-  return decode_impl(p, ids, batch, q, nullptr, nullptr, out, scale, (hipStream_t)stream_);
+  int32_t n_launched = 0;
+  return decode_impl(p, ids, batch, q, nullptr, nullptr, out, scale, (hipStream_t)stream_, &n_launched);
 }
 
 int ellm_kv_append_decode(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const void* k_new, const void* v_new,
@@ -655,10 +750,11 @@ int ellm_kv_append_decode(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch
   if (rc) return rc;
   if (batch == 0) return ELLM_OK;
   if (p->metadata_only) return set_err(ELLM_ERR_NO_DEVICE, "kv_append_decode: pool has no device");
-  rc = decode_impl(p, ids, batch, q, k_new, v_new, out, scale, (hipStream_t)stream_);
-  if (rc) return rc;
-  p->core->append_commit(ids, batch, p->n_eff);
-  return ELLM_OK;
+  // the kernels of a launch write the new rows, so the lengths of its requests advance with it
+  int32_t n_launched = 0;
+  rc = decode_impl(p, ids, batch, q, k_new, v_new, out, scale, (hipStream_t)stream_, &n_launched);
+  p->core->append_commit(ids, n_launched, p->n_eff.data());
+  return rc;
 }
 
 int ellm_chunk_deflate_to_host(ellm_pool* p, ellm_tensor_id id, int32_t first_slot, int32_t n_slots) {
@@ -698,11 +794,36 @@ int ellm_chunk_inflate_from_host(ellm_pool* p, ellm_tensor_id id, int32_t first_
   return ELLM_OK;
 }
 
+uint64_t ellm_workspace_bytes(const ellm_pool_desc* d, int32_t max_batch) {
+  if (!d || max_batch < 1 || !d->n_kv_heads || !d->n_q_heads || d->n_q_heads % d->n_kv_heads ||
+      (d->head_dim != 64 && d->head_dim != 128))
+    return 0;
+  const int32_t n_req = std::min<int32_t>(max_batch, ellm::MAX_LAUNCH_REQ);
+  return (uint64_t)launch_slot_bound(device_simds(), d->n_kv_heads, n_req) *
+         slot_bytes(d->n_q_heads / d->n_kv_heads, d->head_dim);
+}
+
+int ellm_pool_prepare(ellm_pool* p, void* stream) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  if (p->metadata_only) return ELLM_OK;
+  int rc = ensure_device(p);
+  if (rc) return rc;
+  return flush_table(p, (hipStream_t)stream);
+}
+
+int ellm_debug_fail_launch(ellm_pool* p, int32_t nth) {
+  if (!p || nth < 0) return set_err(ELLM_ERR_INVALID, "debug_fail_launch: bad argument");
+  p->fail_launch_in = nth;
+  return ELLM_OK;
+}
+
 int ellm_pool_sync(ellm_pool* p) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
   if (!p->dev_ready) return ELLM_OK;
   HIP_TRY(hipStreamSynchronize(p->side_in), "hipStreamSynchronize(side)");
+  p->r_in.done = p->r_in.seq;
   HIP_TRY(hipStreamSynchronize(p->side_out), "hipStreamSynchronize(side)");
+  p->r_out.done = p->r_out.seq;
   return ELLM_OK;
 }
 
@@ -804,7 +925,7 @@ int ellm_debug_kv_stream_read(ellm_pool* p, const ellm_tensor_id* ids, int32_t b
   ellm::BatchArgs a;
   for (int32_t b0 = 0; b0 < batch; b0 += ellm::MAX_LAUNCH_REQ) {
     const int32_t nb = std::min<int32_t>(ellm::MAX_LAUNCH_REQ, batch - b0);
-    plan_launch(p, ids + b0, nb, b0, 0, a);
+    plan_launch(p, ids + b0, nb, b0, a);
     int e = ellm::launch_kv_stream(pv, (uint32_t*)sink, a, stream);
     if (e) return hip_err((hipError_t)e, "kv stream launch");
   }

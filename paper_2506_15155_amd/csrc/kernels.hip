@@ -239,10 +239,10 @@ __device__ __forceinline__ Share locate_share(const BatchArgs& a, int32_t index,
 // Scores are kept in log2 units (scale_log2 = scale * log2 e).
 // ---------------------------------------------------------------------------------------------
 template <int D, int G, bool APPEND>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_partial_kernel(PoolView pv, const uint16_t* __restrict__ q,
-                                                            const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
-                                                            float* __restrict__ ws, float scale_log2,
-                                                            int32_t g_first, BatchArgs a) {
+__device__ __forceinline__ void decode_partial_body(const PoolView& pv, const uint16_t* __restrict__ q,
+                                                    const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
+                                                    float* __restrict__ ws, uint16_t* __restrict__ out, float scale_log2,
+                                                    int32_t g_first, const BatchArgs& a) {
   constexpr int LPR = D / 8;             // lanes per row = 16-byte pieces per row
   constexpr int RPW = 64 / LPR;          // rows per wave-wide load
   constexpr int NL = 64 / RPW;           // wave-wide loads per 64-row tile and plane
@@ -284,6 +284,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     const BatchArgs::Req nx_ = a.req[cb];                                                           \
     len = nx_.len;                                                                                  \
     left = tiles_of(len, Tc, pv.tiles_per_chunk);                                                   \
+    c_np = nx_.n_part;                                                                              \
+    c_p0 = nx_.part0;                                                                               \
     trow = (const_i32_ptr)(pv.table + (int64_t)nx_.tensor * pv.max_slots);                          \
     slot = 0;                                                                                       \
     r = 0;                                                                                          \
@@ -387,8 +389,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
     const char* kb = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + ((uint64_t)(g * 2) * Tc + r) * ROWB;
     ELLM_LOAD_K_TILE(kb, nv_c)
 
-    // the request being accumulated, and which of its partials this wave writes
+    // the request being accumulated, and which of its partials this wave writes; b_np, b_p0: how
+    // many waves share the request and where its partial slots start (c_np, c_p0: the same for the
+    // cursor's request, which runs one tile ahead)
     int32_t b = cb, j = sh.w - first.wave_first;
+    int32_t b_np = first.n_part, b_p0 = first.part0, c_np = b_np, c_p0 = b_p0;
     uint32_t qreg[G][QR];
     uint4 kn, vn;
     ELLM_LOAD_Q(b)
@@ -464,28 +469,48 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
           }
           l[i] = wave_sum(l[i]);
         }
-        // accumulators: one row of D floats per (partial slot, q head), every row a whole number of
-        // cache lines; m and l of all partials sit together behind the rows, two floats each
-        const int64_t row0 = (a.ws_slot0 + (int64_t)(b * pv.n_kv_heads + g) * a.max_partials + j) * pv.group + g_first;
-        float* wout = ws + row0 * D;
-        float* wml = ws + (int64_t)a.ws_slots * pv.group * D + row0 * WS_ML;
-        if (rg == 0) {
+        if (b_np == 1) {
+          // the whole request lay inside this wave's share: this is the final result. Normalise and
+          // round exactly as the combine pass would for a single partial (weight 1) and write the
+          // output rows; no workspace traffic, no second pass for this request
+          if (rg == 0) {
 #pragma unroll
-          for (int i = 0; i < G; i++) {
-            float4* dst = reinterpret_cast<float4*>(wout + i * D + sub * 8);
-            dst[0] = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
-            dst[1] = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
+            for (int i = 0; i < G; i++) {
+              const float li = l[i];
+              uint32_t w[4];
+#pragma unroll
+              for (int e = 0; e < 4; e++)
+                w[e] = f32_to_bf16_bits((acc[i][2 * e] + 0.f) / li) | (f32_to_bf16_bits((acc[i][2 * e + 1] + 0.f) / li) << 16);
+              uint16_t* o = out + ((int64_t)(a.q_row0 + b) * pv.n_q_heads + hq0 + i) * D + sub * 8;
+              *reinterpret_cast<uint4*>(o) = make_uint4(w[0], w[1], w[2], w[3]);
+            }
           }
-          float mm = m[0], ll = l[0];       // lane `sub` writes head sub's pair
+        } else {
+          // accumulators: one row of D floats per (partial slot, q head), every row a whole number of
+          // cache lines; m and l of all partials sit together behind the rows, two floats each
+          const int64_t row0 = ((int64_t)g * a.parts_per_head + b_p0 + j) * pv.group + g_first;
+          float* wout = ws + row0 * D;
+          float* wml = ws + (int64_t)a.ws_slots * pv.group * D + row0 * WS_ML;
+          if (rg == 0) {
 #pragma unroll
-          for (int i = 1; i < G; i++)
-            if (sub == i) { mm = m[i]; ll = l[i]; }
-          if (sub < G) *reinterpret_cast<float2*>(wml + sub * WS_ML) = make_float2(mm, ll);
+            for (int i = 0; i < G; i++) {
+              float4* dst = reinterpret_cast<float4*>(wout + i * D + sub * 8);
+              dst[0] = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+              dst[1] = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
+            }
+            float mm = m[0], ll = l[0];       // lane `sub` writes head sub's pair
+#pragma unroll
+            for (int i = 1; i < G; i++)
+              if (sub == i) { mm = m[i]; ll = l[i]; }
+            if (sub < G) *reinterpret_cast<float2*>(wml + sub * WS_ML) = make_float2(mm, ll);
+          }
         }
         if (more) {
           // the cursor is already in the next request, whose first tile this wave holds
           b = cb;
           j = 0;
+          b_np = c_np;
+          b_p0 = c_p0;
           ELLM_LOAD_Q(b)
           ELLM_LOAD_NEW_ROW(b)
           q_settled = false;
@@ -508,8 +533,25 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
 #undef ELLM_TILE_PV
 }
 
+// Launched with one wave per SIMD, so a wave may use the SIMD's whole register file. The instances
+// for up to 4 q heads per kv head fit the budget of two waves per SIMD with room to spare and keep
+// that cap (it is what their schedule was tuned under); the 8-head instance, whose accumulators
+// alone take 64 registers more, is compiled without it and does not spill.
+template <int D, int G, bool APPEND>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_partial_kernel(
+    PoolView pv, const uint16_t* __restrict__ q, const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
+    float* __restrict__ ws, uint16_t* __restrict__ out, float scale_log2, int32_t g_first, BatchArgs a) {
+  decode_partial_body<D, G, APPEND>(pv, q, k_new, v_new, ws, out, scale_log2, g_first, a);
+}
+template <int D, int G, bool APPEND>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void decode_partial_kernel_wide(
+    PoolView pv, const uint16_t* __restrict__ q, const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
+    float* __restrict__ ws, uint16_t* __restrict__ out, float scale_log2, int32_t g_first, BatchArgs a) {
+  decode_partial_body<D, G, APPEND>(pv, q, k_new, v_new, ws, out, scale_log2, g_first, a);
+}
+
 // ---------------------------------------------------------------------------------------------
-// combine pass: one wave per (request, q head). First the common maximum and the normaliser from
+// combine pass: one wave per (split request, q head). First the common maximum and the normaliser from
 // the (m, l) pairs of all partials, one partial per lane; then the weighted sum of the
 // accumulators, whose loads do not depend on one another.
 // ---------------------------------------------------------------------------------------------
@@ -518,10 +560,11 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const float* __restr
                                                             int32_t n_q_heads, int32_t n_kv_heads, int32_t group,
                                                             BatchArgs a) {
   constexpr int DPL = D / 64;        // output dims per lane
-  const int b = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+  const int h = blockIdx.y, lane = threadIdx.x;
+  const int b = (a.split_req[blockIdx.x >> 2] >> ((blockIdx.x & 3) * 8)) & 0xff;   // blockIdx.x-th split request
   const int g = h / group;
   const int n_part = a.req[b].n_part;
-  const int64_t row0 = (a.ws_slot0 + (int64_t)(b * n_kv_heads + g) * a.max_partials) * group + (h - g * group);
+  const int64_t row0 = ((int64_t)g * a.parts_per_head + a.req[b].part0) * group + (h - g * group);
   const float* p0 = ws + row0 * D;                                            // accumulator rows of this head
   const float* q0 = ws + (int64_t)a.ws_slots * group * D + row0 * WS_ML;      // their (m, l) pairs
   const int64_t stride = (int64_t)group * D, qstride = (int64_t)group * WS_ML;
@@ -684,7 +727,7 @@ static int group_step(int left) { return left >= 8 ? 8 : left >= 4 ? 4 : left >=
 template <int D>
 static const void* partial_kernel_ptr(int step) {
   switch (step) {
-    case 8: return (const void*)decode_partial_kernel<D, 8, true>;
+    case 8: return (const void*)decode_partial_kernel_wide<D, 8, true>;
     case 4: return (const void*)decode_partial_kernel<D, 4, true>;
     case 2: return (const void*)decode_partial_kernel<D, 2, true>;
     default: return (const void*)decode_partial_kernel<D, 1, true>;
@@ -702,27 +745,36 @@ int partial_waves_per_cu(int head_dim, int group) {
 
 template <int D, int G>
 static void launch_partial_t(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
-                             float scale_log2, int32_t g_first, const BatchArgs& a, hipStream_t stream) {
+                             void* out, float scale_log2, int32_t g_first, const BatchArgs& a, hipStream_t stream) {
   const unsigned grid = (unsigned)(a.waves_per_head * pv.n_kv_heads);
-  if (k_new)
-    hipLaunchKernelGGL((decode_partial_kernel<D, G, true>), dim3(grid), dim3(64), 0, stream, pv, (const uint16_t*)q,
-                       (const uint4*)k_new, (const uint4*)v_new, ws, scale_log2, g_first, a);
-  else
-    hipLaunchKernelGGL((decode_partial_kernel<D, G, false>), dim3(grid), dim3(64), 0, stream, pv, (const uint16_t*)q,
-                       nullptr, nullptr, ws, scale_log2, g_first, a);
+  if constexpr (G == 8) {
+    if (k_new)
+      hipLaunchKernelGGL((decode_partial_kernel_wide<D, G, true>), dim3(grid), dim3(64), 0, stream, pv, (const uint16_t*)q,
+                         (const uint4*)k_new, (const uint4*)v_new, ws, (uint16_t*)out, scale_log2, g_first, a);
+    else
+      hipLaunchKernelGGL((decode_partial_kernel_wide<D, G, false>), dim3(grid), dim3(64), 0, stream, pv, (const uint16_t*)q,
+                         nullptr, nullptr, ws, (uint16_t*)out, scale_log2, g_first, a);
+  } else {
+    if (k_new)
+      hipLaunchKernelGGL((decode_partial_kernel<D, G, true>), dim3(grid), dim3(64), 0, stream, pv, (const uint16_t*)q,
+                         (const uint4*)k_new, (const uint4*)v_new, ws, (uint16_t*)out, scale_log2, g_first, a);
+    else
+      hipLaunchKernelGGL((decode_partial_kernel<D, G, false>), dim3(grid), dim3(64), 0, stream, pv, (const uint16_t*)q,
+                         nullptr, nullptr, ws, (uint16_t*)out, scale_log2, g_first, a);
+  }
 }
 
 // a group size that is not 8, 4, 2 or 1 is covered by several launches over the same K/V
 template <int D>
 static int launch_partial_d(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
-                            float scale_log2, const BatchArgs& a, hipStream_t stream) {
+                            void* out, float scale_log2, const BatchArgs& a, hipStream_t stream) {
   int done = 0;
   while (done < pv.group) {
     const int step = group_step(pv.group - done);
-    if (step == 8) launch_partial_t<D, 8>(pv, q, k_new, v_new, ws, scale_log2, done, a, stream);
-    else if (step == 4) launch_partial_t<D, 4>(pv, q, k_new, v_new, ws, scale_log2, done, a, stream);
-    else if (step == 2) launch_partial_t<D, 2>(pv, q, k_new, v_new, ws, scale_log2, done, a, stream);
-    else launch_partial_t<D, 1>(pv, q, k_new, v_new, ws, scale_log2, done, a, stream);
+    if (step == 8) launch_partial_t<D, 8>(pv, q, k_new, v_new, ws, out, scale_log2, done, a, stream);
+    else if (step == 4) launch_partial_t<D, 4>(pv, q, k_new, v_new, ws, out, scale_log2, done, a, stream);
+    else if (step == 2) launch_partial_t<D, 2>(pv, q, k_new, v_new, ws, out, scale_log2, done, a, stream);
+    else launch_partial_t<D, 1>(pv, q, k_new, v_new, ws, out, scale_log2, done, a, stream);
     ELLM_HIP_CHECK_LAUNCH();
     done += step;
   }
@@ -730,19 +782,19 @@ static int launch_partial_d(const PoolView& pv, const void* q, const void* k_new
 }
 
 int launch_decode_partial(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
-                          float scale_log2, const BatchArgs& a, hipStream_t stream) {
+                          void* out, float scale_log2, const BatchArgs& a, hipStream_t stream) {
   if (a.n_req <= 0 || a.waves_per_head <= 0) return 0;
-  return pv.head_dim == 128 ? launch_partial_d<128>(pv, q, k_new, v_new, ws, scale_log2, a, stream)
-                            : launch_partial_d<64>(pv, q, k_new, v_new, ws, scale_log2, a, stream);
+  return pv.head_dim == 128 ? launch_partial_d<128>(pv, q, k_new, v_new, ws, out, scale_log2, a, stream)
+                            : launch_partial_d<64>(pv, q, k_new, v_new, ws, out, scale_log2, a, stream);
 }
 
 int launch_decode_combine(const PoolView& pv, const float* ws, void* out, const BatchArgs& a, hipStream_t stream) {
-  if (a.n_req <= 0) return 0;
+  if (a.n_req <= 0 || a.n_split_req <= 0) return 0;
   if (pv.head_dim == 128)
-    hipLaunchKernelGGL(decode_combine_kernel<128>, dim3(a.n_req, pv.n_q_heads), dim3(64), 0, stream, ws,
+    hipLaunchKernelGGL(decode_combine_kernel<128>, dim3(a.n_split_req, pv.n_q_heads), dim3(64), 0, stream, ws,
                        (uint16_t*)out, pv.n_q_heads, pv.n_kv_heads, pv.group, a);
   else
-    hipLaunchKernelGGL(decode_combine_kernel<64>, dim3(a.n_req, pv.n_q_heads), dim3(64), 0, stream, ws,
+    hipLaunchKernelGGL(decode_combine_kernel<64>, dim3(a.n_split_req, pv.n_q_heads), dim3(64), 0, stream, ws,
                        (uint16_t*)out, pv.n_q_heads, pv.n_kv_heads, pv.group, a);
   ELLM_HIP_CHECK_LAUNCH();
   return 0;

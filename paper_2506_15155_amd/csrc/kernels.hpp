@@ -28,32 +28,41 @@ struct PoolView {
 // For every kv head the tiles of all requests, laid end to end in request order, form one sequence
 // of tiles_per_head tiles, which is dealt out evenly to waves_per_head waves: wave w takes
 // tiles_each tiles, the first tiles_extra waves one more, each from where the wave before it
-// stopped. A wave whose share runs from one request into the next writes a partial result for
-// each; so request b gets n_part partials per kv head, numbered from the wave that holds its first
-// tile (wave_first). A launch has one wave for every SIMD of the GPU (a second wave on a SIMD is
-// served markedly worse than the first and slows both down): all are resident at once and have
-// the same amount to read, so none waits for a slot and none is left over at the end. The cut is
-// fixed by the plan, so results do not depend on which wave ran when.
+// stopped. A wave whose share runs from one request into the next finishes a result for each; so
+// request b is covered by n_part waves per kv head, numbered from the wave that holds its first
+// tile (wave_first). A request that lies wholly inside one wave's share (n_part == 1) needs no
+// second pass: that wave normalises and writes the output row itself. Only the others ("split"
+// requests) get partial results in the workspace, part0 + j for the j-th wave, and a combine pass.
+// A launch has one wave for every SIMD of the GPU (a second wave on a SIMD is served markedly
+// worse than the first and slows both down): all are resident at once and have the same amount to
+// read, so none waits for a slot and none is left over at the end. The cut is fixed by the plan,
+// so results do not depend on which wave ran when.
+//
+// Workspace of a launch, from the pointer the launch is given: accumulator rows
+// [kv head][partial slot of the head][q head of the group][D] fp32 (ws_slots = n_kv_heads *
+// parts_per_head slots in all), then the (m, l) pairs in the same order, WS_ML floats each.
 struct BatchArgs {
   int32_t n_req;
   int32_t q_row0;             // row of the first request in q / out
   int32_t tiles_per_head;     // tiles of all requests of the launch, for one kv head
   int32_t waves_per_head;     // <= tiles_per_head
   int32_t tiles_each, tiles_extra;   // tiles_per_head = waves_per_head * tiles_each + tiles_extra
-  int32_t max_partials;       // partial slots per (request, kv head) = most partials any request has
-  int32_t ws_slot0;           // first partial slot of this launch in the workspace
+  int32_t parts_per_head;     // partial slots per kv head = sum of n_part over the split requests
+  int32_t ws_slots;           // n_kv_heads * parts_per_head
   int32_t use_wave_req;       // wave_req is filled in (waves_per_head <= MAX_WAVE_REQ)
-  int32_t ws_slots;           // partial slots of the whole call: the (m, l) region starts behind that many accumulator rows
+  int32_t n_split_req;        // requests with n_part > 1: the combine pass runs for these only
   // request that holds the first tile of wave w of a kv head, one byte each: lets a wave find its
   // request with one scalar load instead of a search through the prefix entries
   uint32_t wave_req[MAX_WAVE_REQ / 4];
+  // the split requests in ascending order, one byte each
+  uint32_t split_req[MAX_LAUNCH_REQ / 4];
   // per request, one record, so that a wave gets all of it with one round of scalar loads
   struct Req {
     int32_t len, tensor;
     int32_t tile_prefix;      // tiles of the requests before this one
     int32_t wave_first;       // wave that holds this request's first tile
     int32_t n_part;           // waves that hold tiles of this request
-    int32_t pad;
+    int32_t part0;            // first partial slot of the request within a kv head's slots (split requests)
   } req[MAX_LAUNCH_REQ];
 };
 
@@ -80,8 +89,9 @@ int launch_kv_append(const PoolView& pv, const void* k_new, const void* v_new, c
 // k_new / v_new non-NULL: fused append. a.len then counts one token per request whose K/V row
 // ([request][kv head][dim], rows q_row0 .. of the caller's batch) is still in k_new / v_new; the
 // kernel uses it from there and writes it into the chunk.
+// out: the caller's output rows; requests with n_part == 1 are finished by the partial pass itself.
 int launch_decode_partial(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
-                          float scale_log2, const BatchArgs& a, hipStream_t stream);
+                          void* out, float scale_log2, const BatchArgs& a, hipStream_t stream);
 int launch_decode_combine(const PoolView& pv, const float* ws, void* out, const BatchArgs& a, hipStream_t stream);
 
 // calibration (measurement only)

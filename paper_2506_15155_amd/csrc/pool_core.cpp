@@ -23,6 +23,7 @@ PoolCore::PoolCore(const Geometry& g, const uint8_t* initial_owner) : g_(g) {
   for (int32_t i = 0; i < g.max_tensors; i++) free_ids_.insert(free_ids_.end(), i);
   t_.resize(g.max_tensors);
   table_.assign((size_t)g.max_tensors * g.max_slots, ENTRY_UNMAPPED);
+  row_version_.assign(g.max_tensors, 0u);
   stamp_.assign((size_t)std::max(g.n_chunks, g.max_tensors), 0u);
 }
 
@@ -36,6 +37,7 @@ void PoolCore::set_entry(int32_t id, int32_t slot, int32_t value) {
   if (table_[flat] != value) {
     table_[flat] = value;
     dirty_.push_back(flat);
+    row_version_[id]++;
   }
 }
 
@@ -362,7 +364,7 @@ int PoolCore::append_check(const int32_t* ids, int32_t batch, const int32_t* n_n
   return OK;
 }
 
-void PoolCore::append_commit(const int32_t* ids, int32_t batch, const std::vector<int32_t>& n_eff) {
+void PoolCore::append_commit(const int32_t* ids, int32_t batch, const int32_t* n_eff) {
   for (int32_t b = 0; b < batch; b++) t_[ids[b]].len += n_eff[b];
 }
 

@@ -77,7 +77,7 @@ class PoolCore {
   // append: check the whole batch; on success `n_eff[b]` holds the token counts. commit bumps lens.
   int append_check(const int32_t* ids, int32_t batch, const int32_t* n_new, std::vector<int32_t>& n_eff,
                    int64_t* total);
-  void append_commit(const int32_t* ids, int32_t batch, const std::vector<int32_t>& n_eff);
+  void append_commit(const int32_t* ids, int32_t batch, const int32_t* n_eff);
   // extra: tokens a not yet committed append adds to every request (0 or 1)
   int decode_check(const int32_t* ids, int32_t batch, int32_t extra = 0);
 
@@ -96,6 +96,8 @@ class PoolCore {
   }
   const int32_t* row(int32_t id) const { return &table_[(size_t)id * g_.max_slots]; }
   const std::vector<int32_t>& table() const { return table_; }
+  // bumped by every change of an entry of the tensor's row
+  uint32_t row_version(int32_t id) const { return row_version_[id]; }
 
   // table entries changed since the last take_dirty(): flat index into table()
   std::vector<int64_t> take_dirty();
@@ -127,6 +129,7 @@ class PoolCore {
   std::vector<TensorRec> t_;
   std::vector<int32_t> table_;     // max_tensors x max_slots, row-major, ENTRY_UNMAPPED where empty
   std::vector<int64_t> dirty_;
+  std::vector<uint32_t> row_version_;
   int32_t logical_host_ = 0;
   struct Slo {
     bool on = false;

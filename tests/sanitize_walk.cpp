@@ -172,7 +172,7 @@ int main(int argc, char** argv) {
         std::vector<int32_t> n_eff;
         int64_t total = 0;
         a = lib.append_check(tids.data(), (int32_t)tids.size(), np_, n_eff, &total);
-        if (a == 0) lib.append_commit(tids.data(), (int32_t)tids.size(), n_eff);
+        if (a == 0) lib.append_commit(tids.data(), (int32_t)tids.size(), n_eff.data());
         b = orc_kv_append(orc, tids.data(), (int32_t)tids.size(), np_, kv.data(), kv.data());
       } break;
       case 10: {

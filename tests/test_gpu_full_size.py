@@ -38,7 +38,7 @@ def bits_np(t: torch.Tensor) -> np.ndarray:
 def run_sampled(cfg, n_sample):
     """History drawn on the device (seeded) and written through the library for every request; the
     same values go to the oracle for a seeded sample of requests (always with the longest and the
-    shortest one), which it then computes one by one."""
+    shortest one, spread evenly over the length order), which it then computes one by one."""
     st = W.draw_step(cfg, with_values=False)
     owner = st.placement.owner if cfg.act_fraction > 0 else None
     dev = torch.empty(cfg.n_chunks * cfg.chunk_bytes, dtype=torch.uint8, device="cuda")
@@ -50,11 +50,11 @@ def run_sampled(cfg, n_sample):
     if len(st.placement.act_busy):
         assert E.ellm_pool_set_act_busy(pool, st.placement.act_busy, 1, check=False) == 0
         assert orc.set_act_busy(st.placement.act_busy, 1) == 0
-    rng = np.random.default_rng(cfg.seed + 77)
-    sample = {int(np.argmax(st.lens)), int(np.argmin(st.lens))}
-    while len(sample) < n_sample:
-        sample.add(int(rng.integers(cfg.batch)))
-    sample = sorted(sample)
+    # requests at evenly spaced ranks of the length order: the shortest, the longest and, from 11
+    # samples on, at least one from every length decile
+    order = np.argsort(st.lens, kind="stable")
+    ranks = np.unique(np.rint(np.linspace(0, cfg.batch - 1, min(n_sample, cfg.batch))).astype(int))
+    sample = sorted(int(order[r]) for r in ranks)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(cfg.seed)
     shape = (cfg.n_kv_heads, cfg.head_dim)
@@ -123,14 +123,14 @@ def run_sampled(cfg, n_sample):
 
 def test_mha13b_full_sampled():
     """13B-shaped MHA layer at full size (128 requests, 2k..16k tokens, 102-token chunks, half the
-    pool busy activations): 4 sampled requests against the oracle."""
-    run_sampled(W.CONFIGS["mha13b"], 4)
+    pool busy activations): 16 requests, at least one from every length decile, against the oracle."""
+    run_sampled(W.CONFIGS["mha13b"], 16)
 
 
-def test_long70b_full_sampled():
+def test_long70b_full_every_request():
     """70B-shaped long-context layer at full size (16 requests of 32k..128k tokens, group of 8):
-    the longest, the shortest and one more request against the oracle."""
-    run_sampled(W.CONFIGS["long70b"], 3)
+    every request against the oracle."""
+    run_sampled(W.CONFIGS["long70b"], 16)
 
 
 def test_elastic_ten_steps_twin_run():

@@ -334,6 +334,69 @@ def test_split_plan_depends_only_on_lengths():
     assert plans[0] == plans[1]
 
 
+def test_workspace_bytes_bounds_every_plan():
+    """ellm_workspace_bytes is an upper bound of what any launch's partition needs: checked against the
+    partition the library itself reports for the five workload shapes at their seeded lengths, for a
+    batch of many short requests (most request boundaries per wave), one of 300 requests (three
+    launches) and a single long request."""
+    import workloads as W
+    cases = [(W.CONFIGS[n], None) for n in ("tiny", "llama8b", "mha13b", "elastic", "long70b")]
+    cases.append((W.scaled(W.CONFIGS["llama8b"], batch=128), np.full(128, 65)))
+    cases.append((W.scaled(W.CONFIGS["llama8b"], batch=300), None))
+    cases.append((W.scaled(W.CONFIGS["long70b"], batch=1), np.array([131072])))
+    for cfg, lens in cases:
+        if lens is None:
+            lens = W.draw_lengths(cfg, np.random.default_rng(cfg.seed))
+        Tc, B = cfg.tokens_per_chunk, cfg.batch
+        need = [int(-(-int(l) // Tc)) for l in lens]
+        P = E.ellm_pool_create(None, None, cfg.chunk_bytes, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, B, max(need),
+                               flags=1, device_bytes=(sum(need) + 1) * cfg.chunk_bytes)
+        ids = []
+        for b in range(B):
+            t = E.ellm_tensor_create(P, need[b] * Tc)
+            E.ellm_tensor_map_chunks(P, t, 0, need[b])
+            ids.append(t)
+        E.ellm_kv_append(P, ids, DUMMY, DUMMY, np.asarray(lens, np.int32), stream=0)
+        n_split, _ = E.ellm_decode_plan(P, ids)
+        slot_bytes = cfg.group * (cfg.head_dim + 2) * 4
+        cap = E.ellm_workspace_bytes(cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, B)
+        assert cap > 0 and cap % slot_bytes == 0
+        assert cap == (1024 + cfg.n_kv_heads * (min(B, 128) - 1)) * slot_bytes       # no device here: 1024 SIMDs assumed
+        for b0 in range(0, B, 128):                                                   # one launch per 128 requests
+            ns = n_split[b0:b0 + 128]
+            slots = cfg.n_kv_heads * int(ns[ns > 1].sum())
+            assert slots * slot_bytes <= cap, (cfg.name, B, slots)
+        E.ellm_pool_destroy(P)
+    assert E.ellm_workspace_bytes(32, 8, 96, 4) == 0 and E.ellm_workspace_bytes(32, 8, 128, 0) == 0
+
+
+def test_refused_launch_leaves_whole_groups():
+    """An append of more than 128 requests works in launches of 128. When the runtime refuses one (forced
+    here by the test hook), the groups before it are appended completely and the rest not at all: the
+    state equals the oracle's after an append of exactly those groups."""
+    Pn = Pair(n_chunks=320, n_host=0, max_tensors=300, max_slots=2)
+    ids = []
+    for i in range(300):
+        t = E.ellm_tensor_create(Pn.lib, 32)
+        assert Pn.orc.tensor_create(32) == (0, t)
+        assert E.ellm_tensor_map_chunks(Pn.lib, t, 0, 1, None, check=False) == 0 == Pn.orc.map_chunks(t, 0, 1, None, 0)
+        ids.append(t)
+    n_new = (np.arange(300) % 5 + 1).astype(np.int32)
+    E.ellm_debug_fail_launch(Pn.lib, 2)
+    rc = E.ellm_kv_append(Pn.lib, ids, DUMMY, DUMMY, n_new, stream=0, check=False)
+    assert rc == E.ERR.HIP and "refused" in E.ellm_last_error()
+    rows = np.zeros((int(n_new[:128].sum()), Pn.Hkv, Pn.D), np.uint16)
+    assert Pn.orc.append(ids[:128], rows, rows, n_new[:128]) == 0
+    Pn.compare()
+    lens = [E.ellm_tensor_get_table(Pn.lib, t)[1] for t in ids]
+    assert lens[:128] == list(n_new[:128]) and not any(lens[128:])
+    # the hook is spent: the rest goes through, and a check that fails still changes nothing
+    assert E.ellm_kv_append(Pn.lib, ids[128:], DUMMY, DUMMY, n_new[128:], stream=0, check=False) == 0
+    assert E.ellm_kv_append(Pn.lib, ids, DUMMY, DUMMY, np.full(300, 32, np.int32), stream=0, check=False) == E.ERR.RANGE
+    assert [E.ellm_tensor_get_table(Pn.lib, t)[1] for t in ids] == list(n_new)
+    Pn.close()
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py is a one-GPU measurement: asking for more exits with a message, before any GPU work."""
     import subprocess
