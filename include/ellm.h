@@ -261,6 +261,24 @@ int ellm_kv_append(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, co
 int ellm_decode_attention(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, const void* q,
                           void* out, float scale, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid it): ellm_decode_attention with the partial results kept in a fixed
+ * workspace of ELLM_NOALLOC_WORKSPACE_BYTES that is part of the library's own device image instead
+ * of the pool's allocated one. The call allocates and frees nothing on the device and never waits
+ * for it. Same arguments, checks, kernels, partition and output bits as ellm_decode_attention.
+ * Additional errors: INVALID if the pool's device-side metadata has not been created yet (creating
+ * it allocates; ellm_pool_prepare and every append / migration call do it, so a pool whose tensors
+ * hold tokens has it); RANGE if a launch of the batch needs more partial results than the fixed workspace holds (a
+ * launch of n requests needs at most SIMDs + n_kv_heads * (n - 1) slots of G * (head_dim + 2) * 4
+ * bytes: 3.2 MB for 64 requests of 32 q / 8 kv heads of 128 on 1024 SIMDs). Every GPU the library
+ * runs on holds one such workspace from load to process end, shared by all pools and all calls of
+ * this entry point on that GPU: calls that overlap in time on one GPU (two streams, two pools)
+ * race on it and must be ordered by the caller. Nothing in it needs clearing between calls: every
+ * slot a call reads, the same call has written before. */
+#define ELLM_NOALLOC_WORKSPACE_BYTES (16u << 20)
+int ellm_decode_attention_noalloc(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, const void* q,
+                                  void* out, float scale, void* stream);
+
 /* One decode iteration in a single pass (Sec. 3.1: every sequence writes one token, then attends
  * over its whole context): the same tables, lengths, chunk bytes and output bits as
  * ellm_kv_append(pool, ids, batch, NULL, k_new, v_new, stream) followed by

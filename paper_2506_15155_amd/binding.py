@@ -26,6 +26,7 @@ ELLM_CHUNK_FREE, ELLM_CHUNK_MAPPED, ELLM_CHUNK_BUSY = 0, 1, 2
 ELLM_BF16 = 1
 ELLM_MAP_ALLOW_INFLATE = 1
 ELLM_POOL_METADATA_ONLY = 1
+ELLM_NOALLOC_WORKSPACE_BYTES = 16 << 20
 
 
 class ERR:
@@ -74,6 +75,7 @@ _sigs = {
     "ellm_pool_set_act_busy": [_vp, _i32p, C.c_int32, C.c_int],
     "ellm_kv_append": [_vp, _i32p, C.c_int32, _i32p, _vp, _vp, _vp],
     "ellm_decode_attention": [_vp, _i32p, C.c_int32, _vp, _vp, C.c_float, _vp],
+    "ellm_decode_attention_noalloc": [_vp, _i32p, C.c_int32, _vp, _vp, C.c_float, _vp],
     "ellm_kv_append_decode": [_vp, _i32p, C.c_int32, _vp, _vp, _vp, _vp, C.c_float, _vp],
     "ellm_chunk_deflate_to_host": [_vp, C.c_int32, C.c_int32, C.c_int32],
     "ellm_chunk_inflate_from_host": [_vp, C.c_int32, C.c_int32, C.c_int32, _i32p],
@@ -304,6 +306,12 @@ def ellm_decode_attention(pool, ids, q, out, scale=0.0, stream=None, check=True)
     _, p, n = _i32(ids)
     s = _stream(stream)
     return _ret(lib.ellm_decode_attention(pool, p, n, _ptr(q), _ptr(out), float(scale), s), check)
+
+
+def ellm_decode_attention_noalloc(pool, ids, q, out, scale=0.0, stream=None, check=True):
+    _, p, n = _i32(ids)
+    s = _stream(stream)
+    return _ret(lib.ellm_decode_attention_noalloc(pool, p, n, _ptr(q), _ptr(out), float(scale), s), check)
 
 
 def ellm_kv_append_decode(pool, ids, k_new, v_new, q, out, scale=0.0, stream=None, check=True):

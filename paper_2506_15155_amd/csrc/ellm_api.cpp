@@ -52,6 +52,8 @@ struct ellm_pool {
   int32_t* d_table = nullptr;
   float* d_ws = nullptr;               // partial results of one decode launch (see BatchArgs)
   int64_t ws_cap_slots = 0;            // partial slots it holds
+  float* static_ws = nullptr;          // this device's copy of the library's fixed workspace
+  int64_t static_ws_slots = 0;
   hipStream_t side_in = nullptr;       // fetches (host -> device)
   hipStream_t side_out = nullptr;      // offloads (device -> host): a stream of its own, so that the two
                                        // directions use their own copy engines and run at the same time
@@ -126,6 +128,8 @@ ellm::PoolView view_of(const ellm_pool* p) {
   return v;
 }
 
+int32_t wave_slots(ellm_pool* p);
+
 // SIMDs of the current device (4 per compute unit); without a device, those of a nominal MI355X
 int32_t device_simds() {
   int dev = 0, cus = 0;
@@ -157,6 +161,17 @@ int ensure_device(ellm_pool* p) {
   HIP_TRY(hipStreamCreateWithFlags(&p->side_in, hipStreamNonBlocking), "hipStreamCreate(side)");
   HIP_TRY(hipStreamCreateWithFlags(&p->side_out, hipStreamNonBlocking), "hipStreamCreate(side)");
   HIP_TRY(hipEventCreateWithFlags(&p->ev_switch, hipEventDisableTiming), "hipEventCreate");
+  {
+    // everything a later call that may not allocate will need is looked up now: the wave capacity
+    // (an occupancy query) and this device's address of the library's fixed workspace
+    (void)wave_slots(p);
+    size_t bytes = 0;
+    const int e = ellm::static_workspace(&p->static_ws, &bytes);
+    if (e) return hip_err((hipError_t)e, "hipGetSymbolAddress(fixed workspace)");
+    p->static_ws_slots = (int64_t)(bytes / slot_bytes(p->geom.group, p->geom.head_dim));
+    p->launches.reserve(((size_t)p->geom.max_tensors + ellm::MAX_LAUNCH_REQ - 1) / ellm::MAX_LAUNCH_REQ);
+    p->tiles_tmp.reserve(ellm::MAX_LAUNCH_REQ);
+  }
   if (p->geom.n_host_slots > 0) {
     p->chunk_compute.assign(p->geom.n_chunks, 0);
     p->chunk_in.assign(p->geom.n_chunks, 0);
@@ -697,7 +712,8 @@ static int decode_impl(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, c
     most_slots = std::max(most_slots, p->plan_slots);
   }
   if (ws_fixed && most_slots > ws_fixed_slots)
-    return set_err(ELLM_ERR_RANGE, "decode_attention: the batch needs more partial results than the fixed workspace holds");
+    return set_err(ELLM_ERR_RANGE, "decode_attention_noalloc: the batch needs more partial results than the fixed "
+                                   "workspace of ELLM_NOALLOC_WORKSPACE_BYTES holds");
   int rc = enter_compute(p, stream, ids, batch);
   if (rc) return rc;
   if (!ws_fixed && (rc = ensure_workspace(p, most_slots))) return rc;
@@ -737,6 +753,22 @@ int ellm_decode_attention(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch
   if (p->metadata_only) return set_err(ELLM_ERR_NO_DEVICE, "decode_attention: pool has no device");
   int32_t n_launched = 0;
   return decode_impl(p, ids, batch, q, nullptr, nullptr, out, scale, (hipStream_t)stream_, &n_launched);
+}
+
+int ellm_decode_attention_noalloc(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const void* q, void* out,
+                                  float scale, void* stream_) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  if (batch < 0 || !q || !out || !std::isfinite(scale)) return set_err(ELLM_ERR_INVALID, "decode_attention_noalloc: bad argument");
+  int rc = core_err(p, p->core->decode_check(ids, batch));
+  if (rc) return rc;
+  if (batch == 0) return ELLM_OK;
+  if (p->metadata_only) return set_err(ELLM_ERR_NO_DEVICE, "decode_attention_noalloc: pool has no device");
+  if (!p->dev_ready)
+    return set_err(ELLM_ERR_INVALID, "decode_attention_noalloc: the pool's device-side metadata does not exist yet and "
+                                     "creating it allocates: call ellm_pool_prepare first");
+  int32_t n_launched = 0;
+  return decode_impl(p, ids, batch, q, nullptr, nullptr, out, scale, (hipStream_t)stream_, &n_launched, p->static_ws,
+                     p->static_ws_slots);
 }
 
 int ellm_kv_append_decode(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const void* k_new, const void* v_new,

@@ -693,6 +693,33 @@ __global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __
 }
 
 // ---------------------------------------------------------------------------------------------
+// A fixed workspace inside the library's own image, for callers that may not allocate: every GPU
+// the library runs on holds one copy of this array, at its own address, until the process ends.
+// Host code never uses the array's name as an address (on the host it is only a stand-in for the
+// symbol); it asks the runtime for the device address once per device and uses that.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[STATIC_WS_BYTES];
+
+int static_workspace(float** ptr, size_t* bytes) {
+  constexpr int MAX_DEVICES = 64;
+  static void* addr[MAX_DEVICES] = {};           // per device: where that device holds the array
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= MAX_DEVICES) return (int)hipErrorInvalidDevice;
+  if (!addr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return (int)e;
+    if (!p) return (int)hipErrorInvalidSymbol;
+    addr[dev] = p;
+  }
+  *ptr = reinterpret_cast<float*>(addr[dev]);
+  *bytes = STATIC_WS_BYTES;
+  return 0;
+}
+
+// ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
 #define ELLM_HIP_CHECK_LAUNCH()                      \

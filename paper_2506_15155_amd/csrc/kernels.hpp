@@ -1,5 +1,6 @@
 // Argument blocks and launchers shared by the C-ABI layer and the HIP kernels.
 #pragma once
+#include <cstddef>
 #include <cstdint>
 
 #include <hip/hip_runtime_api.h>
@@ -12,6 +13,7 @@ constexpr int MAX_PATCH = 448;        // table entries patched by one launch
 constexpr int TILE_TOKENS = 64;       // rows of K (and V) one wave handles at a time
 constexpr int SIMDS_PER_CU = 4;       // a decode launch runs one wave on each SIMD
 constexpr int WS_ML = 2;              // floats per partial and q head in the (m, l) region of the workspace
+constexpr size_t STATIC_WS_BYTES = 16u << 20;   // the fixed workspace of the entry point that allocates nothing
 
 // what a kernel needs to turn (tensor, token) into an address
 struct PoolView {
@@ -93,6 +95,10 @@ int launch_kv_append(const PoolView& pv, const void* k_new, const void* v_new, c
 int launch_decode_partial(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
                           void* out, float scale_log2, const BatchArgs& a, hipStream_t stream);
 int launch_decode_combine(const PoolView& pv, const float* ws, void* out, const BatchArgs& a, hipStream_t stream);
+
+// Device address and size of the library's fixed workspace on the current device (resolved once per
+// device, kept afterwards). Allocates nothing. Returns 0 or a hipError_t value.
+int static_workspace(float** ptr, size_t* bytes);
 
 // calibration (measurement only)
 int launch_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream);
