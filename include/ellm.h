@@ -74,6 +74,23 @@ extern "C" {
                                       fetch move bookkeeping without copying bytes, decode returns
                                       ELLM_ERR_NO_DEVICE after validating. For host-logic tests.  */
 
+#define ELLM_POOL_DRIVER_MAPPED 2u  /* pool flag: the paper's own mechanism (Sec. 2.1.1 "Virtualization
+                                      Design", Sec. 3.2). The library creates every chunk as a physical
+                                      allocation of its own (device_base must be NULL, device_bytes says how
+                                      many; chunk_bytes must be a multiple of the driver's allocation
+                                      granularity). A tensor is a reserved virtual address range; a chunk that
+                                      backs one of its slots is mapped there by the driver's virtual-memory
+                                      calls, and the append and attention kernels read the tensor as
+                                      contiguous addresses, with no table. The host table is kept all the
+                                      same (it is what every check and every introspection call reads), and
+                                      all chunks are mapped a second time, in id order, into one range
+                                      (ellm_pool_get_device_base), through which copies address them. Every
+                                      call that changes table entries makes the driver calls before it
+                                      returns; one that takes a chunk out of a slot (unmap, offload, destroy,
+                                      chunks taken back by acquire) first waits, on the host, for the kernels
+                                      already enqueued that read that chunk. Same results, bit for bit, as a
+                                      pool without the flag. */
+
 /* Table-entry encoding (compared bit-exactly by tests):
  *   e >= 0   device chunk id
  *   e == -1  slot has no chunk
@@ -99,7 +116,8 @@ typedef int32_t ellm_tensor_id;       /* dense handle >= 0            */
  * by offload / fetch, which always move whole chunks.
  */
 typedef struct ellm_pool_desc {
-  void*    device_base;      /* device, caller-owned, 256-byte aligned; NULL only with METADATA_ONLY */
+  void*    device_base;      /* device, caller-owned, 256-byte aligned; NULL with METADATA_ONLY and
+                                DRIVER_MAPPED                                                       */
   uint64_t device_bytes;
   void*    host_base;        /* host, caller-owned, pinned; NULL iff host_bytes < chunk_bytes     */
   uint64_t host_bytes;
@@ -110,7 +128,7 @@ typedef struct ellm_pool_desc {
   uint16_t dtype;            /* ELLM_BF16                                                         */
   uint32_t max_tensors;      /* tensor handles 0 .. max_tensors-1                                 */
   uint32_t max_slots_per_tensor;
-  uint32_t flags;            /* 0 or ELLM_POOL_METADATA_ONLY                                      */
+  uint32_t flags;            /* 0, ELLM_POOL_METADATA_ONLY or ELLM_POOL_DRIVER_MAPPED             */
   uint32_t reserved;         /* must be 0                                                         */
   const uint8_t* initial_owner; /* host, n_chunks bytes of ELLM_OWNER_*; NULL = all KV.
                                    Every chunk starts FREE.                                       */
@@ -118,7 +136,9 @@ typedef struct ellm_pool_desc {
 
 /* Create a pool over caller-owned buffers (Sec. 2.1: one unified physical pool).
  * Errors: INVALID for any violated constraint above. No HIP call is made here; device-side
- * metadata is created lazily by the first call that launches or copies. */
+ * metadata is created lazily by the first call that launches or copies. A driver-mapped pool is
+ * the exception: its chunks are created and mapped here (errors: HIP, and INVALID for a chunk size
+ * the driver's granularity does not divide). */
 int ellm_pool_create(const ellm_pool_desc* desc, ellm_pool** out);
 
 /* Drains the library's streams, frees its metadata. Caller buffers are untouched. */
@@ -345,6 +365,14 @@ int ellm_pool_slo_observe(ellm_pool* pool, double ttft, double tpot, int32_t* lo
 int ellm_pool_sync(ellm_pool* pool);
 
 /* ---- introspection (host state, for bit-exact checks) -------------------------------------- */
+/* Address of chunk 0 (chunk c is at base + c * chunk_bytes): the caller's device_base, or for a
+ * driver-mapped pool the range into which the library has mapped all its chunks. */
+int ellm_pool_get_device_base(ellm_pool* pool, void** base);
+/* Driver-mapped pools: how many chunk mappings the driver has made and removed for this pool's
+ * tensors so far and the host microseconds spent in those calls (map + set-access, unmap), the
+ * figure the paper reports as the share of time in virtual-memory operations (Sec. 4.6). Any out
+ * pointer may be NULL; zeros for other pools. */
+int ellm_pool_get_mapping_stats(ellm_pool* pool, int64_t* n_map, double* us_map, int64_t* n_unmap, double* us_unmap);
 /* Geometry: any out pointer may be NULL. */
 int ellm_pool_get_geometry(ellm_pool* pool, int32_t* n_chunks, int32_t* tokens_per_chunk,
                            int32_t* n_host_slots, uint64_t* bytes_per_token);
@@ -415,6 +443,11 @@ int ellm_debug_vmm_latency(uint64_t chunk_bytes, int32_t n_chunks, double* us);
 int ellm_debug_vmm_buffer_create(uint64_t chunk_bytes, int32_t n_chunks, uint32_t seed, uint16_t fill16,
                                  void** base, uint64_t* bytes);
 int ellm_debug_vmm_buffer_destroy(void* base);
+
+/* Driver-mapped pools, for comparisons in one pool: on != 0 makes append and attention read the
+ * chunks through the software table (in the range of ellm_pool_get_device_base) as in a plain pool;
+ * 0 goes back to the tensors' own address ranges. Same output bits. INVALID for other pools. */
+int ellm_debug_set_table_kernels(ellm_pool* pool, int on);
 
 /* Test hook for the error path of calls that work in several launches: the nth kernel launch of
  * ellm_kv_append / ellm_decode_attention / ellm_kv_append_decode from now on (1 = the next one) is

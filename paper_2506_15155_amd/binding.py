@@ -26,6 +26,7 @@ ELLM_CHUNK_FREE, ELLM_CHUNK_MAPPED, ELLM_CHUNK_BUSY = 0, 1, 2
 ELLM_BF16 = 1
 ELLM_MAP_ALLOW_INFLATE = 1
 ELLM_POOL_METADATA_ONLY = 1
+ELLM_POOL_DRIVER_MAPPED = 2
 ELLM_NOALLOC_WORKSPACE_BYTES = 16 << 20
 
 
@@ -82,6 +83,9 @@ _sigs = {
     "ellm_pool_sync": [_vp],
     "ellm_pool_prepare": [_vp, _vp],
     "ellm_debug_fail_launch": [_vp, C.c_int32],
+    "ellm_pool_get_device_base": [_vp, C.POINTER(C.c_void_p)],
+    "ellm_pool_get_mapping_stats": [_vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)],
+    "ellm_debug_set_table_kernels": [_vp, C.c_int],
     "ellm_pool_get_geometry": [_vp, _i32p, _i32p, _i32p, C.POINTER(C.c_uint64)],
     "ellm_tensor_get_table": [_vp, C.c_int32, _i32p, C.c_int32, _i32p, C.POINTER(C.c_int64)],
     "ellm_pool_get_owner_state": [_vp, _vp, _vp, _i32p, _i32p],
@@ -341,6 +345,22 @@ def ellm_workspace_bytes(n_q_heads, n_kv_heads, head_dim, max_batch):
     d = _Desc()
     d.n_q_heads, d.n_kv_heads, d.head_dim, d.dtype = n_q_heads, n_kv_heads, head_dim, ELLM_BF16
     return int(lib.ellm_workspace_bytes(C.byref(d), int(max_batch)))
+
+
+def ellm_pool_get_device_base(pool):
+    base = C.c_void_p()
+    _ret(lib.ellm_pool_get_device_base(pool, C.byref(base)), True)
+    return int(base.value or 0)
+
+
+def ellm_pool_get_mapping_stats(pool):
+    nm, um, nu, uu = C.c_int64(), C.c_double(), C.c_int64(), C.c_double()
+    _ret(lib.ellm_pool_get_mapping_stats(pool, C.byref(nm), C.byref(um), C.byref(nu), C.byref(uu)), True)
+    return {"maps": nm.value, "us_map": um.value, "unmaps": nu.value, "us_unmap": uu.value}
+
+
+def ellm_debug_set_table_kernels(pool, on, check=True):
+    return _ret(lib.ellm_debug_set_table_kernels(pool, int(bool(on))), check)
 
 
 def ellm_debug_fail_launch(pool, nth, check=True):

@@ -86,6 +86,22 @@ struct ellm_pool {
   struct CopySeen { uint32_t row_version = 0; bool valid = false; int64_t in = 0, out = 0; };
   std::vector<CopySeen> copy_seen;
   int32_t fail_launch_in = 0;          // debug: the n-th launch from now fails without launching (0 = off)
+
+  // Driver-mapped pools (ELLM_POOL_DRIVER_MAPPED): the chunks are physical allocations of the
+  // library's own, all mapped once, in id order, into one range (`window`, which is device_base:
+  // copies and table-reading kernels address chunks there), and additionally, while they back a
+  // slot, into the virtual range of that slot's tensor, which is what the attention kernel reads.
+  bool vmm = false;
+  bool vmm_table_kernels = false;      // debug: run the table-reading kernels (on the window) instead
+  int vmm_device = 0;
+  std::vector<hipMemGenericAllocationHandle_t> vmm_handles;   // per chunk
+  size_t vmm_window_mapped = 0;        // chunks mapped into the window so far
+  std::vector<char*> vbase;            // per tensor handle: start of its reserved range, nullptr = none yet
+  std::vector<int32_t> vmm_mapped;     // per (tensor, slot): chunk the driver has mapped there, -1 = none
+  uint64_t* d_vbase = nullptr;         // device copy of vbase
+  std::vector<int32_t> vbase_dirty;    // tensor handles whose base the device copy does not have yet
+  double vmm_map_us = 0, vmm_unmap_us = 0;   // host time spent in the driver's map (+ set-access) and unmap calls
+  int64_t vmm_maps = 0, vmm_unmaps = 0;
   int32_t split_override = 0;
   int32_t wave_slots = 0;              // waves of a decode launch: one per SIMD of the GPU (0 = not asked yet)
   int32_t waves_percent = 100;         // waves of a launch, as a share of what the GPU holds at once
@@ -113,10 +129,20 @@ int core_err(ellm_pool* p, int rc) {
   return rc;
 }
 
+int vmm_sync(ellm_pool* p);
+
+// result of a call into the host state machine that may have changed table entries: a failed call
+// changed nothing; after a successful one a driver-mapped pool brings its mappings in line
+int core_changed(ellm_pool* p, int rc) {
+  if (rc) return core_err(p, rc);
+  return p->vmm ? vmm_sync(p) : ELLM_OK;
+}
+
 ellm::PoolView view_of(const ellm_pool* p) {
   ellm::PoolView v;
   v.base = p->device_base;
   v.table = p->d_table;
+  v.vbase = (p->vmm && !p->vmm_table_kernels) ? p->d_vbase : nullptr;
   v.chunk_bytes = p->geom.chunk_bytes;
   v.tokens_per_chunk = p->geom.tokens_per_chunk;
   v.tiles_per_chunk = (p->geom.tokens_per_chunk + ellm::TILE_TOKENS - 1) / ellm::TILE_TOKENS;
@@ -158,6 +184,11 @@ int ensure_device(ellm_pool* p) {
   // the workspace is sized once, for the largest launch the automatic partition can produce
   p->ws_cap_slots = launch_slot_bound(device_simds(), p->geom.n_kv_heads, std::min<int32_t>(p->geom.max_tensors, ellm::MAX_LAUNCH_REQ));
   HIP_TRY(hipMalloc((void**)&p->d_ws, (size_t)p->ws_cap_slots * slot_bytes(p->geom.group, p->geom.head_dim)), "hipMalloc(workspace)");
+  if (p->vmm) {
+    const size_t vb = (size_t)p->geom.max_tensors * sizeof(uint64_t);
+    HIP_TRY(hipMalloc((void**)&p->d_vbase, vb), "hipMalloc(tensor bases)");
+    HIP_TRY(hipMemset(p->d_vbase, 0, vb), "hipMemset(tensor bases)");
+  }
   HIP_TRY(hipStreamCreateWithFlags(&p->side_in, hipStreamNonBlocking), "hipStreamCreate(side)");
   HIP_TRY(hipStreamCreateWithFlags(&p->side_out, hipStreamNonBlocking), "hipStreamCreate(side)");
   HIP_TRY(hipEventCreateWithFlags(&p->ev_switch, hipEventDisableTiming), "hipEventCreate");
@@ -172,7 +203,7 @@ int ensure_device(ellm_pool* p) {
     p->launches.reserve(((size_t)p->geom.max_tensors + ellm::MAX_LAUNCH_REQ - 1) / ellm::MAX_LAUNCH_REQ);
     p->tiles_tmp.reserve(ellm::MAX_LAUNCH_REQ);
   }
-  if (p->geom.n_host_slots > 0) {
+  if (p->geom.n_host_slots > 0 || p->vmm) {
     p->chunk_compute.assign(p->geom.n_chunks, 0);
     p->chunk_in.assign(p->geom.n_chunks, 0);
     p->chunk_out.assign(p->geom.n_chunks, 0);
@@ -194,6 +225,23 @@ int ensure_device(ellm_pool* p) {
 // travel in the arguments of small patch kernels, MAX_PATCH per launch, so nothing here waits for
 // the device and no staging buffer has to outlive the call
 int flush_table(ellm_pool* p, hipStream_t stream) {
+  if (!p->vbase_dirty.empty()) {
+    // new tensor ranges: their 64-bit bases go to the device as pairs of 32-bit words
+    ellm::PatchArgs a;
+    a.n = 0;
+    for (size_t i = 0; i < p->vbase_dirty.size(); i++) {
+      const int32_t id = p->vbase_dirty[i];
+      const uint64_t v = (uint64_t)(uintptr_t)p->vbase[id];
+      a.idx[a.n] = 2 * id;     a.val[a.n++] = (int32_t)(uint32_t)v;
+      a.idx[a.n] = 2 * id + 1; a.val[a.n++] = (int32_t)(uint32_t)(v >> 32);
+      if (a.n + 2 > ellm::MAX_PATCH || i + 1 == p->vbase_dirty.size()) {
+        int e = ellm::launch_table_patch((int32_t*)p->d_vbase, a, stream);
+        if (e) return hip_err((hipError_t)e, "tensor base patch launch");
+        a.n = 0;
+      }
+    }
+    p->vbase_dirty.clear();
+  }
   if (!p->core->has_dirty()) return ELLM_OK;
   std::vector<int64_t> dirty = p->core->take_dirty();
   const std::vector<int32_t>& tab = p->core->table();
@@ -211,7 +259,9 @@ int flush_table(ellm_pool* p, hipStream_t stream) {
   return ELLM_OK;
 }
 
-bool tracks_chunks(const ellm_pool* p) { return p->geom.n_host_slots > 0; }
+// chunks are tracked where something besides the kernels touches them: copies to and from host
+// slots, or the driver unmapping them from a tensor's range
+bool tracks_chunks(const ellm_pool* p) { return p->geom.n_host_slots > 0 || p->vmm; }
 
 // the event that covers call `need` of ring r: its own, or, once the ring has gone round, the
 // newest one of the same (in-order) stream
@@ -347,6 +397,113 @@ int settle_copies(ellm_pool* p, const int32_t* chunk_ids, int32_t n) {
   return host_wait(p->r_in, need_in);
 }
 
+// ---- driver-mapped pools --------------------------------------------------------------------
+// The paper's mechanism (Sec. 2.1.1, Sec. 3.2): a tensor is a reserved virtual address range and a
+// chunk that backs one of its slots is mapped there by the driver. The host table stays the
+// source of truth; after every call that changed table entries the driver mappings are brought in
+// line with it, entry by entry: what left a slot is unmapped (once the kernels that may still
+// read it there have finished: the host waits), what came is mapped and made accessible.
+hipMemAllocationProp vmm_prop(int dev) {
+  hipMemAllocationProp prop = {};
+  prop.type = hipMemAllocationTypePinned;
+  prop.location.type = hipMemLocationTypeDevice;
+  prop.location.id = dev;
+  return prop;
+}
+
+int vmm_sync(ellm_pool* p) {
+  if (!p->vmm) return ELLM_OK;
+  const std::vector<int64_t> changed = p->core->take_map_changes();
+  if (changed.empty()) return ELLM_OK;
+  using clk = std::chrono::steady_clock;
+  auto us_since = [](clk::time_point t0) { return std::chrono::duration<double, std::micro>(clk::now() - t0).count(); };
+  const size_t cb = p->geom.chunk_bytes;
+  const std::vector<int32_t>& tab = p->core->table();
+  hipMemAccessDesc acc = {};
+  acc.location.type = hipMemLocationTypeDevice;
+  acc.location.id = p->vmm_device;
+  acc.flags = hipMemAccessFlagsProtReadWrite;
+  for (int64_t flat : changed) {
+    const int32_t id = (int32_t)(flat / p->geom.max_slots), slot = (int32_t)(flat % p->geom.max_slots);
+    const int32_t want = tab[flat] >= 0 ? tab[flat] : -1, have = p->vmm_mapped[flat];
+    if (want == have) continue;
+    if (!p->vbase[id]) {
+      // a tensor handle's range is reserved once, for the largest tensor the pool allows, and kept
+      // for the handle's later lives
+      void* va = nullptr;
+      HIP_TRY(hipMemAddressReserve(&va, (size_t)p->geom.max_slots * cb, 0, nullptr, 0), "hipMemAddressReserve(tensor)");
+      p->vbase[id] = (char*)va;
+      p->vbase_dirty.push_back(id);
+    }
+    char* at = p->vbase[id] + (size_t)slot * cb;
+    if (have >= 0) {
+      if (p->dev_ready) {
+        int rc = host_wait(p->r_compute, p->chunk_compute[have]);
+        if (rc) return rc;
+      }
+      const auto t0 = clk::now();
+      HIP_TRY(hipMemUnmap(at, cb), "hipMemUnmap(tensor slot)");
+      p->vmm_unmap_us += us_since(t0);
+      p->vmm_unmaps++;
+      p->vmm_mapped[flat] = -1;
+    }
+    if (want >= 0) {
+      const auto t0 = clk::now();
+      HIP_TRY(hipMemMap(at, cb, 0, p->vmm_handles[want], 0), "hipMemMap(tensor slot)");
+      HIP_TRY(hipMemSetAccess(at, cb, &acc, 1), "hipMemSetAccess(tensor slot)");
+      p->vmm_map_us += us_since(t0);
+      p->vmm_maps++;
+      p->vmm_mapped[flat] = want;
+    }
+  }
+  return ELLM_OK;
+}
+
+// creates the chunks and the window; on failure everything created so far is released by vmm_teardown
+int vmm_setup(ellm_pool* p) {
+  HIP_TRY(hipGetDevice(&p->vmm_device), "hipGetDevice");
+  hipMemAllocationProp prop = vmm_prop(p->vmm_device);
+  size_t gran = 0;
+  HIP_TRY(hipMemGetAllocationGranularity(&gran, &prop, hipMemAllocationGranularityMinimum), "hipMemGetAllocationGranularity");
+  if (gran == 0 || p->geom.chunk_bytes % gran)
+    return set_err(ELLM_ERR_INVALID, "pool_create: chunk_bytes must be a multiple of the driver's allocation granularity");
+  const size_t cb = p->geom.chunk_bytes, n = (size_t)p->geom.n_chunks;
+  void* va = nullptr;
+  HIP_TRY(hipMemAddressReserve(&va, cb * n, 0, nullptr, 0), "hipMemAddressReserve(window)");
+  p->device_base = (char*)va;
+  p->vmm_handles.reserve(n);
+  for (size_t c = 0; c < n; c++) {
+    hipMemGenericAllocationHandle_t h;
+    HIP_TRY(hipMemCreate(&h, cb, &prop, 0), "hipMemCreate(chunk)");
+    p->vmm_handles.push_back(h);
+  }
+  for (; p->vmm_window_mapped < n; p->vmm_window_mapped++)
+    HIP_TRY(hipMemMap(p->device_base + p->vmm_window_mapped * cb, cb, 0, p->vmm_handles[p->vmm_window_mapped], 0), "hipMemMap(window)");
+  hipMemAccessDesc acc = {};
+  acc.location = prop.location;
+  acc.flags = hipMemAccessFlagsProtReadWrite;
+  HIP_TRY(hipMemSetAccess(p->device_base, cb * n, &acc, 1), "hipMemSetAccess(window)");
+  p->vbase.assign(p->geom.max_tensors, nullptr);
+  p->vmm_mapped.assign((size_t)p->geom.max_tensors * p->geom.max_slots, -1);
+  p->core->log_map_changes(true);
+  return ELLM_OK;
+}
+
+void vmm_teardown(ellm_pool* p) {
+  const size_t cb = p->geom.chunk_bytes;
+  for (size_t flat = 0; flat < p->vmm_mapped.size(); flat++)
+    if (p->vmm_mapped[flat] >= 0) {
+      const size_t id = flat / p->geom.max_slots, slot = flat % p->geom.max_slots;
+      (void)hipMemUnmap(p->vbase[id] + slot * cb, cb);
+    }
+  for (char* va : p->vbase)
+    if (va) (void)hipMemAddressFree(va, (size_t)p->geom.max_slots * cb);
+  for (size_t c = 0; c < p->vmm_window_mapped; c++) (void)hipMemUnmap(p->device_base + c * cb, cb);
+  for (hipMemGenericAllocationHandle_t h : p->vmm_handles) (void)hipMemRelease(h);
+  if (p->device_base) (void)hipMemAddressFree(p->device_base, cb * (size_t)p->geom.n_chunks);
+  p->device_base = nullptr;
+}
+
 // Under the automatic partition a launch never needs more partial slots than the workspace was
 // sized for. With a partition override in force (tests and measurements) it may: then, and only
 // then, the workspace is replaced by a larger one, which waits for the device.
@@ -471,8 +628,10 @@ const char* ellm_last_error(void) { return g_last_error.c_str(); }
 int ellm_pool_create(const ellm_pool_desc* d, ellm_pool** out) {
   if (!d || !out) return set_err(ELLM_ERR_INVALID, "pool_create: NULL argument");
   *out = nullptr;
-  const bool meta = (d->flags & ELLM_POOL_METADATA_ONLY) != 0;
-  if (d->flags & ~ELLM_POOL_METADATA_ONLY || d->reserved) return set_err(ELLM_ERR_INVALID, "pool_create: unknown flags");
+  const bool meta = (d->flags & ELLM_POOL_METADATA_ONLY) != 0, vmm = (d->flags & ELLM_POOL_DRIVER_MAPPED) != 0;
+  if (d->flags & ~(ELLM_POOL_METADATA_ONLY | ELLM_POOL_DRIVER_MAPPED) || d->reserved || (meta && vmm))
+    return set_err(ELLM_ERR_INVALID, "pool_create: unknown flags");
+  if (vmm && d->device_base) return set_err(ELLM_ERR_INVALID, "pool_create: a driver-mapped pool creates its own chunks; device_base must be NULL");
   if (d->dtype != ELLM_BF16) return set_err(ELLM_ERR_INVALID, "pool_create: dtype must be ELLM_BF16");
   if (d->head_dim != 64 && d->head_dim != 128) return set_err(ELLM_ERR_INVALID, "pool_create: head_dim must be 64 or 128");
   if (!d->n_kv_heads || !d->n_q_heads || d->n_q_heads % d->n_kv_heads || d->n_q_heads / d->n_kv_heads > 64)
@@ -484,7 +643,7 @@ int ellm_pool_create(const ellm_pool_desc* d, ellm_pool** out) {
   const uint64_t n_host = d->host_bytes / d->chunk_bytes;
   if (n_chunks < 1 || n_chunks > 0x7ffffff0ull || n_host > 0x7ffffff0ull)
     return set_err(ELLM_ERR_INVALID, "pool_create: pool must hold between 1 and 2^31 chunks");
-  if (!meta && (!d->device_base || ((uintptr_t)d->device_base & 255)))
+  if (!meta && !vmm && (!d->device_base || ((uintptr_t)d->device_base & 255)))
     return set_err(ELLM_ERR_INVALID, "pool_create: device_base must be a 256-byte aligned device pointer");
   if (!meta && n_host > 0 && !d->host_base) return set_err(ELLM_ERR_INVALID, "pool_create: host_base missing");
   if (!d->max_tensors || !d->max_slots_per_tensor ||
@@ -510,6 +669,15 @@ int ellm_pool_create(const ellm_pool_desc* d, ellm_pool** out) {
   p->device_base = (char*)d->device_base;
   p->host_base = (char*)d->host_base;
   p->metadata_only = meta;
+  p->vmm = vmm;
+  if (vmm) {
+    const int rc = vmm_setup(p);
+    if (rc) {
+      vmm_teardown(p);
+      delete p;
+      return rc;
+    }
+  }
   *out = p;
   return ELLM_OK;
 }
@@ -529,6 +697,11 @@ int ellm_pool_destroy(ellm_pool* p) {
     if (p->ev_switch) (void)hipEventDestroy(p->ev_switch);
     for (hipEvent_t e : p->prof_ev) (void)hipEventDestroy(e);
     if (p->d_ws) (void)hipFree(p->d_ws);
+    if (p->d_vbase) (void)hipFree(p->d_vbase);
+  }
+  if (p->vmm) {
+    if (hipDeviceSynchronize() != hipSuccess) rc = ELLM_ERR_HIP;
+    vmm_teardown(p);
   }
   delete p;
   return rc;
@@ -541,18 +714,18 @@ int ellm_tensor_create(ellm_pool* p, int64_t max_tokens, ellm_tensor_id* out) {
 
 int ellm_tensor_destroy(ellm_pool* p, ellm_tensor_id id) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
-  return core_err(p, p->core->tensor_destroy(id));
+  return core_changed(p, p->core->tensor_destroy(id));
 }
 
 int ellm_tensor_map_chunks(ellm_pool* p, ellm_tensor_id id, int32_t first_slot, int32_t n_slots,
                            const int32_t* chunk_ids, uint32_t flags) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
-  return core_err(p, p->core->map_chunks(id, first_slot, n_slots, chunk_ids, flags));
+  return core_changed(p, p->core->map_chunks(id, first_slot, n_slots, chunk_ids, flags));
 }
 
 int ellm_tensor_unmap_chunks(ellm_pool* p, ellm_tensor_id id, int32_t first_slot, int32_t n_slots) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
-  return core_err(p, p->core->unmap_chunks(id, first_slot, n_slots));
+  return core_changed(p, p->core->unmap_chunks(id, first_slot, n_slots));
 }
 
 int ellm_pool_transfer(ellm_pool* p, const int32_t* chunk_ids, int32_t n, int new_owner) {
@@ -616,13 +789,13 @@ int ellm_kv_append(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const
 
 int ellm_tensor_release(ellm_pool* p, ellm_tensor_id id) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
-  return core_err(p, p->core->tensor_release(id));
+  return core_changed(p, p->core->tensor_release(id));
 }
 
 int ellm_tensor_acquire(ellm_pool* p, int64_t need_tokens, int64_t max_tokens, uint32_t flags, ellm_tensor_id* out) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
   if (flags & ~ELLM_MAP_ALLOW_INFLATE) return set_err(ELLM_ERR_INVALID, "tensor_acquire: unknown flags");
-  return core_err(p, p->core->tensor_acquire(need_tokens, max_tokens, flags, out));
+  return core_changed(p, p->core->tensor_acquire(need_tokens, max_tokens, flags, out));
 }
 
 int ellm_tensor_is_released(ellm_pool* p, ellm_tensor_id id) {
@@ -635,7 +808,7 @@ int ellm_tensor_is_released(ellm_pool* p, ellm_tensor_id id) {
 int ellm_kv_premap_next(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, uint32_t flags, int32_t* n_mapped) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
   if (flags & ~ELLM_MAP_ALLOW_INFLATE) return set_err(ELLM_ERR_INVALID, "premap_next: unknown flags");
-  return core_err(p, p->core->premap_next(ids, batch, flags, n_mapped));
+  return core_changed(p, p->core->premap_next(ids, batch, flags, n_mapped));
 }
 
 int ellm_pool_flush_tables(ellm_pool* p, void* stream) {
@@ -804,7 +977,7 @@ int ellm_chunk_deflate_to_host(ellm_pool* p, ellm_tensor_id id, int32_t first_sl
     if (rc) return rc;
   }
   p->core->offload_commit(id, p->moves);
-  return ELLM_OK;
+  return core_changed(p, ELLM_OK);
 }
 
 int ellm_chunk_inflate_from_host(ellm_pool* p, ellm_tensor_id id, int32_t first_slot, int32_t n_slots,
@@ -823,7 +996,7 @@ int ellm_chunk_inflate_from_host(ellm_pool* p, ellm_tensor_id id, int32_t first_
     if (rc) return rc;
   }
   p->core->fetch_commit(id, p->moves);
-  return ELLM_OK;
+  return core_changed(p, ELLM_OK);
 }
 
 uint64_t ellm_workspace_bytes(const ellm_pool_desc* d, int32_t max_batch) {
@@ -841,6 +1014,27 @@ int ellm_pool_prepare(ellm_pool* p, void* stream) {
   int rc = ensure_device(p);
   if (rc) return rc;
   return flush_table(p, (hipStream_t)stream);
+}
+
+int ellm_pool_get_device_base(ellm_pool* p, void** base) {
+  if (!p || !base) return set_err(ELLM_ERR_INVALID, "get_device_base: NULL argument");
+  *base = p->device_base;
+  return ELLM_OK;
+}
+
+int ellm_pool_get_mapping_stats(ellm_pool* p, int64_t* n_map, double* us_map, int64_t* n_unmap, double* us_unmap) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  if (n_map) *n_map = p->vmm_maps;
+  if (us_map) *us_map = p->vmm_map_us;
+  if (n_unmap) *n_unmap = p->vmm_unmaps;
+  if (us_unmap) *us_unmap = p->vmm_unmap_us;
+  return ELLM_OK;
+}
+
+int ellm_debug_set_table_kernels(ellm_pool* p, int on) {
+  if (!p || !p->vmm) return set_err(ELLM_ERR_INVALID, "set_table_kernels: not a driver-mapped pool");
+  p->vmm_table_kernels = on != 0;
+  return ELLM_OK;
 }
 
 int ellm_debug_fail_launch(ellm_pool* p, int32_t nth) {

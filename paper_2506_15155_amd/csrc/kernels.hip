@@ -127,6 +127,33 @@ constexpr int CPOL_NT = 2;    // cache-policy operand of the load-to-LDS builtin
 typedef const __attribute__((address_space(1))) void* global_cptr_t;
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const int32_t __attribute__((address_space(4)))* const_i32_ptr;
+typedef const uint64_t __attribute__((address_space(4)))* const_u64_ptr;
+
+// How a kernel gets from (tensor, slot) to the chunk's bytes. With the software table the slot's
+// entry names a chunk of the pool. DIRECT is the paper's own arrangement (Sec. 2.1.1, Sec. 3.2): the
+// tensor is a contiguous virtual address range into which the driver has mapped the chunks, so a
+// slot's bytes sit at base + slot * chunk_bytes and no table is read.
+struct TensorWalk {
+  const_i32_ptr trow;      // table row of the tensor (table addressing)
+  const char* tbase;       // start of the tensor's virtual range (direct addressing)
+};
+template <bool DIRECT>
+__device__ __forceinline__ TensorWalk tensor_walk(const PoolView& pv, int32_t tensor) {
+  TensorWalk w;
+  if (DIRECT) {
+    w.trow = nullptr;
+    w.tbase = reinterpret_cast<const char*>(((const_u64_ptr)pv.vbase)[tensor]);
+  } else {
+    w.trow = (const_i32_ptr)(pv.table + (int64_t)tensor * pv.max_slots);
+    w.tbase = nullptr;
+  }
+  return w;
+}
+template <bool DIRECT>
+__device__ __forceinline__ const char* chunk_addr(const PoolView& pv, const TensorWalk& w, int32_t slot) {
+  if (DIRECT) return w.tbase + (uint64_t)slot * pv.chunk_bytes;
+  return pv.base + (uint64_t)w.trow[slot] * pv.chunk_bytes;
+}
 
 // s_waitcnt immediates (gfx9 encoding): vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8
 constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
@@ -144,7 +171,7 @@ __global__ void table_patch_kernel(int32_t* table, PatchArgs a) {
 // ---------------------------------------------------------------------------------------------
 // KV append: copy rows of D bf16 from the dense [token][Hkv][D] inputs to their chunk rows
 // ---------------------------------------------------------------------------------------------
-template <int D>
+template <int D, bool DIRECT>
 __global__ __launch_bounds__(256) void kv_append_kernel(PoolView pv, const uint4* __restrict__ k_new,
                                                         const uint4* __restrict__ v_new, AppendArgs a) {
   // One workgroup per new token: which request it belongs to, its position and its chunk are the
@@ -161,8 +188,8 @@ __global__ __launch_bounds__(256) void kv_append_kernel(PoolView pv, const uint4
   const int64_t pos = (int64_t)a.len_before[b] + (tau - a.tok0[b]);
   const int32_t slot = (int32_t)(pos / pv.tokens_per_chunk);
   const int32_t r = (int32_t)(pos - (int64_t)slot * pv.tokens_per_chunk);
-  const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)a.tensor[b] * pv.max_slots);
-  char* chunk = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + (uint64_t)r * (D * 2);
+  const TensorWalk walk = tensor_walk<DIRECT>(pv, a.tensor[b]);
+  char* chunk = const_cast<char*>(chunk_addr<DIRECT>(pv, walk, slot)) + (uint64_t)r * (D * 2);
   const uint64_t plane_bytes = (uint64_t)pv.tokens_per_chunk * (D * 2);
   const int n16 = pv.n_kv_heads * LPR;       // 16-byte pieces of the token's K (and of its V)
   const uint4* ks = k_new + (int64_t)tau * n16;
@@ -238,7 +265,7 @@ __device__ __forceinline__ Share locate_share(const BatchArgs& a, int32_t index,
 // V of the tile is in flight while its scores are computed, K of the next tile while V is multiplied.
 // Scores are kept in log2 units (scale_log2 = scale * log2 e).
 // ---------------------------------------------------------------------------------------------
-template <int D, int G, bool APPEND>
+template <int D, int G, bool APPEND, bool DIRECT>
 __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const uint16_t* __restrict__ q,
                                                     const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
                                                     float* __restrict__ ws, uint16_t* __restrict__ out, float scale_log2,
@@ -286,7 +313,7 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
     left = tiles_of(len, Tc, pv.tiles_per_chunk);                                                   \
     c_np = nx_.n_part;                                                                              \
     c_p0 = nx_.part0;                                                                               \
-    trow = (const_i32_ptr)(pv.table + (int64_t)nx_.tensor * pv.max_slots);                          \
+    walk = tensor_walk<DIRECT>(pv, nx_.tensor);                                                     \
     slot = 0;                                                                                       \
     r = 0;                                                                                          \
   } else {                                                                                          \
@@ -295,7 +322,7 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
     if (r >= Tc) { r = 0; slot += 1; }                                                              \
   }                                                                                                 \
   nv_c = min(TILE_TOKENS, min(Tc - r, len - (slot * Tc + r)));                                      \
-  kb = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + ((uint64_t)(g * 2) * Tc + r) * ROWB;
+  kb = chunk_addr<DIRECT>(pv, walk, slot) + ((uint64_t)(g * 2) * Tc + r) * ROWB;
 // scores of one tile (lane = token) and online softmax: leaves the tile's weights, rounded to bf16,
 // in pu[] (one per head, for this lane's token). Consecutive dot products go to different heads'
 // accumulators, so no instruction waits for the one before it.
@@ -375,18 +402,18 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
     const Share sh = locate_share(a, blockIdx.x, lane);
     const int32_t g = sh.g, n_tiles = sh.n_tiles;
     const int hq0 = g * pv.group + g_first;            // first q head handled here
-    // cursor: the tile whose K is in LDS or on its way there. cb: its request; len, trow: that
-    // request's length and table row (read-only for the kernel's lifetime: uniform loads)
+    // cursor: the tile whose K is in LDS or on its way there. cb: its request; len, walk: that
+    // request's length and its table row or base address (read-only for the kernel's lifetime: uniform loads)
     int32_t cb = sh.b;
     const BatchArgs::Req first = a.req[cb];
     int32_t len = first.len;
-    const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)first.tensor * pv.max_slots);
+    TensorWalk walk = tensor_walk<DIRECT>(pv, first.tensor);
     const int32_t tile0 = sh.t_lo - first.tile_prefix;
     int32_t left = tiles_of(len, Tc, pv.tiles_per_chunk) - tile0;
     int32_t slot = tile0 / pv.tiles_per_chunk;
     int32_t r = (tile0 - slot * pv.tiles_per_chunk) * TILE_TOKENS;
     int32_t nv_c = min(TILE_TOKENS, min(Tc - r, len - (slot * Tc + r)));
-    const char* kb = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + ((uint64_t)(g * 2) * Tc + r) * ROWB;
+    const char* kb = chunk_addr<DIRECT>(pv, walk, slot) + ((uint64_t)(g * 2) * Tc + r) * ROWB;
     ELLM_LOAD_K_TILE(kb, nv_c)
 
     // the request being accumulated, and which of its partials this wave writes; b_np, b_p0: how
@@ -537,17 +564,17 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
 // for up to 4 q heads per kv head fit the budget of two waves per SIMD with room to spare and keep
 // that cap (it is what their schedule was tuned under); the 8-head instance, whose accumulators
 // alone take 64 registers more, is compiled without it and does not spill.
-template <int D, int G, bool APPEND>
+template <int D, int G, bool APPEND, bool DIRECT>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_partial_kernel(
     PoolView pv, const uint16_t* __restrict__ q, const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
     float* __restrict__ ws, uint16_t* __restrict__ out, float scale_log2, int32_t g_first, BatchArgs a) {
-  decode_partial_body<D, G, APPEND>(pv, q, k_new, v_new, ws, out, scale_log2, g_first, a);
+  decode_partial_body<D, G, APPEND, DIRECT>(pv, q, k_new, v_new, ws, out, scale_log2, g_first, a);
 }
-template <int D, int G, bool APPEND>
+template <int D, int G, bool APPEND, bool DIRECT>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void decode_partial_kernel_wide(
     PoolView pv, const uint16_t* __restrict__ q, const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
     float* __restrict__ ws, uint16_t* __restrict__ out, float scale_log2, int32_t g_first, BatchArgs a) {
-  decode_partial_body<D, G, APPEND>(pv, q, k_new, v_new, ws, out, scale_log2, g_first, a);
+  decode_partial_body<D, G, APPEND, DIRECT>(pv, q, k_new, v_new, ws, out, scale_log2, g_first, a);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -644,7 +671,7 @@ __global__ __launch_bounds__(256) void read_kernel(const uint4* __restrict__ src
 
 // the K/V rows a decode over this batch reads, with the same work partition and load shape (one
 // wave per share of the same cut, 64-row tiles, 128-bit loads), but no arithmetic
-template <int D>
+template <int D, bool DIRECT>
 __global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __restrict__ sink, BatchArgs a) {
   constexpr int LPR = D / 8, RPW = 64 / LPR, NL = 64 / RPW, ROWB = D * 2;
   const int lane = threadIdx.x;
@@ -661,9 +688,9 @@ __global__ __launch_bounds__(64) void kv_stream_kernel(PoolView pv, uint32_t* __
     int32_t slot = tile0 / pv.tiles_per_chunk;
     int32_t r = (tile0 - slot * pv.tiles_per_chunk) * TILE_TOKENS;
     for (int32_t it = 0; it < sh.n_tiles; it++) {
-      const const_i32_ptr trow = (const_i32_ptr)(pv.table + (int64_t)rec.tensor * pv.max_slots);
+      const TensorWalk walk = tensor_walk<DIRECT>(pv, rec.tensor);
       const int32_t nv = min(TILE_TOKENS, min(Tc - r, rec.len - (slot * Tc + r)));
-      const char* kb = pv.base + (uint64_t)trow[slot] * pv.chunk_bytes + ((uint64_t)(g * 2) * Tc + r) * ROWB;
+      const char* kb = chunk_addr<DIRECT>(pv, walk, slot) + ((uint64_t)(g * 2) * Tc + r) * ROWB;
       const char* vb = kb + (uint64_t)Tc * ROWB;
       uint4 kr[NL], vr[NL];
 #pragma unroll
@@ -738,12 +765,12 @@ int launch_table_patch(int32_t* table, const PatchArgs& a, hipStream_t stream) {
 int launch_kv_append(const PoolView& pv, const void* k_new, const void* v_new, const AppendArgs& a,
                      hipStream_t stream) {
   if (a.total_new <= 0) return 0;
-  if (pv.head_dim == 128)
-    hipLaunchKernelGGL(kv_append_kernel<128>, dim3((unsigned)a.total_new), dim3(256), 0, stream, pv,
-                       (const uint4*)k_new, (const uint4*)v_new, a);
-  else
-    hipLaunchKernelGGL(kv_append_kernel<64>, dim3((unsigned)a.total_new), dim3(256), 0, stream, pv,
-                       (const uint4*)k_new, (const uint4*)v_new, a);
+  const dim3 grid((unsigned)a.total_new), block(256);
+  const uint4 *k = (const uint4*)k_new, *v = (const uint4*)v_new;
+  if (pv.head_dim == 128 && pv.vbase) hipLaunchKernelGGL((kv_append_kernel<128, true>), grid, block, 0, stream, pv, k, v, a);
+  else if (pv.head_dim == 128) hipLaunchKernelGGL((kv_append_kernel<128, false>), grid, block, 0, stream, pv, k, v, a);
+  else if (pv.vbase) hipLaunchKernelGGL((kv_append_kernel<64, true>), grid, block, 0, stream, pv, k, v, a);
+  else hipLaunchKernelGGL((kv_append_kernel<64, false>), grid, block, 0, stream, pv, k, v, a);
   ELLM_HIP_CHECK_LAUNCH();
   return 0;
 }
@@ -754,10 +781,10 @@ static int group_step(int left) { return left >= 8 ? 8 : left >= 4 ? 4 : left >=
 template <int D>
 static const void* partial_kernel_ptr(int step) {
   switch (step) {
-    case 8: return (const void*)decode_partial_kernel_wide<D, 8, true>;
-    case 4: return (const void*)decode_partial_kernel<D, 4, true>;
-    case 2: return (const void*)decode_partial_kernel<D, 2, true>;
-    default: return (const void*)decode_partial_kernel<D, 1, true>;
+    case 8: return (const void*)decode_partial_kernel_wide<D, 8, true, false>;
+    case 4: return (const void*)decode_partial_kernel<D, 4, true, false>;
+    case 2: return (const void*)decode_partial_kernel<D, 2, true, false>;
+    default: return (const void*)decode_partial_kernel<D, 1, true, false>;
   }
 }
 
@@ -770,25 +797,25 @@ int partial_waves_per_cu(int head_dim, int group) {
   return n;
 }
 
+template <int D, int G, bool APPEND, bool DIRECT>
+static void launch_partial_i(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
+                             void* out, float scale_log2, int32_t g_first, const BatchArgs& a, hipStream_t stream) {
+  const unsigned grid = (unsigned)(a.waves_per_head * pv.n_kv_heads);
+  if constexpr (G == 8)
+    hipLaunchKernelGGL((decode_partial_kernel_wide<D, G, APPEND, DIRECT>), dim3(grid), dim3(64), 0, stream, pv,
+                       (const uint16_t*)q, (const uint4*)k_new, (const uint4*)v_new, ws, (uint16_t*)out, scale_log2, g_first, a);
+  else
+    hipLaunchKernelGGL((decode_partial_kernel<D, G, APPEND, DIRECT>), dim3(grid), dim3(64), 0, stream, pv,
+                       (const uint16_t*)q, (const uint4*)k_new, (const uint4*)v_new, ws, (uint16_t*)out, scale_log2, g_first, a);
+}
+
 template <int D, int G>
 static void launch_partial_t(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
                              void* out, float scale_log2, int32_t g_first, const BatchArgs& a, hipStream_t stream) {
-  const unsigned grid = (unsigned)(a.waves_per_head * pv.n_kv_heads);
-  if constexpr (G == 8) {
-    if (k_new)
-      hipLaunchKernelGGL((decode_partial_kernel_wide<D, G, true>), dim3(grid), dim3(64), 0, stream, pv, (const uint16_t*)q,
-                         (const uint4*)k_new, (const uint4*)v_new, ws, (uint16_t*)out, scale_log2, g_first, a);
-    else
-      hipLaunchKernelGGL((decode_partial_kernel_wide<D, G, false>), dim3(grid), dim3(64), 0, stream, pv, (const uint16_t*)q,
-                         nullptr, nullptr, ws, (uint16_t*)out, scale_log2, g_first, a);
-  } else {
-    if (k_new)
-      hipLaunchKernelGGL((decode_partial_kernel<D, G, true>), dim3(grid), dim3(64), 0, stream, pv, (const uint16_t*)q,
-                         (const uint4*)k_new, (const uint4*)v_new, ws, (uint16_t*)out, scale_log2, g_first, a);
-    else
-      hipLaunchKernelGGL((decode_partial_kernel<D, G, false>), dim3(grid), dim3(64), 0, stream, pv, (const uint16_t*)q,
-                         nullptr, nullptr, ws, (uint16_t*)out, scale_log2, g_first, a);
-  }
+  if (k_new && pv.vbase) launch_partial_i<D, G, true, true>(pv, q, k_new, v_new, ws, out, scale_log2, g_first, a, stream);
+  else if (k_new) launch_partial_i<D, G, true, false>(pv, q, k_new, v_new, ws, out, scale_log2, g_first, a, stream);
+  else if (pv.vbase) launch_partial_i<D, G, false, true>(pv, q, nullptr, nullptr, ws, out, scale_log2, g_first, a, stream);
+  else launch_partial_i<D, G, false, false>(pv, q, nullptr, nullptr, ws, out, scale_log2, g_first, a, stream);
 }
 
 // a group size that is not 8, 4, 2 or 1 is covered by several launches over the same K/V
@@ -848,10 +875,10 @@ int launch_read(const void* src, int64_t bytes, uint32_t* sink, hipStream_t stre
 int launch_kv_stream(const PoolView& pv, uint32_t* sink, const BatchArgs& a, hipStream_t stream) {
   const unsigned grid = (unsigned)(a.waves_per_head * pv.n_kv_heads);
   if (a.n_req <= 0 || grid == 0) return 0;
-  if (pv.head_dim == 128)
-    hipLaunchKernelGGL(kv_stream_kernel<128>, dim3(grid), dim3(64), 0, stream, pv, sink, a);
-  else
-    hipLaunchKernelGGL(kv_stream_kernel<64>, dim3(grid), dim3(64), 0, stream, pv, sink, a);
+  if (pv.head_dim == 128 && pv.vbase) hipLaunchKernelGGL((kv_stream_kernel<128, true>), dim3(grid), dim3(64), 0, stream, pv, sink, a);
+  else if (pv.head_dim == 128) hipLaunchKernelGGL((kv_stream_kernel<128, false>), dim3(grid), dim3(64), 0, stream, pv, sink, a);
+  else if (pv.vbase) hipLaunchKernelGGL((kv_stream_kernel<64, true>), dim3(grid), dim3(64), 0, stream, pv, sink, a);
+  else hipLaunchKernelGGL((kv_stream_kernel<64, false>), dim3(grid), dim3(64), 0, stream, pv, sink, a);
   ELLM_HIP_CHECK_LAUNCH();
   return 0;
 }

@@ -19,6 +19,8 @@ constexpr size_t STATIC_WS_BYTES = 16u << 20;   // the fixed workspace of the en
 struct PoolView {
   char* base;                 // device pool
   const int32_t* table;       // device mirror of the chunk tables, [max_tensors][max_slots]
+  const uint64_t* vbase;      // NULL: kernels go through the table. Else: per tensor, the start of its virtual
+                              // address range, into which the driver has mapped its chunks; kernels read that
   uint32_t chunk_bytes;
   int32_t tokens_per_chunk;
   int32_t tiles_per_chunk;    // ceil(tokens_per_chunk / TILE_TOKENS); a tile never straddles a chunk

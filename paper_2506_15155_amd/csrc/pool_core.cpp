@@ -37,6 +37,7 @@ void PoolCore::set_entry(int32_t id, int32_t slot, int32_t value) {
   if (table_[flat] != value) {
     table_[flat] = value;
     dirty_.push_back(flat);
+    if (map_log_) map_dirty_.push_back(flat);
     row_version_[id]++;
   }
 }
@@ -46,6 +47,14 @@ std::vector<int64_t> PoolCore::take_dirty() {
   dirty_.erase(std::unique(dirty_.begin(), dirty_.end()), dirty_.end());
   std::vector<int64_t> out;
   out.swap(dirty_);
+  return out;
+}
+
+std::vector<int64_t> PoolCore::take_map_changes() {
+  std::sort(map_dirty_.begin(), map_dirty_.end());
+  map_dirty_.erase(std::unique(map_dirty_.begin(), map_dirty_.end()), map_dirty_.end());
+  std::vector<int64_t> out;
+  out.swap(map_dirty_);
   return out;
 }
 

@@ -102,6 +102,10 @@ class PoolCore {
   // table entries changed since the last take_dirty(): flat index into table()
   std::vector<int64_t> take_dirty();
   bool has_dirty() const { return !dirty_.empty(); }
+  // a second, independent record of changed entries for a consumer that mirrors the table elsewhere
+  // (driver mappings); off unless asked for
+  void log_map_changes(bool on) { map_log_ = on; }
+  std::vector<int64_t> take_map_changes();
 
   const std::vector<uint8_t>& owner() const { return owner_; }
   const std::vector<uint8_t>& state() const { return state_; }
@@ -128,7 +132,8 @@ class PoolCore {
   std::set<std::pair<int32_t, int32_t>> released_;   // (leading mapped slots, handle) of every released tensor
   std::vector<TensorRec> t_;
   std::vector<int32_t> table_;     // max_tensors x max_slots, row-major, ENTRY_UNMAPPED where empty
-  std::vector<int64_t> dirty_;
+  std::vector<int64_t> dirty_, map_dirty_;
+  bool map_log_ = false;
   std::vector<uint32_t> row_version_;
   int32_t logical_host_ = 0;
   struct Slo {

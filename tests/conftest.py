@@ -27,3 +27,13 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+@pytest.fixture(params=["table", "driver"])
+def pool_mode(request):
+    """Runs a GPU test twice: on a plain pool read through the software table, and on a driver-mapped
+    pool whose kernels read each tensor as a contiguous virtual address range (the paper's mechanism)."""
+    from tests import gpu_harness as H
+    H.POOL_MODE = request.param
+    yield request.param
+    H.POOL_MODE = "table"

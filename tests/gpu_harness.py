@@ -12,6 +12,13 @@ from oracle.model import OraclePool
 MAX_ABS, MEAN_ABS = 2e-2, 2e-3     # bf16 output vs fp64 oracle (tolerances of the benchmark spec)
 POISON = 0x7FC0                    # bf16 NaN: any stray read of a non-KV byte turns the output NaN
 
+# How the pools of a test are built unless the test says otherwise: "table" = one plain device
+# buffer of the caller's, chunks found through the software table; "driver" = the paper's own
+# mechanism, ELLM_POOL_DRIVER_MAPPED: chunks created by the library and mapped by the driver into
+# each tensor's address range, which the kernels read directly. The `pool_mode` fixture in
+# conftest.py runs a test once in each.
+POOL_MODE = "table"
+
 
 def dev_bits(a: np.ndarray) -> torch.Tensor:
     """uint16 bit patterns -> device int16 tensor (same bits)."""
@@ -30,11 +37,15 @@ def out_f64(t: torch.Tensor) -> np.ndarray:
 
 class Both:
     def __init__(self, cfg: W.Config, owner=None, oracle=True, keep_twin=False, poison=True, max_tensors=None,
-                 driver_mapped=False):
+                 driver_mapped=False, mode=None):
         self.cfg = cfg
         nbytes = cfg.n_chunks * cfg.chunk_bytes
         self.vmm_base = None
-        if driver_mapped:
+        self.mode = mode or POOL_MODE
+        self.dev = None
+        if self.mode == "driver" and not driver_mapped:
+            pass                                   # the library creates the memory: see below
+        elif driver_mapped:
             # every chunk a physical allocation of its own, mapped into one virtual range by the driver
             self.vmm_base, got = E.ellm_debug_vmm_buffer_create(cfg.chunk_bytes, cfg.n_chunks, 5, POISON if poison else 0)
             assert got == nbytes
@@ -50,8 +61,23 @@ class Both:
             self.host = torch.empty(cfg.host_slots * cfg.chunk_bytes, dtype=torch.uint8, pin_memory=True)
             self.host.zero_()
         mt = max_tensors or cfg.batch
-        self.pool = E.ellm_pool_create(self.dev, self.host, cfg.chunk_bytes, cfg.n_q_heads, cfg.n_kv_heads,
-                                       cfg.head_dim, mt, cfg.max_slots, owner, device_bytes=nbytes)
+        self.window = None
+        if self.dev is None:
+            self.pool = E.ellm_pool_create(None, self.host, cfg.chunk_bytes, cfg.n_q_heads, cfg.n_kv_heads,
+                                           cfg.head_dim, mt, cfg.max_slots, owner, flags=E.ELLM_POOL_DRIVER_MAPPED,
+                                           device_bytes=nbytes)
+            self.window = E.ellm_pool_get_device_base(self.pool)      # every chunk, in id order
+            fill = torch.empty(min(nbytes, 64 << 20), dtype=torch.uint8, device="cuda")
+            if poison:
+                fill.view(torch.int16).fill_(POISON)
+            else:
+                fill.zero_()
+            for off in range(0, nbytes, fill.numel()):
+                E.ellm_debug_copy(self.window + off, fill, min(fill.numel(), nbytes - off))
+            torch.cuda.synchronize()
+        else:
+            self.pool = E.ellm_pool_create(self.dev, self.host, cfg.chunk_bytes, cfg.n_q_heads, cfg.n_kv_heads,
+                                           cfg.head_dim, mt, cfg.max_slots, owner, device_bytes=nbytes)
         self.orc = None
         if oracle:
             self.orc = OraclePool(cfg.n_chunks, cfg.chunk_bytes, cfg.host_slots, cfg.n_q_heads, cfg.n_kv_heads,
@@ -144,9 +170,10 @@ class Both:
 
     def chunk_bytes_dev(self, c) -> np.ndarray:
         cb = self.cfg.chunk_bytes
-        if self.vmm_base is not None:
+        base = self.vmm_base if self.vmm_base is not None else self.window
+        if base is not None:
             tmp = torch.empty(cb, dtype=torch.uint8, device="cuda")
-            E.ellm_debug_copy(tmp, self.vmm_base + c * cb, cb)
+            E.ellm_debug_copy(tmp, base + c * cb, cb)
             torch.cuda.synchronize()
             return tmp.cpu().numpy()
         return self.dev[c * cb:(c + 1) * cb].cpu().numpy()

@@ -1,0 +1,85 @@
+"""The paper's own mapping mechanism as a pool mode (Sec. 2.1.1, Sec. 3.2): chunks mapped by the
+driver into each tensor's reserved address range, kernels that read the range with no table. The
+parity tests of the other files run in this mode too (the `pool_mode` fixture); here: the two kinds
+of kernels against each other on one pool, the driver mappings followed call by call, and what
+the mode costs on the host."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2506_15155_amd as E
+import workloads as W
+from tests import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def test_direct_kernels_equal_table_kernels_on_one_pool():
+    cfg = W.scaled(W.CONFIGS["llama8b"], batch=14, n_chunks=150, len_lo=64, len_hi=5000, lognormal_median=1200,
+                   host_slots=24)
+    st = W.draw_step(cfg, seed=83)
+    B = H.Both(cfg, mode="driver")
+    P = H.Both(cfg, oracle=False, mode="table")
+    ids = H.load_step(B, st)
+    assert H.load_step(P, st) == ids
+    n_mapped = sum(len(c) for c in st.placement.chunk_ids)
+    stats = E.ellm_pool_get_mapping_stats(B.pool)
+    assert stats["maps"] == n_mapped and stats["unmaps"] == 0 and stats["us_map"] > 0
+    assert E.ellm_pool_get_mapping_stats(P.pool) == {"maps": 0, "us_map": 0.0, "unmaps": 0, "us_unmap": 0.0}
+    # fused step through the tensors' own address ranges, against the oracle and the plain pool
+    rc, out, ref = B.append_decode(ids, st.k_new, st.v_new, st.q)
+    assert rc == 0
+    H.check_close(out, ref, "driver-mapped, direct kernels")
+    rcp, outp, _ = P.append_decode(ids, st.k_new, st.v_new, st.q)
+    assert rcp == 0 and torch.equal(out, outp)
+    B.compare_state()
+    # the same pool read through the table instead: same bits; and the appended rows are where both views agree
+    E.ellm_debug_set_table_kernels(B.pool, 1)
+    rc, via_table = B.decode(ids, st.q)
+    assert rc == 0 and torch.equal(via_table, out)
+    E.ellm_debug_set_table_kernels(B.pool, 0)
+    rc, direct = B.decode(ids, st.q)
+    assert rc == 0 and torch.equal(direct, out)
+    for b in (0, 5, 13):
+        for c in E.ellm_tensor_get_table(B.pool, ids[b])[0]:
+            if c >= 0:
+                assert np.array_equal(B.chunk_bytes_dev(int(c)), P.chunk_bytes_dev(int(c)))
+    assert E.ellm_debug_set_table_kernels(P.pool, 1, check=False) == E.ERR.INVALID
+    # offload takes the chunks out of the tensor's range, fetch maps other chunks there
+    t = ids[5]
+    n = int((E.ellm_tensor_get_table(B.pool, t)[0] >= 0).sum())
+    assert B.offload(t, 0, n) == 0
+    s1 = E.ellm_pool_get_mapping_stats(B.pool)
+    assert s1["unmaps"] == n and s1["maps"] == n_mapped
+    q = H.dev_bits(st.q)
+    assert E.ellm_decode_attention(B.pool, ids, q, torch.empty_like(q), check=False) == E.ERR.NOT_RESIDENT
+    _, state, _, _ = E.ellm_pool_get_owner_state(B.pool)
+    free = [c for c in range(cfg.n_chunks - 1, -1, -1) if state[c] == 0][:n]
+    assert B.fetch(t, 0, n, free) == 0
+    s2 = E.ellm_pool_get_mapping_stats(B.pool)
+    assert s2["maps"] == n_mapped + n and s2["unmaps"] == n
+    rc, back = B.decode(ids, st.q)
+    assert rc == 0 and torch.equal(back, out)
+    # release keeps the mapping (Sec. 2.1.2): no driver call; destroy gives everything back
+    assert B.release(ids[0]) == 0
+    assert E.ellm_pool_get_mapping_stats(B.pool)["unmaps"] == n
+    n0 = int((E.ellm_tensor_get_table(B.pool, ids[0])[0] >= 0).sum())
+    rc, t_new = B.acquire(10, cfg.max_tokens)
+    assert rc == 0 and t_new == ids[0] and E.ellm_pool_get_mapping_stats(B.pool)["maps"] == n_mapped + n
+    assert B.both("destroy", lambda: E.ellm_tensor_destroy(B.pool, t_new, check=False), lambda: B.orc.tensor_destroy(t_new)) == 0
+    B.ids.remove(t_new)
+    assert E.ellm_pool_get_mapping_stats(B.pool)["unmaps"] == n + n0
+    B.compare_state()
+    rc, rest = B.decode(ids[1:], st.q[1:])          # another batch, another partition: tolerance, not bits
+    assert rc == 0
+    H.check_close(rest, ref[1:], "after the turnover")
+    print("driver calls:", E.ellm_pool_get_mapping_stats(B.pool))
+    B.close()
+    P.close()
+
+
+def test_driver_mapped_pool_rejects_what_the_driver_cannot_map():
+    # 5 kv heads of 64: a 16-token chunk is 20480 bytes ... times 1.5 = 30720, not a whole number of 4 KiB pages
+    rc, _ = E.ellm_pool_create(None, None, 30720, 5, 5, 64, 2, 2, flags=E.ELLM_POOL_DRIVER_MAPPED, device_bytes=4 * 30720,
+                               check=False)
+    assert rc == E.ERR.INVALID and "granularity" in E.ellm_last_error()

@@ -13,7 +13,7 @@ from tests import gpu_harness as H
 pytestmark = pytest.mark.gpu
 
 
-def test_llama8b_full_every_output():
+def test_llama8b_full_every_output(pool_mode):
     """The 8B-shaped configuration at its full size: all 64 requests, every output element."""
     cfg = W.CONFIGS["llama8b"]
     st = W.draw_step(cfg)
@@ -133,7 +133,7 @@ def test_long70b_full_every_request():
     run_sampled(W.CONFIGS["long70b"], 16)
 
 
-def test_elastic_ten_steps_twin_run():
+def test_elastic_ten_steps_twin_run(pool_mode):
     """Ten decode steps with the pool reshaped before each: 30 % of the activation region handed
     to the KV side, all chunks of 25 % of the requests offloaded to pinned host and fetched back
     into whatever chunks the pool picks, then map-ahead, append and decode. A twin pool takes the
@@ -142,7 +142,7 @@ def test_elastic_ten_steps_twin_run():
     cfg = W.CONFIGS["elastic"]
     st = W.draw_step(cfg)
     A = H.Both(cfg, owner=st.placement.owner)
-    T = H.Both(cfg, owner=st.placement.owner, oracle=False)
+    T = H.Both(cfg, owner=st.placement.owner, oracle=False, mode="table")     # the twin is always a plain pool
     ids = H.load_step(A, st)
     idt = H.load_step(T, st)
     assert ids == idt

@@ -283,6 +283,13 @@ def test_pool_create_rejects_bad_geometry():
     bad = dict(ok)
     bad["flags"] = 0
     assert E.ellm_pool_create(**bad, check=False)[0] == E.ERR.INVALID
+    # a driver-mapped pool brings its own memory, and is never metadata-only (checked before any device call)
+    bad = dict(ok)
+    bad["flags"] = E.ELLM_POOL_DRIVER_MAPPED | E.ELLM_POOL_METADATA_ONLY
+    assert E.ellm_pool_create(**bad, check=False)[0] == E.ERR.INVALID
+    bad = dict(ok)
+    bad["flags"], bad["device_buf"] = E.ELLM_POOL_DRIVER_MAPPED, DUMMY
+    assert E.ellm_pool_create(**bad, check=False)[0] == E.ERR.INVALID
 
 
 def test_driver_mapped_buffer_rejects_bad_arguments_before_any_device_call():
