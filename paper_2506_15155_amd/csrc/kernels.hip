@@ -2,8 +2,10 @@
 //
 // Decode attention is a streaming read of every cached K and V row once per step (the paper calls
 // auto-regressive generation memory-bound, Introduction and Sec. 2.2.1), so the kernels are built
-// around 128-bit coalesced loads from the scattered chunks and keep all arithmetic on ordinary
-// vector lanes; there is no dense contraction here that would pay for the matrix cores.
+// around 128-bit coalesced loads from the scattered chunks. With one query token per request the
+// arithmetic is G (q heads per kv head) flops per byte read: for one or two heads it stays on
+// ordinary vector lanes; for four and eight, where the lanes of a wave could no longer keep up with
+// the bytes, the two small products of a tile run on the matrix cores.
 //
 // Per-launch metadata (which tensors, their lengths, how the tiles are dealt out) is passed by value
 // in the kernel arguments, so a launch needs no host-to-device copy and no staging buffer whose
@@ -81,6 +83,8 @@ __device__ __forceinline__ float wave_sum(float v) {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef short __attribute__((ext_vector_type(4))) bf16x4_bits_t;     // four bf16 values as the matrix instructions take them
+typedef float __attribute__((ext_vector_type(4))) f32x4_t;
 
 // c + a.lo * b.lo + a.hi * b.hi on packed bf16 pairs, fp32 accumulate
 __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
@@ -275,6 +279,19 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
   constexpr int NL = 64 / RPW;           // wave-wide loads per 64-row tile and plane
   constexpr int ROWB = D * 2;            // bytes per row
   constexpr int QR = D / 32;             // registers holding one head's query (16 lanes x 1 pair each)
+  // With 4 or 8 q heads per kv head the two products of a tile are small dense contractions, [G x D] by
+  // [D x 64 tokens] and [G x 64 tokens] by [64 x D], and on ordinary lanes, with one wave per SIMD, the
+  // 8-head instance's arithmetic takes longer than the tile's bytes take to arrive (70B-shaped layer:
+  // 1.07 ms, against 0.86 ms with either product switched off, which is also what a kernel that only
+  // reads the same tiles takes). Those instances form both products on the matrix cores, 4 heads by 4
+  // tokens (or dims) by 4 at a time; the 1- and 2-head instances, which are not short of lane time,
+  // keep the dot products on ordinary lanes. The softmax is on ordinary lanes in all of them.
+  constexpr bool MFMA_QK = (G % 4 == 0);
+  // For the weighted sum of V a lane then owns NL consecutive rows of the tile instead of every RPW-th
+  // one, so that four of its rows at a time are the contraction index of one product; the tile's
+  // weights reach it through a small transposed copy in LDS.
+  constexpr bool MFMA_PV = (G % 4 == 0);
+  __shared__ __attribute__((aligned(16))) uint16_t sm_p[MFMA_PV ? G * 64 : 8];   // weights [head][token], bf16
   __shared__ __attribute__((aligned(16))) char sm_k[64 * ROWB];      // the K tile being scored
 
   const int lane = threadIdx.x;
@@ -297,9 +314,11 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
     __builtin_amdgcn_global_load_lds((global_cptr_t)((base) + off_),                                \
                                      (lds_ptr_t)(sm_k + u * (RPW * ROWB)), 16, 0, CPOL_NT);         \
   }
+// V: tile row that lane (rg, sub) holds in register u of a tile
+#define ELLM_VROW(u) (MFMA_PV ? NL * rg + (u) : RPW * (u) + rg)
 #define ELLM_LOAD_TILE(dst, base, nvalid)                                                           \
   _Pragma("unroll") for (int u = 0; u < NL; u++) {                                                  \
-    const uint32_t off_ = (uint32_t)min(RPW * u + rg, (nvalid) - 1) * ROWB + sub * 16;              \
+    const uint32_t off_ = (uint32_t)min(ELLM_VROW(u), (nvalid) - 1) * ROWB + sub * 16;              \
     dst[u] = load_stream16((base) + off_);                                                          \
   }
 // Move the cursor to the next tile of the share and compute its address and valid rows. `left`
@@ -329,21 +348,51 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
 #define ELLM_TILE_SCORES(nvalid)                                                                    \
   float s[G];                                                                                       \
   uint32_t pu[G];                                                                                   \
+  bf16x4_bits_t wa[MFMA_PV ? NL / 4 : 1];                                                           \
   {                                                                                                 \
-    _Pragma("unroll") for (int i = 0; i < G; i++) s[i] = 0.f;                                       \
-    static_for<0, LPR>([&](auto jc) {                                                               \
-      constexpr int j = decltype(jc)::value;                                                        \
-      const uint4 kp = *reinterpret_cast<const uint4*>(sm_k + lane * ROWB + ((j ^ kswz) * 16));     \
-      _Pragma("unroll") for (int i = 0; i < G; i++)                                                 \
-        s[i] = dot2_bf16_rowlane<4 * (j % 4) + 0>(qreg[i][j / 4], kp.x, s[i]);                      \
-      _Pragma("unroll") for (int i = 0; i < G; i++)                                                 \
-        s[i] = dot2_bf16_rowlane<4 * (j % 4) + 1>(qreg[i][j / 4], kp.y, s[i]);                      \
-      _Pragma("unroll") for (int i = 0; i < G; i++)                                                 \
-        s[i] = dot2_bf16_rowlane<4 * (j % 4) + 2>(qreg[i][j / 4], kp.z, s[i]);                      \
-      _Pragma("unroll") for (int i = 0; i < G; i++)                                                 \
-        s[i] = dot2_bf16_rowlane<4 * (j % 4) + 3>(qreg[i][j / 4], kp.w, s[i]);                      \
-    });                                                                                             \
-    _Pragma("unroll") for (int i = 0; i < G; i++) settle(s[i]);                                     \
+    if constexpr (MFMA_QK) {                                                                        \
+      /* v_mfma_f32_4x4x4 (16 blocks of 4 lanes): block b computes D[i][j] = sum_k A[i][k] B[k][j] */ \
+      /* with A[i][.] in lane 4b + i, B[.][j] in lane 4b + j and D[i][j] in register i of lane    */ \
+      /* 4b + j. B = this lane's K row, four dims at a time, so column j of block b is token      */ \
+      /* 4b + j = lane; A = the query rows of four heads, taken by all blocks from the block that */ \
+      /* holds them (lanes 0..3: heads 0..3, lanes 4..7: heads 4..7). D: register i = score of    */ \
+      /* head i for this lane's token, the layout the softmax below expects.                      */ \
+      f32x4_t sacc[G / 4];                                                                          \
+      _Pragma("unroll") for (int h = 0; h < G / 4; h++) sacc[h] = f32x4_t{0.f, 0.f, 0.f, 0.f};      \
+      static_for<0, LPR>([&](auto jc) {                                                             \
+        constexpr int j = decltype(jc)::value;                                                      \
+        const uint4 kp = *reinterpret_cast<const uint4*>(sm_k + lane * ROWB + ((j ^ kswz) * 16));   \
+        const bf16x4_bits_t k0 = __builtin_bit_cast(bf16x4_bits_t, make_uint2(kp.x, kp.y));         \
+        const bf16x4_bits_t k1 = __builtin_bit_cast(bf16x4_bits_t, make_uint2(kp.z, kp.w));         \
+        static_for<0, G / 4>([&](auto hc) {                                                         \
+          constexpr int h = decltype(hc)::value;                                                    \
+          sacc[h] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(qa[2 * j], k0, sacc[h], 4, h, 0);        \
+        });                                                                                         \
+        static_for<0, G / 4>([&](auto hc) {                                                         \
+          constexpr int h = decltype(hc)::value;                                                    \
+          sacc[h] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(qa[2 * j + 1], k1, sacc[h], 4, h, 0);    \
+        });                                                                                         \
+      });                                                                                           \
+      _Pragma("unroll") for (int h = 0; h < G / 4; h++) {                                           \
+        s[4 * h + 0] = sacc[h][0]; s[4 * h + 1] = sacc[h][1];                                       \
+        s[4 * h + 2] = sacc[h][2]; s[4 * h + 3] = sacc[h][3];                                       \
+      }                                                                                             \
+    } else {                                                                                        \
+      _Pragma("unroll") for (int i = 0; i < G; i++) s[i] = 0.f;                                     \
+      static_for<0, LPR>([&](auto jc) {                                                             \
+        constexpr int j = decltype(jc)::value;                                                      \
+        const uint4 kp = *reinterpret_cast<const uint4*>(sm_k + lane * ROWB + ((j ^ kswz) * 16));   \
+        _Pragma("unroll") for (int i = 0; i < G; i++)                                               \
+          s[i] = dot2_bf16_rowlane<4 * (j % 4) + 0>(qreg[i][j / 4], kp.x, s[i]);                    \
+        _Pragma("unroll") for (int i = 0; i < G; i++)                                               \
+          s[i] = dot2_bf16_rowlane<4 * (j % 4) + 1>(qreg[i][j / 4], kp.y, s[i]);                    \
+        _Pragma("unroll") for (int i = 0; i < G; i++)                                               \
+          s[i] = dot2_bf16_rowlane<4 * (j % 4) + 2>(qreg[i][j / 4], kp.z, s[i]);                    \
+        _Pragma("unroll") for (int i = 0; i < G; i++)                                               \
+          s[i] = dot2_bf16_rowlane<4 * (j % 4) + 3>(qreg[i][j / 4], kp.w, s[i]);                    \
+      });                                                                                           \
+      _Pragma("unroll") for (int i = 0; i < G; i++) settle(s[i]);                                   \
+    }                                                                                               \
     _Pragma("unroll") for (int i = 0; i < G; i++) {                                                 \
       const float sc = lane < (nvalid) ? s[i] * scale_log2 : -INFINITY;                             \
       /* the running maximum is the same in every lane: it lives in a scalar register */           \
@@ -353,13 +402,50 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
       pu[i] = __float_as_uint(fast_exp2(sc - mn));                                                  \
       pu[i] = (pu[i] + 0x7fffu + ((pu[i] >> 16) & 1u)) & 0xffff0000u; /* nearest even */            \
       l[i] = l[i] * alpha + __uint_as_float(pu[i]);                                                 \
-      _Pragma("unroll") for (int e = 0; e < 8; e++) acc[i][e] *= alpha;                             \
+      if constexpr (MFMA_PV) { _Pragma("unroll") for (int e = 0; e < 8; e++) accv[i / 4][e][i % 4] *= alpha; } \
+      else { _Pragma("unroll") for (int e = 0; e < 8; e++) acc[i][e] *= alpha; }                    \
+    }                                                                                               \
+    if constexpr (MFMA_PV) {                                                                        \
+      /* the tile's weights through LDS, transposed to [head][token], so that lane (rg, sub) gets  */ \
+      /* the weights of its own NL consecutive rows for head sub % G. Done here, while no          */ \
+      /* load-to-LDS is pending, so that these LDS reads do not have to wait for one.              */ \
+      _Pragma("unroll") for (int i = 0; i < G; i++) sm_p[i * 64 + lane] = (uint16_t)(pu[i] >> 16);  \
+      __builtin_amdgcn_wave_barrier();                                                              \
+      const uint2* src_ = reinterpret_cast<const uint2*>(sm_p + (sub % G) * 64 + NL * rg);          \
+      _Pragma("unroll") for (int mm = 0; mm < NL / 4; mm++) wa[mm] = __builtin_bit_cast(bf16x4_bits_t, src_[mm]); \
+      __builtin_amdgcn_wave_barrier();                                                              \
     }                                                                                               \
   }
 // weighted V: the PV lane (rg, sub) fetches the weights of its rows RPW*u + rg from the lanes that
 // own those tokens (a cross-lane read, no LDS memory), packs two of them into one register, and
 // adds two tokens per dot2
 #define ELLM_TILE_PV(VR)                                                                            \
+  if constexpr (MFMA_PV) {                                                                          \
+    /* wa[mm] (set up with the scores): for head sub % G, the weights of rows 4 mm .. 4 mm + 3 of  */ \
+    /* this lane's NL rows = one A operand. A[i][k] is looked up in lane 4b + i of the block named */ \
+    /* by abid within each group of LPR / 4 blocks (the lanes of one row-group): block 0 holds     */ \
+    /* heads 0..3, block 1 heads 4..7.                                                             */ \
+    /* B[k][j] = four rows' values of one dim of lane 4b + j; D[i][j] = head i, that dim.          */ \
+    constexpr int CB = (LPR == 16) ? 2 : 1;     /* log2 of the blocks that share one A */          \
+    static_for<0, NL / 4>([&](auto mc) {                                                            \
+      constexpr int mm = decltype(mc)::value;                                                       \
+      const uint4 r0 = VR[4 * mm], r1 = VR[4 * mm + 1], r2 = VR[4 * mm + 2], r3 = VR[4 * mm + 3];   \
+      static_for<0, 8>([&](auto ec) {                                                               \
+        constexpr int e = decltype(ec)::value;                                                      \
+        constexpr uint32_t sel = (e % 2) ? 0x07060302u : 0x05040100u;                               \
+        const uint32_t w0 = e / 2 == 0 ? r0.x : e / 2 == 1 ? r0.y : e / 2 == 2 ? r0.z : r0.w;       \
+        const uint32_t w1 = e / 2 == 0 ? r1.x : e / 2 == 1 ? r1.y : e / 2 == 2 ? r1.z : r1.w;       \
+        const uint32_t w2 = e / 2 == 0 ? r2.x : e / 2 == 1 ? r2.y : e / 2 == 2 ? r2.z : r2.w;       \
+        const uint32_t w3 = e / 2 == 0 ? r3.x : e / 2 == 1 ? r3.y : e / 2 == 2 ? r3.z : r3.w;       \
+        const bf16x4_bits_t vb = __builtin_bit_cast(                                                \
+            bf16x4_bits_t, make_uint2(__builtin_amdgcn_perm(w1, w0, sel), __builtin_amdgcn_perm(w3, w2, sel))); \
+        static_for<0, G / 4>([&](auto hc) {                                                         \
+          constexpr int h = decltype(hc)::value;                                                    \
+          accv[h][e] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(wa[mm], vb, accv[h][e], CB, h, 0);    \
+        });                                                                                         \
+      });                                                                                           \
+    });                                                                                             \
+  } else {                                                                                          \
   _Pragma("unroll") for (int i = 0; i < G; i++) {                                                   \
     uint32_t pp[NL / 2];                                                                            \
     _Pragma("unroll") for (int v = 0; v < NL / 2; v++) {                                            \
@@ -378,11 +464,22 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
       acc[i][6] = dot2_bf16(__builtin_amdgcn_perm(Bv.w, A.w, 0x05040100u), pp[v], acc[i][6]);       \
       acc[i][7] = dot2_bf16(__builtin_amdgcn_perm(Bv.w, A.w, 0x07060302u), pp[v], acc[i][7]);       \
     }                                                                                               \
+  }                                                                                                 \
   }
 
-// query of request b_: lane keeps pair (16 c + lane % 16) of each head in qreg[.][c]
+// query of request b_. Lanes: lane keeps pair (16 c + lane % 16) of each head in qreg[.][c]. Matrix
+// cores: lane i < G keeps the whole row of head i, four dims per entry of qa (the other lanes' copies
+// are never looked at; they read the last head's row, which is in bounds)
 #define ELLM_LOAD_Q(b_)                                                                             \
-  {                                                                                                 \
+  if constexpr (MFMA_QK) {                                                                          \
+    const uint4* qsrc = reinterpret_cast<const uint4*>(                                             \
+        q + ((int64_t)(a.q_row0 + (b_)) * pv.n_q_heads + hq0 + min(lane, G - 1)) * D);              \
+    _Pragma("unroll") for (int c = 0; c < LPR; c++) {                                               \
+      const uint4 t_ = qsrc[c];                                                                     \
+      qa[2 * c] = __builtin_bit_cast(bf16x4_bits_t, make_uint2(t_.x, t_.y));                        \
+      qa[2 * c + 1] = __builtin_bit_cast(bf16x4_bits_t, make_uint2(t_.z, t_.w));                    \
+    }                                                                                               \
+  } else {                                                                                          \
     const uint32_t* qsrc =                                                                          \
         reinterpret_cast<const uint32_t*>(q + ((int64_t)(a.q_row0 + (b_)) * pv.n_q_heads + hq0) * D); \
     _Pragma("unroll") for (int i = 0; i < G; i++)                                                   \
@@ -421,18 +518,24 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
     // cursor's request, which runs one tile ahead)
     int32_t b = cb, j = sh.w - first.wave_first;
     int32_t b_np = first.n_part, b_p0 = first.part0, c_np = b_np, c_p0 = b_p0;
-    uint32_t qreg[G][QR];
+    uint32_t qreg[MFMA_QK ? 1 : G][QR];
+    bf16x4_bits_t qa[MFMA_QK ? 2 * LPR : 1];
     uint4 kn, vn;
     ELLM_LOAD_Q(b)
     ELLM_LOAD_NEW_ROW(b)
 
     float m[G], l[G], acc[G][8];
+    f32x4_t accv[MFMA_PV ? G / 4 : 1][8];      // matrix cores: accv[h][e][i] = head 4h + i, dim 8 sub + e
 #pragma unroll
     for (int i = 0; i < G; i++) {
       m[i] = NEG_BIG; l[i] = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; e++) acc[i][e] = 0.f;
     }
+#pragma unroll
+    for (int h = 0; h < (MFMA_PV ? G / 4 : 1); h++)
+#pragma unroll
+      for (int e = 0; e < 8; e++) accv[h][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     bool q_settled = false;
 
     for (int32_t it = 0; it < n_tiles; it++) {
@@ -458,7 +561,7 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
           *reinterpret_cast<uint4*>(dst + plane) = vn;
         }
       }
-      if (!q_settled) {
+      if (!MFMA_QK && !q_settled) {
 #pragma unroll
         for (int i = 0; i < G; i++)
 #pragma unroll
@@ -476,7 +579,7 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
       if (APPEND && last) {
 #pragma unroll
         for (int u = 0; u < NL; u++)
-          if (RPW * u + rg >= nv - 1) vr[u] = vn;
+          if (ELLM_VROW(u) >= nv - 1) vr[u] = vn;
       }
       if (more) {
         ELLM_LOAD_K_TILE(kb, nv_c)
@@ -487,6 +590,12 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
       if (last || !more) {
         // request b ends here, or the share does: write partial j of pair (b, g).
         // Every row-group holds the same dims for different tokens under one common maximum: add them up
+        if constexpr (MFMA_PV) {
+#pragma unroll
+          for (int i = 0; i < G; i++)
+#pragma unroll
+            for (int e = 0; e < 8; e++) acc[i][e] = accv[i / 4][e][i % 4];
+        }
 #pragma unroll
         for (int i = 0; i < G; i++) {
 #pragma unroll
@@ -547,6 +656,10 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
 #pragma unroll
             for (int e = 0; e < 8; e++) acc[i][e] = 0.f;
           }
+#pragma unroll
+          for (int h = 0; h < (MFMA_PV ? G / 4 : 1); h++)
+#pragma unroll
+            for (int e = 0; e < 8; e++) accv[h][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         }
       }
     }
@@ -554,6 +667,7 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
 #undef ELLM_LOAD_Q
 #undef ELLM_LOAD_NEW_ROW
 #undef ELLM_LOAD_TILE
+#undef ELLM_VROW
 #undef ELLM_LOAD_K_TILE
 #undef ELLM_NEXT_TILE
 #undef ELLM_TILE_SCORES
@@ -561,9 +675,10 @@ __device__ __forceinline__ void decode_partial_body(const PoolView& pv, const ui
 }
 
 // Launched with one wave per SIMD, so a wave may use the SIMD's whole register file. The instances
-// for up to 4 q heads per kv head fit the budget of two waves per SIMD with room to spare and keep
-// that cap (it is what their schedule was tuned under); the 8-head instance, whose accumulators
-// alone take 64 registers more, is compiled without it and does not spill.
+// for 1 and 2 q heads per kv head fit the budget of two waves per SIMD with room to spare and keep
+// that cap (it is what their schedule was tuned under); the 4- and 8-head instances, which keep the
+// whole query rows and the matrix-core accumulators in registers, are compiled without it and do
+// not spill.
 template <int D, int G, bool APPEND, bool DIRECT>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_partial_kernel(
     PoolView pv, const uint16_t* __restrict__ q, const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
@@ -782,7 +897,7 @@ template <int D>
 static const void* partial_kernel_ptr(int step) {
   switch (step) {
     case 8: return (const void*)decode_partial_kernel_wide<D, 8, true, false>;
-    case 4: return (const void*)decode_partial_kernel<D, 4, true, false>;
+    case 4: return (const void*)decode_partial_kernel_wide<D, 4, true, false>;
     case 2: return (const void*)decode_partial_kernel<D, 2, true, false>;
     default: return (const void*)decode_partial_kernel<D, 1, true, false>;
   }
@@ -801,7 +916,7 @@ template <int D, int G, bool APPEND, bool DIRECT>
 static void launch_partial_i(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
                              void* out, float scale_log2, int32_t g_first, const BatchArgs& a, hipStream_t stream) {
   const unsigned grid = (unsigned)(a.waves_per_head * pv.n_kv_heads);
-  if constexpr (G == 8)
+  if constexpr (G >= 4)
     hipLaunchKernelGGL((decode_partial_kernel_wide<D, G, APPEND, DIRECT>), dim3(grid), dim3(64), 0, stream, pv,
                        (const uint16_t*)q, (const uint4*)k_new, (const uint4*)v_new, ws, (uint16_t*)out, scale_log2, g_first, a);
   else
