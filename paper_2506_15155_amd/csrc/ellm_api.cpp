@@ -74,6 +74,12 @@ struct ellm_pool {
     int64_t done = 0;                  // highest seq the host has seen finished
   };
   Ring r_compute, r_in, r_out;
+  // Compute calls are numbered but not marked one by one: an event behind every kernel would cost the
+  // caller's stream a few microseconds each. A mark is recorded, on the stream of the latest compute
+  // call, only when a copy (or an unmap) has to wait for a compute call no mark covers yet; mark i
+  // (event r_compute.ev[i % EV_RING]) covers every compute call up to compute_covers[i % EV_RING].
+  std::vector<int64_t> compute_covers;
+  int64_t compute_marks = 0, compute_covered = 0;
   std::vector<int64_t> chunk_compute, chunk_in, chunk_out;   // per chunk: seq of the last call of a kind, 0 = none
   std::vector<int64_t> host_in, host_out;                    // per host slot: last fetch that read it, last offload that wrote it
   // what each waiting stream already waits for, per ring (a stream is in order, so waiting for seq n covers all before)
@@ -210,6 +216,7 @@ int ensure_device(ellm_pool* p) {
     p->host_in.assign(p->geom.n_host_slots, 0);
     p->host_out.assign(p->geom.n_host_slots, 0);
     p->copy_seen.assign(p->geom.max_tensors, ellm_pool::CopySeen());
+    p->compute_covers.assign(ellm_pool::EV_RING, 0);
     for (ellm_pool::Ring* r : {&p->r_compute, &p->r_in, &p->r_out})
       for (int i = 0; i < ellm_pool::EV_RING; i++) {
         hipEvent_t e;
@@ -286,6 +293,55 @@ int host_wait(ellm_pool::Ring& r, int64_t need) {
   return ELLM_OK;
 }
 
+// The event behind compute call `need` of this pool, recorded now if no mark covers that call yet
+// (then it covers everything enqueued so far on the compute stream, which is in order). *covers
+// receives the newest call the event stands behind.
+int compute_mark(ellm_pool* p, int64_t need, hipEvent_t* ev, int64_t* covers) {
+  ellm_pool::Ring& r = p->r_compute;
+  if (need > p->compute_covered) {
+    const int64_t i = p->compute_marks % ellm_pool::EV_RING;
+    HIP_TRY(hipEventRecord(r.ev[i], p->last_stream), "hipEventRecord(compute mark)");
+    p->compute_covers[i] = p->compute_covered = r.seq;
+    p->compute_marks++;
+    *ev = r.ev[i];
+    *covers = r.seq;
+    return ELLM_OK;
+  }
+  // the oldest mark still in the ring that covers the call (marks are in ascending order of cover)
+  int64_t pick = p->compute_marks - 1;
+  for (int64_t i = p->compute_marks - 2; i >= 0 && i > p->compute_marks - 1 - ellm_pool::EV_RING; i--) {
+    if (p->compute_covers[i % ellm_pool::EV_RING] < need) break;
+    pick = i;
+  }
+  *ev = r.ev[pick % ellm_pool::EV_RING];
+  *covers = p->compute_covers[pick % ellm_pool::EV_RING];
+  return ELLM_OK;
+}
+
+// `waiter` (a side stream) waits for compute call `need`
+int wait_for_compute(ellm_pool* p, hipStream_t waiter, int64_t need, int64_t& waited) {
+  if (need <= waited || need <= p->r_compute.done) return ELLM_OK;
+  hipEvent_t ev;
+  int64_t covers;
+  int rc = compute_mark(p, need, &ev, &covers);
+  if (rc) return rc;
+  HIP_TRY(hipStreamWaitEvent(waiter, ev, 0), "hipStreamWaitEvent(compute mark)");
+  waited = covers;
+  return ELLM_OK;
+}
+
+// the host waits for compute call `need`
+int host_wait_compute(ellm_pool* p, int64_t need) {
+  if (need <= p->r_compute.done) return ELLM_OK;
+  hipEvent_t ev;
+  int64_t covers;
+  int rc = compute_mark(p, need, &ev, &covers);
+  if (rc) return rc;
+  HIP_TRY(hipEventSynchronize(ev), "hipEventSynchronize(compute mark)");
+  p->r_compute.done = covers;
+  return ELLM_OK;
+}
+
 // a call of ring r's kind has enqueued its work on `stream`: number it and mark its end
 int record_on(ellm_pool::Ring& r, hipStream_t stream, int64_t* seq) {
   *seq = ++r.seq;
@@ -338,9 +394,8 @@ int enter_compute(ellm_pool* p, hipStream_t stream, const int32_t* ids, int32_t 
 // after a compute call's launches: remember which chunks it touches and mark its end on the stream
 int leave_compute(ellm_pool* p, hipStream_t stream, const int32_t* ids, int32_t batch) {
   if (!tracks_chunks(p)) return ELLM_OK;
-  int64_t seq;
-  int rc = record_on(p->r_compute, stream, &seq);
-  if (rc) return rc;
+  (void)stream;                        // == p->last_stream: where a mark for this call would be recorded
+  const int64_t seq = ++p->r_compute.seq;
   for (int32_t b = 0; b < batch; b++) {
     const ellm::TensorRec* t = p->core->tensor(ids[b]);
     const int32_t* r = p->core->row(ids[b]);
@@ -364,10 +419,10 @@ int enter_migration(ellm_pool* p, const std::vector<ellm::Move>& moves, bool fet
     else need_other = std::max({need_other, p->chunk_in[m.chunk], p->host_in[m.host_slot]});
   }
   if (fetch) {
-    if ((rc = wait_for(p->side_in, p->r_compute, need_compute, p->in_waits_compute))) return rc;
+    if ((rc = wait_for_compute(p, p->side_in, need_compute, p->in_waits_compute))) return rc;
     return wait_for(p->side_in, p->r_out, need_other, p->in_waits_out);
   }
-  if ((rc = wait_for(p->side_out, p->r_compute, need_compute, p->out_waits_compute))) return rc;
+  if ((rc = wait_for_compute(p, p->side_out, need_compute, p->out_waits_compute))) return rc;
   return wait_for(p->side_out, p->r_in, need_other, p->out_waits_in);
 }
 
@@ -438,7 +493,7 @@ int vmm_sync(ellm_pool* p) {
     char* at = p->vbase[id] + (size_t)slot * cb;
     if (have >= 0) {
       if (p->dev_ready) {
-        int rc = host_wait(p->r_compute, p->chunk_compute[have]);
+        int rc = host_wait_compute(p, p->chunk_compute[have]);
         if (rc) return rc;
       }
       const auto t0 = clk::now();
