@@ -51,7 +51,9 @@ def parse():
                     help="waves per decode launch as a percentage of the library's choice, one wave per SIMD (0 = leave it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
-    ap.add_argument("--event-stride", type=int, default=7, help="time every n-th attention launch with HIP events")
+    ap.add_argument("--event-stride", type=int, default=0,
+                    help="time every n-th attention launch with HIP events (0 = 13 for the 8B-shaped workload, whose "
+                         "launches are short, 1 for the others)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the measured read ceilings")
     ap.add_argument("--separate-calls", action="store_true",
                     help="ellm_kv_append then ellm_decode_attention instead of the fused ellm_kv_append_decode")
@@ -219,17 +221,19 @@ class Workload:
         self.host = None
 
 
-def measure(wl, K, Wm, event_stride=7, use_events=True):
+def measure(wl, K, Wm, event_stride=0, use_events=True):
     """Wm untimed steps, then K timed steps between device synchronisations: wall clock for the mean
     (inputs resident in HBM), one stream event per step for the spread, the library's own event pairs
     around every event_stride-th attention kernel for the roofline."""
     E, torch, W, cfg = wl.E, wl.torch, wl.W, wl.cfg
+    if not event_stride:
+        event_stride = 13 if wl.name in ("llama8b", "tiny") else 1
     for _ in range(Wm):
         wl.step()
     torch.cuda.synchronize()
     if use_events:
-        # 7 and the layer counts share no factor, so every layer gets its turn; an event pair costs about 3 us
-        # of stream time, 7 % of the step if it sat around every launch
+        # 13 and the layer count share no factor, so every layer gets its turn; an event pair costs about 3 us
+        # of stream time, 7 % of the 8B-shaped step if it sat around every launch
         E.ellm_pool_profile_enable(wl.pool, K * wl.n_layers * 2)
         E.ellm_pool_profile_stride(wl.pool, event_stride)
     n_items, S, n_split_req = wl.n_split_items()
@@ -546,7 +550,7 @@ def elastic_step(E, torch, W, args, steps=3):
     t_off2 = timed(lambda: [offload_layer(l) for l in range(n_layers)], 1)     # parked again: the state between steps
     t_block = timed(blocking)
     E.ellm_pool_profile_enable(pool, steps * n_layers)
-    E.ellm_pool_profile_stride(pool, 7)
+    E.ellm_pool_profile_stride(pool, 13)
     t_layer = timed(layerwise)
     kern = E.ellm_pool_profile_collect(pool, steps * n_layers)
     E.ellm_pool_profile_enable(pool, 0)
