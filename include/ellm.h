@@ -16,9 +16,11 @@
  *     whole cached context with standard softmax attention, grouped-query or multi-head
  *     (Sec. 4.1 "Models"; Sec. 5 "Efficient Kernels").
  *
- * The paper maps chunks with the GPU driver's virtual-memory API. This library keeps the
- * virtual-to-physical map in software instead: one int32 table row per tensor, token t living
- * in slot t / T_c at row t % T_c of the chunk the table names, read directly by the kernels.
+ * The paper maps chunks with the GPU driver's virtual-memory API. By default this library keeps
+ * the virtual-to-physical map in software instead: one int32 table row per tensor, token t living
+ * in slot t / T_c at row t % T_c of the chunk the table names, read directly by the kernels. A
+ * pool created with ELLM_POOL_DRIVER_MAPPED does it the paper's way as well: the driver maps the
+ * chunks into each tensor's address range and the kernels read contiguous addresses.
  *
  * All pointers say "host" or "device" below. No call allocates memory the caller has to free
  * except ellm_pool_create (freed by ellm_pool_destroy). A pool is NOT thread-safe: one host

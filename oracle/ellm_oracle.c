@@ -26,9 +26,11 @@
  *               evaluated in fp64, two passes, no mask, no blocking or reordering.
  *
  * Readings where the paper is silent (chunk layout, which free chunk is taken, error order) are
- * the C-ABI contract's; they are restated at each function. Parity status: the attention
- * arithmetic is pinned by tests against closed forms and a library routine; the allocator order
- * and the in-chunk layout are conventions of this build, "parity unpinned" by the paper.
+ * the C-ABI contract's; they are restated at each function. Parity status: every function here
+ * has a pin in tests/oracle_pins.py (the attention arithmetic against closed forms and a library
+ * routine, the pool rules against brute force and hand-worked sequences); the allocator order,
+ * the in-chunk layout and the tie and rounding rules of reuse and buffer scaling are conventions
+ * of this build, "parity unpinned" by the paper, which is silent on them.
  *
  * Build: gcc -O2 -shared -fPIC -pthread ellm_oracle.c -o libellm_oracle.so -lm
  */
