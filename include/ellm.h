@@ -86,12 +86,19 @@ extern "C" {
                                       contiguous addresses, with no table. The host table is kept all the
                                       same (it is what every check and every introspection call reads), and
                                       all chunks are mapped a second time, in id order, into one range
-                                      (ellm_pool_get_device_base), through which copies address them. Every
-                                      call that changes table entries makes the driver calls before it
-                                      returns; one that takes a chunk out of a slot (unmap, offload, destroy,
-                                      chunks taken back by acquire) first waits, on the host, for the kernels
-                                      already enqueued that read that chunk. Same results, bit for bit, as a
-                                      pool without the flag. */
+                                      (ellm_pool_get_device_base), through which copies address them. A call
+                                      that changes table entries does not make the driver calls itself: it
+                                      hands them, in order, to a thread the pool owns (Sec. 3.1: chunks are
+                                      mapped ahead of their first use and unmapping is kept off the critical
+                                      path), and returns. A compute call waits, on the host, until the slots
+                                      it is about to touch have been mapped; a slot mapped a step ahead
+                                      (ellm_pool_premap_next) is ready by then. A chunk taken out of a slot
+                                      (unmap, offload, destroy, chunks taken back by acquire) is unmapped by
+                                      that thread once the kernels enqueued so far have finished. A driver
+                                      error met by the thread is returned, as ELLM_ERR_HIP, by the next call
+                                      that waits for it and by every such call after that. ellm_pool_sync
+                                      also waits for the thread. Same results, bit for bit, as a pool
+                                      without the flag. */
 
 /* Table-entry encoding (compared bit-exactly by tests):
  *   e >= 0   device chunk id
@@ -363,7 +370,8 @@ int ellm_pool_slo_configure(ellm_pool* pool, double ttft_slo, double tpot_slo, d
                             int32_t threshold);
 int ellm_pool_slo_observe(ellm_pool* pool, double ttft, double tpot, int32_t* logical_host_slots);
 
-/* Block until all migrations enqueued so far have finished. Returns HIP on an asynchronous fault. */
+/* Block until all migrations enqueued so far have finished (and, in a driver-mapped pool, all
+ * mappings asked for have been made). Returns HIP on an asynchronous fault. */
 int ellm_pool_sync(ellm_pool* pool);
 
 /* ---- introspection (host state, for bit-exact checks) -------------------------------------- */
@@ -375,6 +383,9 @@ int ellm_pool_get_device_base(ellm_pool* pool, void** base);
  * figure the paper reports as the share of time in virtual-memory operations (Sec. 4.6). Any out
  * pointer may be NULL; zeros for other pools. */
 int ellm_pool_get_mapping_stats(ellm_pool* pool, int64_t* n_map, double* us_map, int64_t* n_unmap, double* us_unmap);
+/* Host microseconds the pool's callers have spent waiting for the thread that makes the driver calls
+ * (host): what is left of the figure above on the critical path. */
+int ellm_pool_get_mapping_wait(ellm_pool* pool, double* us_waited);
 /* Geometry: any out pointer may be NULL. */
 int ellm_pool_get_geometry(ellm_pool* pool, int32_t* n_chunks, int32_t* tokens_per_chunk,
                            int32_t* n_host_slots, uint64_t* bytes_per_token);
@@ -450,6 +461,10 @@ int ellm_debug_vmm_buffer_destroy(void* base);
  * chunks through the software table (in the range of ellm_pool_get_device_base) as in a plain pool;
  * 0 goes back to the tensors' own address ranges. Same output bits. INVALID for other pools. */
 int ellm_debug_set_table_kernels(ellm_pool* pool, int on);
+/* Driver-mapped pools, for measurements: on == 0 makes every call that changes table entries wait
+ * until the driver calls it asked for have been made (what the pool would cost without its mapper
+ * thread); != 0 (the default) goes back to handing them over. INVALID for other pools. */
+int ellm_debug_set_async_mapping(ellm_pool* pool, int on);
 
 /* Test hook for the error path of calls that work in several launches: the nth kernel launch of
  * ellm_kv_append / ellm_decode_attention / ellm_kv_append_decode from now on (1 = the next one) is

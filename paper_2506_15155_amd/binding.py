@@ -86,6 +86,8 @@ _sigs = {
     "ellm_pool_get_device_base": [_vp, C.POINTER(C.c_void_p)],
     "ellm_pool_get_mapping_stats": [_vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)],
     "ellm_debug_set_table_kernels": [_vp, C.c_int],
+    "ellm_debug_set_async_mapping": [_vp, C.c_int],
+    "ellm_pool_get_mapping_wait": [_vp, C.POINTER(C.c_double)],
     "ellm_pool_get_geometry": [_vp, _i32p, _i32p, _i32p, C.POINTER(C.c_uint64)],
     "ellm_tensor_get_table": [_vp, C.c_int32, _i32p, C.c_int32, _i32p, C.POINTER(C.c_int64)],
     "ellm_pool_get_owner_state": [_vp, _vp, _vp, _i32p, _i32p],
@@ -361,6 +363,16 @@ def ellm_pool_get_mapping_stats(pool):
 
 def ellm_debug_set_table_kernels(pool, on, check=True):
     return _ret(lib.ellm_debug_set_table_kernels(pool, int(bool(on))), check)
+
+
+def ellm_debug_set_async_mapping(pool, on, check=True):
+    return _ret(lib.ellm_debug_set_async_mapping(pool, int(bool(on))), check)
+
+
+def ellm_pool_get_mapping_wait(pool):
+    us = C.c_double()
+    _ret(lib.ellm_pool_get_mapping_wait(pool, C.byref(us)), True)
+    return us.value
 
 
 def ellm_debug_fail_launch(pool, nth, check=True):

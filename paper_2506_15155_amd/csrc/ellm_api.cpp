@@ -5,13 +5,18 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <cmath>
+#include <condition_variable>
 #include <cstdio>
 #include <cstring>
+#include <deque>
 #include <memory>
+#include <mutex>
 #include <string>
 #include <map>
+#include <thread>
 #include <vector>
 
 #include "kernels.hpp"
@@ -107,7 +112,30 @@ struct ellm_pool {
   uint64_t* d_vbase = nullptr;         // device copy of vbase
   std::vector<int32_t> vbase_dirty;    // tensor handles whose base the device copy does not have yet
   double vmm_map_us = 0, vmm_unmap_us = 0;   // host time spent in the driver's map (+ set-access) and unmap calls
-  int64_t vmm_maps = 0, vmm_unmaps = 0;
+  int64_t vmm_maps = 0, vmm_unmaps = 0;      // (written by the mapper thread; read after a drain)
+  double vmm_wait_us = 0;                    // time callers spent waiting for the mapper thread
+  // The driver calls run on a thread of the pool's own, in the order they were asked for (paper
+  // Sec. 3.1: mappings made ahead of time and unmappings both happen beside the computation).
+  struct MapJob {
+    uint64_t seq;
+    char* at;                                // address in a tensor's range
+    hipMemGenericAllocationHandle_t handle;  // chunk to map there (map jobs)
+    bool unmap;
+    hipEvent_t after;                        // not NULL: kernels that may read `at` end before this event
+  };
+  std::thread vmm_thread;
+  std::mutex vmm_mu;
+  std::condition_variable vmm_cv_work, vmm_cv_done;
+  std::deque<MapJob> vmm_queue;              // guarded by vmm_mu
+  bool vmm_stop = false;                     // guarded by vmm_mu
+  std::atomic<uint64_t> vmm_done{0};         // jobs finished (their sequence numbers are 1, 2, ...)
+  int vmm_error = 0;                         // first hipError_t a job met (guarded by vmm_mu); sticky
+  std::string vmm_error_where;
+  uint64_t vmm_seq = 0;                      // jobs asked for
+  uint64_t vmm_last_map = 0;                 // newest map job
+  bool vmm_async = true;                     // false: every call waits for the jobs it asked for
+  std::vector<uint64_t> vmm_slot_job;        // per (tensor, slot): the map job that makes it readable
+  std::vector<uint64_t> vmm_tensor_job;      // per tensor: the newest of those
   int32_t split_override = 0;
   int32_t wave_slots = 0;              // waves of a decode launch: one per SIMD of the GPU (0 = not asked yet)
   int32_t waves_percent = 100;         // waves of a launch, as a share of what the GPU holds at once
@@ -136,6 +164,7 @@ int core_err(ellm_pool* p, int rc) {
 }
 
 int vmm_sync(ellm_pool* p);
+int vmm_wait_slots(ellm_pool* p, const int32_t* ids, int32_t batch, int32_t extra);
 
 // result of a call into the host state machine that may have changed table entries: a failed call
 // changed nothing; after a successful one a driver-mapped pool brings its mappings in line
@@ -330,18 +359,6 @@ int wait_for_compute(ellm_pool* p, hipStream_t waiter, int64_t need, int64_t& wa
   return ELLM_OK;
 }
 
-// the host waits for compute call `need`
-int host_wait_compute(ellm_pool* p, int64_t need) {
-  if (need <= p->r_compute.done) return ELLM_OK;
-  hipEvent_t ev;
-  int64_t covers;
-  int rc = compute_mark(p, need, &ev, &covers);
-  if (rc) return rc;
-  HIP_TRY(hipEventSynchronize(ev), "hipEventSynchronize(compute mark)");
-  p->r_compute.done = covers;
-  return ELLM_OK;
-}
-
 // a call of ring r's kind has enqueued its work on `stream`: number it and mark its end
 int record_on(ellm_pool::Ring& r, hipStream_t stream, int64_t* seq) {
   *seq = ++r.seq;
@@ -350,12 +367,14 @@ int record_on(ellm_pool::Ring& r, hipStream_t stream, int64_t* seq) {
 }
 
 // Things every compute call does before launching on `stream`: wait for the copies that touched
-// the chunks of the tensors it works on, bring the device table up to date. The ordering state
+// the chunks of the tensors it works on (and, in a driver-mapped pool, for the mapper thread to have
+// mapped the slots the call reaches with `extra` more tokens per tensor), bring the device table up to date. The ordering state
 // treats the compute calls as one in-order sequence; a call on another stream than the one before
 // is therefore first put behind that one.
-int enter_compute(ellm_pool* p, hipStream_t stream, const int32_t* ids, int32_t batch) {
+int enter_compute(ellm_pool* p, hipStream_t stream, const int32_t* ids, int32_t batch, int32_t extra) {
   int rc = ensure_device(p);
   if (rc) return rc;
+  if (p->vmm && (rc = vmm_wait_slots(p, ids, batch, extra))) return rc;
   if (p->have_last_stream && stream != p->last_stream) {
     HIP_TRY(hipEventRecord(p->ev_switch, p->last_stream), "hipEventRecord(stream change)");
     HIP_TRY(hipStreamWaitEvent(stream, p->ev_switch, 0), "hipStreamWaitEvent(stream change)");
@@ -457,7 +476,13 @@ int settle_copies(ellm_pool* p, const int32_t* chunk_ids, int32_t n) {
 // chunk that backs one of its slots is mapped there by the driver. The host table stays the
 // source of truth; after every call that changed table entries the driver mappings are brought in
 // line with it, entry by entry: what left a slot is unmapped (once the kernels that may still
-// read it there have finished: the host waits), what came is mapped and made accessible.
+// read it there have finished), what came is mapped and made accessible.
+//   A driver call takes tens of microseconds on an idle GPU and a few hundred while kernels run, so
+// the calls are not made by the thread that changed the table: they are queued, in order, for a
+// thread of the pool's own (paper Sec. 3.1: chunks are mapped ahead of their first use, and
+// unmapping is taken off the critical path). A compute call waits only for the map jobs of the
+// slots it is about to touch; a slot mapped one step ahead is ready by then. An unmap job first
+// waits, on its own thread, for an event recorded behind the kernels launched so far.
 hipMemAllocationProp vmm_prop(int dev) {
   hipMemAllocationProp prop = {};
   prop.type = hipMemAllocationTypePinned;
@@ -466,18 +491,113 @@ hipMemAllocationProp vmm_prop(int dev) {
   return prop;
 }
 
-int vmm_sync(ellm_pool* p) {
-  if (!p->vmm) return ELLM_OK;
-  const std::vector<int64_t> changed = p->core->take_map_changes();
-  if (changed.empty()) return ELLM_OK;
+void vmm_worker(ellm_pool* p) {
   using clk = std::chrono::steady_clock;
   auto us_since = [](clk::time_point t0) { return std::chrono::duration<double, std::micro>(clk::now() - t0).count(); };
   const size_t cb = p->geom.chunk_bytes;
-  const std::vector<int32_t>& tab = p->core->table();
   hipMemAccessDesc acc = {};
   acc.location.type = hipMemLocationTypeDevice;
   acc.location.id = p->vmm_device;
   acc.flags = hipMemAccessFlagsProtReadWrite;
+  hipError_t e = hipSetDevice(p->vmm_device);
+  const char* where = "hipSetDevice(mapper thread)";
+  for (;;) {
+    ellm_pool::MapJob job;
+    {
+      std::unique_lock<std::mutex> lk(p->vmm_mu);
+      if (e != hipSuccess && !p->vmm_error) {
+        p->vmm_error = (int)e;
+        p->vmm_error_where = where;
+      }
+      p->vmm_cv_work.wait(lk, [&] { return p->vmm_stop || !p->vmm_queue.empty(); });
+      if (p->vmm_queue.empty()) return;      // asked to stop, nothing left to do
+      job = p->vmm_queue.front();
+      p->vmm_queue.pop_front();
+    }
+    e = hipSuccess;
+    if (job.after) {
+      e = hipEventSynchronize(job.after);
+      where = "hipEventSynchronize(before unmap)";
+      (void)hipEventDestroy(job.after);
+    }
+    // after an error the queue is still worked off (so that nobody waits for ever), but the driver
+    // is not asked for anything more
+    bool skip;
+    {
+      std::lock_guard<std::mutex> lk(p->vmm_mu);
+      skip = p->vmm_error != 0;
+    }
+    if (e == hipSuccess && !skip) {
+      const auto t0 = clk::now();
+      if (job.unmap) {
+        e = hipMemUnmap(job.at, cb);
+        where = "hipMemUnmap(tensor slot)";
+        p->vmm_unmap_us += us_since(t0);
+        p->vmm_unmaps++;
+      } else {
+        e = hipMemMap(job.at, cb, 0, job.handle, 0);
+        where = "hipMemMap(tensor slot)";
+        if (e == hipSuccess) {
+          e = hipMemSetAccess(job.at, cb, &acc, 1);
+          where = "hipMemSetAccess(tensor slot)";
+        }
+        p->vmm_map_us += us_since(t0);
+        p->vmm_maps++;
+      }
+    }
+    {
+      std::lock_guard<std::mutex> lk(p->vmm_mu);
+      if (e != hipSuccess && !p->vmm_error) {
+        p->vmm_error = (int)e;
+        p->vmm_error_where = where;
+      }
+      p->vmm_done.store(job.seq, std::memory_order_release);
+    }
+    p->vmm_cv_done.notify_all();
+    e = hipSuccess;
+  }
+}
+
+// the caller waits until the mapper thread has finished job `seq`; reports what went wrong there
+int vmm_wait(ellm_pool* p, uint64_t seq) {
+  if (p->vmm_done.load(std::memory_order_acquire) < seq) {
+    const auto t0 = std::chrono::steady_clock::now();
+    std::unique_lock<std::mutex> lk(p->vmm_mu);
+    p->vmm_cv_done.wait(lk, [&] { return p->vmm_done.load(std::memory_order_acquire) >= seq; });
+    p->vmm_wait_us += std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
+  }
+  std::lock_guard<std::mutex> lk(p->vmm_mu);
+  if (p->vmm_error) return hip_err((hipError_t)p->vmm_error, p->vmm_error_where.c_str());
+  return ELLM_OK;
+}
+
+int vmm_drain(ellm_pool* p) { return p->vmm && p->vmm_thread.joinable() ? vmm_wait(p, p->vmm_seq) : ELLM_OK; }
+
+// A compute call is about to touch the first ceil((len + extra) / tokens per chunk) slots of these
+// tensors: the map jobs of those slots must have finished. Slots mapped further ahead are not
+// waited for.
+int vmm_wait_slots(ellm_pool* p, const int32_t* ids, int32_t batch, int32_t extra) {
+  if (p->vmm_done.load(std::memory_order_acquire) >= p->vmm_last_map) return ELLM_OK;
+  uint64_t need = 0;
+  const uint64_t done = p->vmm_done.load(std::memory_order_acquire);
+  for (int32_t b = 0; b < batch; b++) {
+    if (p->vmm_tensor_job[ids[b]] <= done) continue;
+    const ellm::TensorRec* t = p->core->tensor(ids[b]);
+    const int64_t slots = std::min<int64_t>(t->n_slots, (t->len + extra + p->geom.tokens_per_chunk - 1) / p->geom.tokens_per_chunk);
+    const uint64_t* j = &p->vmm_slot_job[(size_t)ids[b] * p->geom.max_slots];
+    for (int64_t s_ = 0; s_ < slots; s_++) need = std::max(need, j[s_]);
+  }
+  return need > done ? vmm_wait(p, need) : ELLM_OK;
+}
+
+int vmm_sync(ellm_pool* p) {
+  if (!p->vmm) return ELLM_OK;
+  const std::vector<int64_t> changed = p->core->take_map_changes();
+  if (changed.empty()) return ELLM_OK;
+  const size_t cb = p->geom.chunk_bytes;
+  const std::vector<int32_t>& tab = p->core->table();
+  std::vector<ellm_pool::MapJob> jobs;
+  bool kernels_may_read = false;             // an unmapped chunk may still be read by a kernel in flight
   for (int64_t flat : changed) {
     const int32_t id = (int32_t)(flat / p->geom.max_slots), slot = (int32_t)(flat % p->geom.max_slots);
     const int32_t want = tab[flat] >= 0 ? tab[flat] : -1, have = p->vmm_mapped[flat];
@@ -492,26 +612,39 @@ int vmm_sync(ellm_pool* p) {
     }
     char* at = p->vbase[id] + (size_t)slot * cb;
     if (have >= 0) {
-      if (p->dev_ready) {
-        int rc = host_wait_compute(p, p->chunk_compute[have]);
-        if (rc) return rc;
-      }
-      const auto t0 = clk::now();
-      HIP_TRY(hipMemUnmap(at, cb), "hipMemUnmap(tensor slot)");
-      p->vmm_unmap_us += us_since(t0);
-      p->vmm_unmaps++;
+      if (p->dev_ready && p->chunk_compute[have] > p->r_compute.done) kernels_may_read = true;
+      jobs.push_back({0, at, hipMemGenericAllocationHandle_t{}, true, nullptr});
       p->vmm_mapped[flat] = -1;
     }
     if (want >= 0) {
-      const auto t0 = clk::now();
-      HIP_TRY(hipMemMap(at, cb, 0, p->vmm_handles[want], 0), "hipMemMap(tensor slot)");
-      HIP_TRY(hipMemSetAccess(at, cb, &acc, 1), "hipMemSetAccess(tensor slot)");
-      p->vmm_map_us += us_since(t0);
-      p->vmm_maps++;
+      jobs.push_back({0, at, p->vmm_handles[want], false, nullptr});
       p->vmm_mapped[flat] = want;
+      p->vmm_slot_job[flat] = p->vmm_tensor_job[id] = p->vmm_last_map = p->vmm_seq + jobs.size();
     }
   }
-  return ELLM_OK;
+  if (jobs.empty()) return ELLM_OK;
+  if (kernels_may_read && p->have_last_stream) {
+    // one event behind everything launched so far covers every unmap of this call: the first of
+    // them waits for it, the others run after that one
+    hipEvent_t ev;
+    HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming), "hipEventCreate(before unmap)");
+    hipError_t e = hipEventRecord(ev, p->last_stream);
+    if (e != hipSuccess) {
+      (void)hipEventDestroy(ev);
+      return hip_err(e, "hipEventRecord(before unmap)");
+    }
+    for (ellm_pool::MapJob& j : jobs)
+      if (j.unmap) { j.after = ev; break; }
+  }
+  {
+    std::lock_guard<std::mutex> lk(p->vmm_mu);
+    for (ellm_pool::MapJob& j : jobs) {
+      j.seq = ++p->vmm_seq;
+      p->vmm_queue.push_back(j);
+    }
+  }
+  p->vmm_cv_work.notify_one();
+  return p->vmm_async ? ELLM_OK : vmm_drain(p);
 }
 
 // creates the chunks and the window; on failure everything created so far is released by vmm_teardown
@@ -540,11 +673,23 @@ int vmm_setup(ellm_pool* p) {
   HIP_TRY(hipMemSetAccess(p->device_base, cb * n, &acc, 1), "hipMemSetAccess(window)");
   p->vbase.assign(p->geom.max_tensors, nullptr);
   p->vmm_mapped.assign((size_t)p->geom.max_tensors * p->geom.max_slots, -1);
+  p->vmm_slot_job.assign((size_t)p->geom.max_tensors * p->geom.max_slots, 0);
+  p->vmm_tensor_job.assign(p->geom.max_tensors, 0);
   p->core->log_map_changes(true);
+  p->vmm_thread = std::thread(vmm_worker, p);
   return ELLM_OK;
 }
 
 void vmm_teardown(ellm_pool* p) {
+  if (p->vmm_thread.joinable()) {
+    // the thread works off what is queued, then ends
+    {
+      std::lock_guard<std::mutex> lk(p->vmm_mu);
+      p->vmm_stop = true;
+    }
+    p->vmm_cv_work.notify_one();
+    p->vmm_thread.join();
+  }
   const size_t cb = p->geom.chunk_bytes;
   for (size_t flat = 0; flat < p->vmm_mapped.size(); flat++)
     if (p->vmm_mapped[flat] >= 0) {
@@ -807,7 +952,9 @@ int ellm_kv_append(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, const
   if (total > 0x7fffffffll / (2 * p->geom.n_kv_heads)) return set_err(ELLM_ERR_RANGE, "kv_append: too many tokens in one call");
   if (total == 0) return ELLM_OK;
   hipStream_t stream = (hipStream_t)stream_;
-  if (!p->metadata_only && (rc = enter_compute(p, stream, ids, batch))) return rc;
+  int32_t most_new = 0;
+  for (int32_t b = 0; b < batch; b++) most_new = std::max(most_new, n_new ? n_new[b] : 1);
+  if (!p->metadata_only && (rc = enter_compute(p, stream, ids, batch, most_new))) return rc;
   // One launch per group of MAX_LAUNCH_REQ requests; a group's lengths advance as soon as its launch
   // has been accepted, so rows written and lengths agree at every point, also when the runtime
   // refuses a later launch.
@@ -942,7 +1089,7 @@ static int decode_impl(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, c
   if (ws_fixed && most_slots > ws_fixed_slots)
     return set_err(ELLM_ERR_RANGE, "decode_attention_noalloc: the batch needs more partial results than the fixed "
                                    "workspace of ELLM_NOALLOC_WORKSPACE_BYTES holds");
-  int rc = enter_compute(p, stream, ids, batch);
+  int rc = enter_compute(p, stream, ids, batch, extra);
   if (rc) return rc;
   if (!ws_fixed && (rc = ensure_workspace(p, most_slots))) return rc;
   float* ws = ws_fixed ? ws_fixed : p->d_ws;
@@ -1079,11 +1226,25 @@ int ellm_pool_get_device_base(ellm_pool* p, void** base) {
 
 int ellm_pool_get_mapping_stats(ellm_pool* p, int64_t* n_map, double* us_map, int64_t* n_unmap, double* us_unmap) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  int rc = vmm_drain(p);           // the figures are the mapper thread's: complete once it has nothing left to do
+  if (rc) return rc;
   if (n_map) *n_map = p->vmm_maps;
   if (us_map) *us_map = p->vmm_map_us;
   if (n_unmap) *n_unmap = p->vmm_unmaps;
   if (us_unmap) *us_unmap = p->vmm_unmap_us;
   return ELLM_OK;
+}
+
+int ellm_pool_get_mapping_wait(ellm_pool* p, double* us_waited) {
+  if (!p || !us_waited) return set_err(ELLM_ERR_INVALID, "get_mapping_wait: NULL argument");
+  *us_waited = p->vmm_wait_us;
+  return ELLM_OK;
+}
+
+int ellm_debug_set_async_mapping(ellm_pool* p, int on) {
+  if (!p || !p->vmm) return set_err(ELLM_ERR_INVALID, "set_async_mapping: not a driver-mapped pool");
+  p->vmm_async = on != 0;
+  return p->vmm_async ? ELLM_OK : vmm_drain(p);
 }
 
 int ellm_debug_set_table_kernels(ellm_pool* p, int on) {
@@ -1100,6 +1261,8 @@ int ellm_debug_fail_launch(ellm_pool* p, int32_t nth) {
 
 int ellm_pool_sync(ellm_pool* p) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  int rc = vmm_drain(p);
+  if (rc) return rc;
   if (!p->dev_ready) return ELLM_OK;
   HIP_TRY(hipStreamSynchronize(p->side_in), "hipStreamSynchronize(side)");
   p->r_in.done = p->r_in.seq;
@@ -1200,7 +1363,7 @@ int ellm_debug_kv_stream_read(ellm_pool* p, const ellm_tensor_id* ids, int32_t b
   if (batch == 0) return ELLM_OK;
   if (p->metadata_only) return set_err(ELLM_ERR_NO_DEVICE, "debug_kv_stream_read: pool has no device");
   hipStream_t stream = (hipStream_t)stream_;
-  rc = enter_compute(p, stream, ids, batch);
+  rc = enter_compute(p, stream, ids, batch, 0);
   if (rc) return rc;
   const ellm::PoolView pv = view_of(p);
   ellm::BatchArgs a;

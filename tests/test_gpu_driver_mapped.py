@@ -83,3 +83,84 @@ def test_driver_mapped_pool_rejects_what_the_driver_cannot_map():
     rc, _ = E.ellm_pool_create(None, None, 30720, 5, 5, 64, 2, 2, flags=E.ELLM_POOL_DRIVER_MAPPED, device_bytes=4 * 30720,
                                check=False)
     assert rc == E.ERR.INVALID and "granularity" in E.ellm_last_error()
+
+
+def test_mapper_thread_orders_driver_calls_with_the_kernels():
+    """The driver calls of a driver-mapped pool are made by a thread of the pool's own (Sec. 3.1: mapping
+    ahead of time, unmapping off the critical path). Slots mapped ahead of their first write while
+    kernels run; a compute call right behind a map call (it has to wait for the thread); chunks that leave
+    one tensor while a kernel that reads them is still enqueued and at once back another tensor; the same
+    sequence of calls on a second pool whose calls make their driver calls themselves: every output equals
+    the oracle's within tolerance and the other pool's bit for bit, every state equals the oracle's."""
+    cfg = W.scaled(W.CONFIGS["llama8b"], batch=10, n_chunks=120, len_lo=200, len_hi=3000, lognormal_median=900)
+    Tc = cfg.tokens_per_chunk
+    st = W.draw_step(cfg, seed=29)
+    A = H.Both(cfg, mode="driver")                       # asynchronous (the default)
+    S = H.Both(cfg, oracle=False, mode="driver")         # every call waits for its own driver calls
+    E.ellm_debug_set_async_mapping(S.pool, 0)
+    assert E.ellm_debug_set_async_mapping(A.pool, 1) == 0
+    ids = H.load_step(A, st)
+    assert H.load_step(S, st) == ids
+    lens = np.array([E.ellm_tensor_get_table(A.pool, t)[1] for t in ids])
+    rng = np.random.default_rng(5)
+    for step in range(6):
+        # map the slot after the last mapped one for a few requests: nothing touches it for a while
+        for b in range(step % 3, cfg.batch, 3):
+            tab = E.ellm_tensor_get_table(A.pool, ids[b])[0]
+            nxt = int((tab >= 0).sum())
+            if nxt < cfg.max_slots:
+                assert A.map(ids[b], nxt, 1) == 0
+                assert E.ellm_tensor_map_chunks(S.pool, ids[b], nxt, 1, None, 0, check=False) == 0
+        # append enough tokens that some requests run into the slots just mapped, decode right behind
+        n_new = rng.integers(1, Tc // 3, size=cfg.batch).astype(np.int32)
+        k = W.normal_bf16(rng, (int(n_new.sum()), cfg.n_kv_heads, cfg.head_dim))
+        v = W.normal_bf16(rng, (int(n_new.sum()), cfg.n_kv_heads, cfg.head_dim))
+        room = np.array([int((E.ellm_tensor_get_table(A.pool, t)[0] >= 0).sum()) * Tc for t in ids]) - lens
+        n_new = np.minimum(n_new, np.maximum(room, 0)).astype(np.int32)
+        k, v = k[:int(n_new.sum())], v[:int(n_new.sum())]
+        assert A.append(ids, k, v, n_new) == 0
+        assert E.ellm_kv_append(S.pool, ids, H.dev_bits(k), H.dev_bits(v), n_new, check=False) == 0
+        lens += n_new
+        q = W.normal_bf16(rng, (cfg.batch, cfg.n_q_heads, cfg.head_dim))
+        rc, out = A.decode(ids, q)
+        rcs, outs = S.decode(ids, q)
+        assert rc == 0 == rcs
+        rco, ref = A.orc.decode(ids, q)
+        assert rco == 0
+        H.check_close(out, ref, f"step {step}")
+        assert torch.equal(out, outs)
+        A.compare_state()
+    # a decode is enqueued and not waited for; the tensors it reads are destroyed (their chunks leave the
+    # ranges once the kernel is through) and new tensors take the same chunks at once
+    q = W.normal_bf16(rng, (cfg.batch, cfg.n_q_heads, cfg.head_dim))
+    qd = H.dev_bits(q)
+    out = torch.empty_like(qd)
+    assert E.ellm_decode_attention(A.pool, ids, qd, out, check=False) == 0
+    rco, ref = A.orc.decode(ids, q)
+    gone = ids[:4]
+    for t in gone:
+        assert A.both("destroy", lambda: E.ellm_tensor_destroy(A.pool, t, check=False), lambda: A.orc.tensor_destroy(t)) == 0
+        A.ids.remove(t)
+    fresh = []
+    for i in range(4):
+        t = A.create(cfg.max_tokens)
+        assert A.map(t, 0, 2) == 0
+        fresh.append(t)
+    kk = W.normal_bf16(rng, (4 * 70, cfg.n_kv_heads, cfg.head_dim))
+    vv = W.normal_bf16(rng, (4 * 70, cfg.n_kv_heads, cfg.head_dim))
+    assert A.append(fresh, kk, vv, np.full(4, 70, np.int32)) == 0
+    torch.cuda.synchronize()
+    H.check_close(out, ref, "decode enqueued before its tensors were destroyed")
+    q2 = W.normal_bf16(rng, (4, cfg.n_q_heads, cfg.head_dim))
+    rc, out2 = A.decode(fresh, q2)
+    rco, ref2 = A.orc.decode(fresh, q2)
+    assert rc == 0 == rco
+    H.check_close(out2, ref2, "tensors backed by chunks that had just left other ranges")
+    A.compare_state()
+    assert E.ellm_pool_sync(A.pool, check=False) == 0
+    sa, ss = E.ellm_pool_get_mapping_stats(A.pool), E.ellm_pool_get_mapping_stats(S.pool)
+    assert sa["unmaps"] > 0 and sa["maps"] > ss["maps"] > 0
+    print("mapper thread:", sa, "callers waited", round(E.ellm_pool_get_mapping_wait(A.pool), 1), "us; inline:", ss,
+          "waited", round(E.ellm_pool_get_mapping_wait(S.pool), 1), "us")
+    A.close()
+    S.close()
