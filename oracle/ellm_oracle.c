@@ -473,6 +473,54 @@ int orc_kv_premap_next(orc_pool* p, const int32_t* ids, int32_t batch, uint32_t 
   return ORC_OK;
 }
 
+/* The same idea with a longer view (Sec. 3.1 maps "ahead of time"; how far is the caller's choice):
+ * every listed sequence is assumed to produce tokens_ahead more tokens (as far as its max_tokens
+ * allows), and every slot those tokens would be written to that has no chunk gets one now, in batch
+ * order and, within a tensor, in slot order. Slots that hold a host copy are left alone. All or
+ * nothing; *n_mapped counts the chunks. With tokens_ahead == 1 this is orc_kv_premap_next. */
+int orc_kv_premap_ahead(orc_pool* p, const int32_t* ids, int32_t batch, int64_t tokens_ahead, uint32_t flags,
+                        int32_t* n_mapped) {
+  if (batch < 0 || tokens_ahead < 1) return ORC_INVALID;
+  const int64_t Tc = p->tokens_per_chunk;
+  int32_t need = 0;
+  for (int32_t b = 0; b < batch; b++) {
+    orc_tensor* t = tensor_of(p, ids[b]);
+    if (!t) return ORC_INVALID;
+    for (int32_t j = 0; j < b; j++) if (ids[j] == ids[b]) return ORC_INVALID;
+    int64_t until = t->len + tokens_ahead;            /* tokens len .. until - 1 are the ones to come */
+    if (until > t->max_tokens) until = t->max_tokens;
+#if ORC_MUTANT == 17
+    for (int64_t s = t->len / Tc; s <= until / Tc && s < t->n_slots; s++)
+#else
+    for (int64_t s = t->len / Tc; s * Tc < until; s++)
+#endif
+      if (t->table[s] == ENTRY_NONE) need++;
+  }
+  int32_t* pick = (int32_t*)malloc(sizeof(int32_t) * (size_t)(need + 1));
+  int rc = choose_chunks(p, need, (flags & 1u) != 0, pick);
+  if (rc) { free(pick); return rc; }
+  int32_t k = 0;
+  for (int32_t b = 0; b < batch; b++) {
+    orc_tensor* t = tensor_of(p, ids[b]);
+    int64_t until = t->len + tokens_ahead;
+    if (until > t->max_tokens) until = t->max_tokens;
+#if ORC_MUTANT == 17
+    for (int64_t s = t->len / Tc; s <= until / Tc && s < t->n_slots; s++) {
+#else
+    for (int64_t s = t->len / Tc; s * Tc < until; s++) {
+#endif
+      if (t->table[s] != ENTRY_NONE) continue;
+      int32_t c = pick[k++];
+      p->owner[c] = OWNER_KV; p->state[c] = ST_MAPPED;
+      p->map_tensor[c] = ids[b]; p->map_slot[c] = (int32_t)s;
+      t->table[s] = c;
+    }
+  }
+  free(pick);
+  if (n_mapped) *n_mapped = need;
+  return ORC_OK;
+}
+
 int orc_pool_transfer(orc_pool* p, const int32_t* ids, int32_t n, int new_owner) {
   if (n < 0 || (new_owner != OWNER_KV && new_owner != OWNER_ACT)) return ORC_INVALID;
   for (int32_t i = 0; i < n; i++) {

@@ -37,6 +37,7 @@ def load(path: str | None = None) -> C.CDLL:
     lib.orc_tensor_acquire.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_uint32, _i32p]
     lib.orc_tensor_is_released.argtypes = [C.c_void_p, C.c_int32]
     lib.orc_kv_premap_next.argtypes = [C.c_void_p, _i32p, C.c_int32, C.c_uint32, _i32p]
+    lib.orc_kv_premap_ahead.argtypes = [C.c_void_p, _i32p, C.c_int32, C.c_int64, C.c_uint32, _i32p]
     lib.orc_pool_set_logical_host_slots.argtypes = [C.c_void_p, C.c_int32]
     lib.orc_pool_get_logical_host_slots.argtypes = [C.c_void_p]
     lib.orc_pool_slo_configure.argtypes = [C.c_void_p, C.c_double, C.c_double, C.c_double, C.c_int32, C.c_int32]
@@ -132,6 +133,12 @@ class OraclePool:
         a, p = _i32(ids)
         out = C.c_int32(0)
         rc = self.lib.orc_kv_premap_next(self.h, p, a.size, int(flags), C.byref(out))
+        return rc, out.value
+
+    def premap_ahead(self, ids, tokens_ahead, flags=0):
+        a, p = _i32(ids)
+        out = C.c_int32(0)
+        rc = self.lib.orc_kv_premap_ahead(self.h, p, a.size, int(tokens_ahead), int(flags), C.byref(out))
         return rc, out.value
 
     def set_logical_host_slots(self, n):

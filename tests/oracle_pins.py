@@ -516,6 +516,66 @@ def pin_release_acquire_premap_rules(lib):
     pool.close()
 
 
+def pin_premap_ahead_rules(lib):
+    """Pre-mapping with a longer view: exactly the empty slots that the next tokens_ahead tokens of
+    each listed tensor fall into get a chunk (hand-worked case with the chunk ids written out); one
+    token ahead is the plain pre-mapping call; on random states the count equals the one taken from
+    the tables in this test, and afterwards that many tokens can be appended with no further mapping."""
+    Tc = 16
+    pool = make_pool(lib, 8, 8, 64, Tc, n_chunks=9, n_host=0, max_tensors=4, max_slots=8)
+    _, a = pool.tensor_create(8 * Tc)
+    _, b = pool.tensor_create(8 * Tc)
+    _, c = pool.tensor_create(24)                                                # two slots at most
+    assert pool.map_chunks(a, 0, 2) == 0 and pool.map_chunks(b, 0, 2) == 0 and pool.map_chunks(c, 0, 1) == 0
+    tok = np.zeros((32, 8, 64), np.uint16)
+    assert pool.append([a], tok, tok, [20]) == 0 and pool.append([b], tok, tok, [32]) == 0
+    assert pool.append([c], tok, tok, [5]) == 0
+    # a: tokens 20..31 stay in slot 1 (mapped); b: 32..43 open slot 2; c: 5..16 reach into slot 1
+    assert pool.premap_ahead([a, b, c], 12) == (0, 2)
+    assert list(pool.table(a)[0][:3]) == [0, 1, -1] and list(pool.table(b)[0][:4]) == [2, 3, 5, -1]
+    assert list(pool.table(c)[0]) == [4, 6]
+    assert pool.premap_ahead([a], 13) == (0, 1) and list(pool.table(a)[0][:4]) == [0, 1, 7, -1]   # token 32 is in slot 2
+    assert pool.premap_ahead([c], 1000) == (0, 0)                                # nothing beyond max_tokens
+    assert pool.premap_ahead([a], 0)[0] == -1 and pool.premap_ahead([a, a], 4)[0] == -1
+    before = [list(pool.table(t)[0]) for t in (a, b, c)]
+    assert pool.premap_ahead([b, a], 40)[0] == -2                                # b needs 2, a 1: only chunk 8 is free
+    assert [list(pool.table(t)[0]) for t in (a, b, c)] == before and pool.check_invariants() == 0
+    pool.close()
+    rng = np.random.default_rng(77)
+    for trial in range(30):
+        Tc = int(rng.choice([4, 16]))
+        pools = [make_pool(lib, 2, 2, 64, Tc, n_chunks=120, n_host=0, max_tensors=6, max_slots=12) for _ in range(2)]
+        ids, lens, maxes = [], [], []
+        for i in range(5):
+            mx = int(rng.integers(1, 12 * Tc + 1))
+            L = int(rng.integers(0, mx + 1))
+            mapped = min(-(-mx // Tc), -(-L // Tc) + int(rng.integers(0, 3)))    # sometimes slots are mapped already
+            for q in pools:
+                _, t = q.tensor_create(mx)
+                assert q.map_chunks(t, 0, mapped) == 0
+                z = np.zeros((L, 2, 64), np.uint16)
+                assert q.append([t], z, z, [L]) == 0
+            ids.append(t); lens.append(L); maxes.append(mx)
+        k = int(rng.integers(1, 3 * Tc))
+        # one token ahead is the plain call
+        assert pools[0].premap_ahead(ids, 1) == pools[1].premap_next(ids)
+        assert all(np.array_equal(pools[0].table(t)[0], pools[1].table(t)[0]) for t in ids)
+        # k ahead: count from the tables
+        want = 0
+        for t, L, mx in zip(ids, lens, maxes):
+            tab = pools[0].table(t)[0]
+            slots = {tok_ // Tc for tok_ in range(L, min(L + k, mx))}
+            want += sum(1 for s_ in slots if tab[s_] == -1)
+        assert pools[0].premap_ahead(ids, k) == (0, want)
+        for step in range(k):
+            live = [t for t, L, mx in zip(ids, lens, maxes) if L + step < mx]
+            z = np.zeros((len(live), 2, 64), np.uint16)
+            assert pools[0].append(live, z, z) == 0
+        assert pools[0].check_invariants() == 0
+        for q in pools:
+            q.close()
+
+
 def pin_slo_buffer_trace(lib, path):
     """Replays the hand-worked trace of the logical buffer scaling (Sec. 2.3.2) in tests/golden, then
     checks that a shrunk logical buffer refuses offloads without evicting what is stored."""
@@ -560,4 +620,4 @@ ALL_PINS = [pin_sdpa_library, pin_single_token, pin_zero_query_is_mean, pin_cons
             pin_weights_sum_to_one, pin_two_token_logistic, pin_dominant_key, pin_shift_invariance,
             pin_gqa_grouping, pin_chunked_equals_twin_and_online, pin_layout_bytes,
             pin_remap_and_roundtrip_invariance, pin_allocator_order_and_inflation, pin_best_fit_is_the_arg_min,
-            pin_release_acquire_premap_rules, pin_unmap_rules, pin_act_busy_both_ways]
+            pin_release_acquire_premap_rules, pin_unmap_rules, pin_act_busy_both_ways, pin_premap_ahead_rules]

@@ -31,6 +31,7 @@ MUTANTS = {
     14: "unmap treats a partly filled slot as empty",
     15: "unmap clears the table entry but leaves the chunk (and host slot) taken",
     16: "busy = 0 leaves the activation chunks busy",
+    17: "pre-mapping ahead also maps the slot after the last token it looks at",
 }
 
 
