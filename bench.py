@@ -187,12 +187,13 @@ class Workload:
         if self.map_lookahead is not None:
             # a driver-mapped pool is told some steps early (the paper maps ahead of time, Sec. 3.1): the
             # pool's mapper thread then has made the driver calls by the time the slot is written
-            hit = np.flatnonzero((self.lens + self.map_lookahead) // Tc >= self.mapped_slots)
-            for b in hit:
-                for l in range(self.n_layers):
-                    E.ellm_tensor_map_chunks(self.pool, int(self.ids[l][b]), int(self.mapped_slots[b]), 1, None,
-                                             E.ELLM_MAP_ALLOW_INFLATE)
-                self.mapped_slots[b] += 1
+            ahead = self.map_lookahead + 1          # tokens: this step's and those of the steps after it
+            if not ((self.lens + ahead - 1) // Tc >= self.mapped_slots).any():
+                return
+            for l in range(self.n_layers):
+                if E.lib.ellm_kv_premap_ahead(self.c_pool, self.c_ids[l], B, C.c_int64(ahead), self.c_inflate, None):
+                    raise E.EllmError(-1, E.ellm_last_error())
+            self.mapped_slots = np.maximum(self.mapped_slots, (self.lens + ahead - 1) // Tc + 1)
             return
         # requests whose next token opens a new chunk get one mapped (inflating if needed)
         if not (self.lens % Tc == 0).any():

@@ -234,6 +234,17 @@ int ellm_tensor_is_released(ellm_pool* pool, ellm_tensor_id id);
 int ellm_kv_premap_next(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, uint32_t flags,
                         int32_t* n_mapped);
 
+/* The same with a longer view (Sec. 3.1 maps "ahead of time"; how far is the caller's policy): every
+ * listed tensor is assumed to produce tokens_ahead more tokens, as far as its max_tokens allows, and
+ * every slot those tokens would be written to that has no chunk gets one now, in batch order and,
+ * within a tensor, in slot order; slots that hold a host copy are left alone. tokens_ahead == 1 is
+ * ellm_kv_premap_next. In a driver-mapped pool this is what gives the pool's mapper thread the time
+ * to make the driver calls before the slot's first write. All or nothing; *n_mapped (may be NULL) =
+ * chunks mapped.
+ * Checks: as ellm_kv_premap_next, and tokens_ahead < 1 -> INVALID. */
+int ellm_kv_premap_ahead(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch, int64_t tokens_ahead,
+                         uint32_t flags, int32_t* n_mapped);
+
 /* Push the table changes made so far to the device mirror now, ordered on `stream`, instead of at
  * the start of the next append / decode call: with ellm_kv_premap_next this moves the mapping
  * work of the next step out of its way (Sec. 3.1). The changed entries travel in the arguments of

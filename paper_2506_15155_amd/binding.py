@@ -62,6 +62,7 @@ _sigs = {
     "ellm_tensor_acquire": [_vp, C.c_int64, C.c_int64, C.c_uint32, _i32p],
     "ellm_tensor_is_released": [_vp, C.c_int32],
     "ellm_kv_premap_next": [_vp, _i32p, C.c_int32, C.c_uint32, _i32p],
+    "ellm_kv_premap_ahead": [_vp, _i32p, C.c_int32, C.c_int64, C.c_uint32, _i32p],
     "ellm_pool_flush_tables": [_vp, _vp],
     "ellm_pool_set_logical_host_slots": [_vp, C.c_int32],
     "ellm_pool_get_logical_host_slots": [_vp, _i32p],
@@ -215,6 +216,17 @@ def ellm_tensor_acquire(pool, need_tokens, max_tokens, flags=0, check=True):
 
 def ellm_tensor_is_released(pool, tid):
     return lib.ellm_tensor_is_released(pool, tid)
+
+
+def ellm_kv_premap_ahead(pool, ids, tokens_ahead, flags=0, check=True):
+    """Returns the number of chunks mapped (check=True) or (rc, n)."""
+    _, p, n = _i32(ids)
+    out = C.c_int32(0)
+    rc = lib.ellm_kv_premap_ahead(pool, p, n, int(tokens_ahead), int(flags), C.byref(out))
+    if check:
+        _ret(rc, True)
+        return out.value
+    return rc, out.value
 
 
 def ellm_kv_premap_next(pool, ids, flags=0, check=True):

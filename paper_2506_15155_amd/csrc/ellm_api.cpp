@@ -1013,6 +1013,13 @@ int ellm_kv_premap_next(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, 
   return core_changed(p, p->core->premap_next(ids, batch, flags, n_mapped));
 }
 
+int ellm_kv_premap_ahead(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, int64_t tokens_ahead, uint32_t flags,
+                         int32_t* n_mapped) {
+  if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
+  if (flags & ~ELLM_MAP_ALLOW_INFLATE) return set_err(ELLM_ERR_INVALID, "premap_ahead: unknown flags");
+  return core_changed(p, p->core->premap_ahead(ids, batch, tokens_ahead, flags, n_mapped));
+}
+
 int ellm_pool_flush_tables(ellm_pool* p, void* stream) {
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
   if (p->metadata_only) return ELLM_OK;

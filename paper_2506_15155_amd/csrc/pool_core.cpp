@@ -250,6 +250,44 @@ int PoolCore::premap_next(const int32_t* ids, int32_t batch, uint32_t flags, int
   return OK;
 }
 
+int PoolCore::premap_ahead(const int32_t* ids, int32_t batch, int64_t tokens_ahead, uint32_t flags, int32_t* n_mapped) {
+  if (batch < 0 || (batch > 0 && !ids)) return fail(ERR_INVALID, "premap_ahead: bad batch");
+  if (tokens_ahead < 1) return fail(ERR_INVALID, "premap_ahead: tokens_ahead must be at least 1");
+  const int64_t Tc = g_.tokens_per_chunk;
+  ++stamp_now_;
+  // slots [first, last) of a tensor are the ones its next tokens_ahead tokens are written to
+  auto span = [&](int32_t id, int64_t* first, int64_t* last) {
+    const TensorRec& t = t_[id];
+    const int64_t until = std::min<int64_t>(t.len + tokens_ahead, t.max_tokens);
+    *first = t.len / Tc;
+    *last = until > t.len ? (until + Tc - 1) / Tc : *first;
+  };
+  int64_t need = 0;
+  for (int32_t b = 0; b < batch; b++) {
+    if (!tensor(ids[b])) return fail(ERR_INVALID, "premap_ahead: bad tensor handle");
+    if (stamp_[ids[b]] == stamp_now_) return fail(ERR_INVALID, "premap_ahead: tensor handle given twice");
+    stamp_[ids[b]] = stamp_now_;
+    int64_t first, last;
+    span(ids[b], &first, &last);
+    const int32_t* r = row(ids[b]);
+    for (int64_t s = first; s < last; s++)
+      if (r[s] == ENTRY_UNMAPPED) need++;
+  }
+  if (need > 0x7fffffffll) return fail(ERR_OOM, "not enough free chunks");
+  std::vector<int32_t> pick;
+  int rc = pick_chunks((int32_t)need, nullptr, (flags & 1u) != 0, pick);
+  if (rc) return rc;
+  int32_t k = 0;
+  for (int32_t b = 0; b < batch; b++) {
+    int64_t first, last;
+    span(ids[b], &first, &last);
+    for (int64_t s = first; s < last; s++)
+      if (row(ids[b])[s] == ENTRY_UNMAPPED) take_chunk(pick[k++], ids[b], (int32_t)s);
+  }
+  if (n_mapped) *n_mapped = (int32_t)need;
+  return OK;
+}
+
 int PoolCore::pick_chunks(int32_t n, const int32_t* ids, bool inflate, std::vector<int32_t>& out) {
   out.clear();
   out.reserve(n);

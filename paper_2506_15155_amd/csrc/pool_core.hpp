@@ -69,6 +69,7 @@ class PoolCore {
   int slo_observe(double ttft, double tpot, int32_t* logical_out);
   // speculative pre-mapping (Sec. 3.1): one chunk for every request whose next token opens an empty slot
   int premap_next(const int32_t* ids, int32_t batch, uint32_t flags, int32_t* n_mapped);
+  int premap_ahead(const int32_t* ids, int32_t batch, int64_t tokens_ahead, uint32_t flags, int32_t* n_mapped);
   int map_chunks(int32_t id, int32_t first, int32_t n, const int32_t* chunk_ids, uint32_t flags);
   int unmap_chunks(int32_t id, int32_t first, int32_t n);
   int transfer(const int32_t* chunk_ids, int32_t n, int new_owner);

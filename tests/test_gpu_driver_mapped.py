@@ -104,13 +104,11 @@ def test_mapper_thread_orders_driver_calls_with_the_kernels():
     lens = np.array([E.ellm_tensor_get_table(A.pool, t)[1] for t in ids])
     rng = np.random.default_rng(5)
     for step in range(6):
-        # map the slot after the last mapped one for a few requests: nothing touches it for a while
-        for b in range(step % 3, cfg.batch, 3):
-            tab = E.ellm_tensor_get_table(A.pool, ids[b])[0]
-            nxt = int((tab >= 0).sum())
-            if nxt < cfg.max_slots:
-                assert A.map(ids[b], nxt, 1) == 0
-                assert E.ellm_tensor_map_chunks(S.pool, ids[b], nxt, 1, None, 0, check=False) == 0
+        # a few requests get the slots of their next T_c tokens mapped: nothing touches them for a while
+        sub = ids[step % 3::3]
+        got = E.ellm_kv_premap_ahead(A.pool, sub, Tc, 0, check=False)
+        assert got == A.orc.premap_ahead(sub, Tc) and got[0] == 0
+        assert E.ellm_kv_premap_ahead(S.pool, sub, Tc, 0, check=False) == got
         # append enough tokens that some requests run into the slots just mapped, decode right behind
         n_new = rng.integers(1, Tc // 3, size=cfg.batch).astype(np.int32)
         k = W.normal_bf16(rng, (int(n_new.sum()), cfg.n_kv_heads, cfg.head_dim))

@@ -159,8 +159,13 @@ def random_walk(seed, steps=600, **kw):
             if alive and rng.random() < 0.8:
                 tids = rng.choice(alive, size=min(nb, len(alive)), replace=False).astype(np.int32)
             fl = int(rng.integers(0, 2))
-            a = E.ellm_kv_premap_next(P.lib, tids, fl, check=False)
-            b = P.orc.premap_next(tids, fl)
+            if rng.random() < 0.5:
+                a = E.ellm_kv_premap_next(P.lib, tids, fl, check=False)
+                b = P.orc.premap_next(tids, fl)
+            else:
+                ahead = int(rng.integers(0, 40))
+                a = E.ellm_kv_premap_ahead(P.lib, tids, ahead, fl, check=False)
+                b = P.orc.premap_ahead(tids, ahead, fl)
             assert a[0] == b[0] and (a[0] != 0 or a[1] == b[1]), (op, a, b)
             rc = a[0]
         elif op == "logical":
