@@ -476,6 +476,11 @@ int ellm_debug_set_table_kernels(ellm_pool* pool, int on);
  * until the driver calls it asked for have been made (what the pool would cost without its mapper
  * thread); != 0 (the default) goes back to handing them over. INVALID for other pools. */
 int ellm_debug_set_async_mapping(ellm_pool* pool, int on);
+/* Test hook for the error path of a driver-mapped pool's mapper thread: the nth mapping it is asked
+ * for from now on (1 = the next one; 0 = none) is not made and counts as refused by the driver. Every
+ * later call that would launch a kernel on the pool, or that waits for the thread, then returns
+ * ELLM_ERR_HIP and launches nothing; ellm_pool_destroy still works. INVALID for other pools. */
+int ellm_debug_fail_mapping(ellm_pool* pool, int32_t nth);
 
 /* Test hook for the error path of calls that work in several launches: the nth kernel launch of
  * ellm_kv_append / ellm_decode_attention / ellm_kv_append_decode from now on (1 = the next one) is

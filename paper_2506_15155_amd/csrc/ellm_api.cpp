@@ -130,10 +130,12 @@ struct ellm_pool {
   bool vmm_stop = false;                     // guarded by vmm_mu
   std::atomic<uint64_t> vmm_done{0};         // jobs finished (their sequence numbers are 1, 2, ...)
   int vmm_error = 0;                         // first hipError_t a job met (guarded by vmm_mu); sticky
+  std::atomic<bool> vmm_failed{false};       // set with it: no kernel may be launched on this pool any more
   std::string vmm_error_where;
   uint64_t vmm_seq = 0;                      // jobs asked for
   uint64_t vmm_last_map = 0;                 // newest map job
   bool vmm_async = true;                     // false: every call waits for the jobs it asked for
+  std::atomic<int> vmm_fail_in{0};           // test hook: the n-th map job from now reports a driver error
   std::vector<uint64_t> vmm_slot_job;        // per (tensor, slot): the map job that makes it readable
   std::vector<uint64_t> vmm_tensor_job;      // per tensor: the newest of those
   int32_t split_override = 0;
@@ -508,6 +510,7 @@ void vmm_worker(ellm_pool* p) {
       if (e != hipSuccess && !p->vmm_error) {
         p->vmm_error = (int)e;
         p->vmm_error_where = where;
+        p->vmm_failed.store(true, std::memory_order_release);
       }
       p->vmm_cv_work.wait(lk, [&] { return p->vmm_stop || !p->vmm_queue.empty(); });
       if (p->vmm_queue.empty()) return;      // asked to stop, nothing left to do
@@ -527,7 +530,10 @@ void vmm_worker(ellm_pool* p) {
       std::lock_guard<std::mutex> lk(p->vmm_mu);
       skip = p->vmm_error != 0;
     }
-    if (e == hipSuccess && !skip) {
+    if (e == hipSuccess && !skip && !job.unmap && p->vmm_fail_in.load() > 0 && p->vmm_fail_in.fetch_sub(1) == 1) {
+      e = hipErrorUnknown;                   // the hook: as if the driver had refused; nothing is mapped
+      where = "hipMemMap(tensor slot): refused (debug hook)";
+    } else if (e == hipSuccess && !skip) {
       const auto t0 = clk::now();
       if (job.unmap) {
         e = hipMemUnmap(job.at, cb);
@@ -550,6 +556,7 @@ void vmm_worker(ellm_pool* p) {
       if (e != hipSuccess && !p->vmm_error) {
         p->vmm_error = (int)e;
         p->vmm_error_where = where;
+        p->vmm_failed.store(true, std::memory_order_release);
       }
       p->vmm_done.store(job.seq, std::memory_order_release);
     }
@@ -577,9 +584,12 @@ int vmm_drain(ellm_pool* p) { return p->vmm && p->vmm_thread.joinable() ? vmm_wa
 // tensors: the map jobs of those slots must have finished. Slots mapped further ahead are not
 // waited for.
 int vmm_wait_slots(ellm_pool* p, const int32_t* ids, int32_t batch, int32_t extra) {
-  if (p->vmm_done.load(std::memory_order_acquire) >= p->vmm_last_map) return ELLM_OK;
-  uint64_t need = 0;
   const uint64_t done = p->vmm_done.load(std::memory_order_acquire);
+  // after a driver error some slot may be without its chunk: nothing is launched on this pool again
+  // (the thread sets the flag before it counts the job as done, so it is read after the count)
+  if (p->vmm_failed.load(std::memory_order_acquire)) return vmm_wait(p, 0);
+  if (done >= p->vmm_last_map) return ELLM_OK;
+  uint64_t need = 0;
   for (int32_t b = 0; b < batch; b++) {
     if (p->vmm_tensor_job[ids[b]] <= done) continue;
     const ellm::TensorRec* t = p->core->tensor(ids[b]);
@@ -1252,6 +1262,12 @@ int ellm_debug_set_async_mapping(ellm_pool* p, int on) {
   if (!p || !p->vmm) return set_err(ELLM_ERR_INVALID, "set_async_mapping: not a driver-mapped pool");
   p->vmm_async = on != 0;
   return p->vmm_async ? ELLM_OK : vmm_drain(p);
+}
+
+int ellm_debug_fail_mapping(ellm_pool* p, int32_t nth) {
+  if (!p || !p->vmm || nth < 0) return set_err(ELLM_ERR_INVALID, "fail_mapping: bad argument");
+  p->vmm_fail_in.store(nth);
+  return ELLM_OK;
 }
 
 int ellm_debug_set_table_kernels(ellm_pool* p, int on) {

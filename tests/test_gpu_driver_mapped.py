@@ -162,3 +162,33 @@ def test_mapper_thread_orders_driver_calls_with_the_kernels():
           "waited", round(E.ellm_pool_get_mapping_wait(S.pool), 1), "us")
     A.close()
     S.close()
+
+
+def test_a_refused_mapping_stops_the_pool_before_any_launch():
+    """The mapper thread meets a driver error (forced by the test hook: the mapping is simply not made):
+    the next call that would launch a kernel on the pool returns ELLM_ERR_HIP and launches nothing, so no
+    kernel ever reads the slot that has no chunk behind it; the host state is untouched by the failed
+    calls; the pool can still be destroyed."""
+    cfg = W.scaled(W.CONFIGS["llama8b"], batch=4, n_chunks=40, len_lo=100, len_hi=900, lognormal_median=400)
+    st = W.draw_step(cfg, seed=31)
+    B = H.Both(cfg, oracle=False, mode="driver")
+    ids = H.load_step(B, st)
+    rc, out0 = B.decode(ids, st.q)
+    assert rc == 0
+    E.ellm_debug_fail_mapping(B.pool, 2)
+    assert E.ellm_kv_premap_ahead(B.pool, ids, cfg.tokens_per_chunk, 0) >= 2      # the second mapping asked for is refused
+    assert E.ellm_pool_sync(B.pool, check=False) == E.ERR.HIP                     # the thread has got there
+    q = H.dev_bits(st.q)
+    out = torch.zeros_like(q)
+    rc = E.ellm_decode_attention(B.pool, ids, q, out, check=False)
+    assert rc == E.ERR.HIP and "refused" in E.ellm_last_error()
+    torch.cuda.synchronize()
+    assert not out.any()                                                          # nothing ran
+    lens = [E.ellm_tensor_get_table(B.pool, t)[1] for t in ids]
+    k, v = H.dev_bits(st.k_new), H.dev_bits(st.v_new)
+    assert E.ellm_kv_append(B.pool, ids, k, v, check=False) == E.ERR.HIP
+    assert E.ellm_kv_append_decode(B.pool, ids, k, v, q, out, check=False) == E.ERR.HIP
+    assert [E.ellm_tensor_get_table(B.pool, t)[1] for t in ids] == lens           # no length moved
+    assert E.ellm_pool_sync(B.pool, check=False) == E.ERR.HIP
+    assert E.ellm_debug_fail_mapping(B.pool, -1, check=False) == E.ERR.INVALID
+    B.close()
