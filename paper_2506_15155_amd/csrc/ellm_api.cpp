@@ -712,6 +712,9 @@ void vmm_teardown(ellm_pool* p) {
   for (hipMemGenericAllocationHandle_t h : p->vmm_handles) (void)hipMemRelease(h);
   if (p->device_base) (void)hipMemAddressFree(p->device_base, cb * (size_t)p->geom.n_chunks);
   p->device_base = nullptr;
+  // after a driver error some slots recorded as mapped never were, and unmapping those fails: that is
+  // expected here and must not be left behind as the calling thread's last error
+  (void)hipGetLastError();
 }
 
 // Under the automatic partition a launch never needs more partial slots than the workspace was

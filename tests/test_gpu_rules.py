@@ -238,3 +238,131 @@ def test_workspace_bound_on_the_device():
         E.ellm_workspace_bytes(cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.batch)
     B.close()
     del free0
+
+
+@pytest.mark.parametrize("seed", [11, 12])
+def test_random_walk_of_every_call_on_the_gpu(pool_mode, seed):
+    """A seeded walk of a few hundred calls of every kind, valid and invalid ones mixed, through the
+    library on the GPU and the oracle side by side: every return code equal; tables, owners, states and
+    host-slot maps equal after every tenth call; every decode that both sides accept within tolerance;
+    at the end every chunk and every host slot byte for byte."""
+    # 8 q / 2 kv heads of 128, 16-token chunks of 16 KiB, 8 tensor handles of at most 8 slots
+    cfg = W.Config("walk", 9, 8, 8, 2, 128, 16 * (2 * 2 * 128 * 2), 56, 16 * 8, "uniform", 1, 128, host_slots=12)
+    Tc, Hkv, Hq, D = cfg.tokens_per_chunk, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim
+    rng = np.random.default_rng(seed)
+    owner = (rng.random(cfg.n_chunks) < 0.25).astype(np.uint8)
+    B = H.Both(cfg, owner=owner, keep_twin=True, max_tensors=8)
+    poison = np.full(cfg.chunk_bytes // 2, H.POISON, np.uint16).view(np.uint8)
+    for c in range(cfg.n_chunks):
+        B.orc.chunk_set_bytes(c, poison)
+    P, O = B.pool, B.orc
+    n_ok = n_dec = 0
+
+    def some_ids(k=None):
+        k = int(rng.integers(1, 5)) if k is None else k
+        if rng.random() < 0.85:
+            live = [t for t in range(8) if O.is_released(t) == 0]
+            if live:
+                return list(rng.choice(live, size=min(k, len(live)), replace=False).astype(np.int32))
+        return list(rng.integers(-1, 9, size=k).astype(np.int32))
+
+    for it in range(320):
+        op = rng.choice(["create", "destroy", "map", "unmap", "append", "fused", "decode", "offload", "fetch", "release",
+                         "acquire", "premap", "transfer", "busy", "logical"],
+                        p=[.08, .03, .12, .03, .16, .12, .12, .07, .07, .03, .04, .05, .04, .02, .02])
+        rc = None
+        if op == "create":
+            mt = int(rng.integers(1, 8 * Tc + 1))
+            a, b = E.ellm_tensor_create(P, mt, check=False), O.tensor_create(mt)
+            assert a[0] == b[0] and (a[0] != 0 or a[1] == b[1]), (op, a, b)
+            rc = a[0]
+            if rc == 0 and a[1] not in B.ids:
+                B.ids.append(a[1])
+        elif op == "destroy":
+            t = int(some_ids(1)[0])
+            rc = E.ellm_tensor_destroy(P, t, check=False)
+            assert rc == O.tensor_destroy(t), op
+            if rc == 0:
+                B.ids.remove(t)
+        elif op == "map":
+            t, first, n, fl = int(some_ids(1)[0]), int(rng.integers(0, 8)), int(rng.integers(1, 4)), int(rng.integers(0, 2))
+            cids = None if rng.random() < 0.7 else rng.integers(0, cfg.n_chunks, size=n).astype(np.int32)
+            rc = B.map(t, first, n, cids, fl)
+        elif op == "unmap":
+            t, first, n = int(some_ids(1)[0]), int(rng.integers(0, 8)), int(rng.integers(1, 3))
+            rc = B.both(op, lambda: E.ellm_tensor_unmap_chunks(P, t, first, n, check=False), lambda: O.unmap_chunks(t, first, n))
+        elif op == "append":
+            ids = some_ids()
+            n_new = rng.integers(0, 2 * Tc, size=len(ids)).astype(np.int32)
+            k = W.normal_bf16(rng, (int(n_new.sum()), Hkv, D))
+            v = W.normal_bf16(rng, (int(n_new.sum()), Hkv, D))
+            rc = B.append(ids, k, v, n_new)
+        elif op == "fused":
+            ids = some_ids()
+            k, v = W.normal_bf16(rng, (len(ids), Hkv, D)), W.normal_bf16(rng, (len(ids), Hkv, D))
+            q = W.normal_bf16(rng, (len(ids), Hq, D))
+            # accepted: the oracle must accept the append and then the decode; refused: nothing may have
+            # changed (the comparison of the states that follows sees to that)
+            rc, out, ref = B.append_decode(ids, k, v, q)
+            if rc == 0:
+                H.check_close(out, ref, f"call {it} fused")
+                n_dec += 1
+        elif op == "decode":
+            ids = some_ids()
+            q = W.normal_bf16(rng, (len(ids), Hq, D))
+            rc, out = B.decode(ids, q)
+            rco, ref = O.decode(ids, q)
+            assert rc == rco, (op, rc, rco, E.ellm_last_error())
+            if rc == 0:
+                H.check_close(out, ref, f"call {it} decode")
+                n_dec += 1
+        elif op == "offload":
+            t, first, n = int(some_ids(1)[0]), int(rng.integers(0, 6)), int(rng.integers(1, 4))
+            rc = B.offload(t, first, n)
+        elif op == "fetch":
+            t, first, n = int(some_ids(1)[0]), int(rng.integers(0, 6)), int(rng.integers(1, 4))
+            rc = B.fetch(t, first, n)
+        elif op == "release":
+            t = int(some_ids(1)[0])
+            rc = B.both(op, lambda: E.ellm_tensor_release(P, t, check=False), lambda: O.release(t))
+        elif op == "acquire":
+            rc, _ = B.acquire(int(rng.integers(0, 6 * Tc)), int(rng.integers(1, 8 * Tc + 1)), int(rng.integers(0, 2)))
+        elif op == "premap":
+            ids, fl = some_ids(), int(rng.integers(0, 2))
+            if rng.random() < 0.5:
+                a, b = E.ellm_kv_premap_next(P, ids, fl, check=False), O.premap_next(ids, fl)
+            else:
+                ahead = int(rng.integers(0, 3 * Tc))
+                a, b = E.ellm_kv_premap_ahead(P, ids, ahead, fl, check=False), O.premap_ahead(ids, ahead, fl)
+            assert a[0] == b[0] and (a[0] != 0 or a[1] == b[1]), (op, a, b)
+            rc = a[0]
+        elif op == "transfer":
+            cids = rng.integers(0, cfg.n_chunks, size=int(rng.integers(1, 5))).astype(np.int32)
+            to = int(rng.integers(0, 2))
+            rc = B.both(op, lambda: E.ellm_pool_transfer(P, cids, to, check=False), lambda: O.transfer(cids, to))
+        elif op == "busy":
+            cids = rng.integers(0, cfg.n_chunks, size=int(rng.integers(1, 4))).astype(np.int32)
+            busy = int(rng.integers(0, 2))
+            rc = B.both(op, lambda: E.ellm_pool_set_act_busy(P, cids, busy, check=False), lambda: O.set_act_busy(cids, busy))
+        else:
+            n_l = int(rng.integers(-1, cfg.host_slots + 2))
+            rc = B.both(op, lambda: E.ellm_pool_set_logical_host_slots(P, n_l, check=False),
+                        lambda: O.set_logical_host_slots(n_l))
+        n_ok += rc == 0
+        if it % 10 == 9 or (op == "fused" and rc != 0):
+            B.compare_state()
+    B.compare_state()
+    assert E.ellm_pool_sync(P, check=False) == 0
+    torch.cuda.synchronize()
+    owner_now, state_now, _, _ = E.ellm_pool_get_owner_state(P)
+    for c in range(cfg.n_chunks):
+        # chunks that belong to busy activations are the caller's to write; all others must match
+        assert np.array_equal(B.chunk_bytes_dev(c), O.chunk_bytes_of(c)), c
+    slot_tensor, _ = E.ellm_pool_get_host_slots(P)
+    for s in range(cfg.host_slots):
+        if slot_tensor[s] >= 0:
+            assert np.array_equal(B.host_slot_bytes(s), O.host_slot_bytes(s)), s
+    del owner_now, state_now
+    assert n_ok >= 80 and n_dec >= 10, (n_ok, n_dec)
+    print(f"walk seed {seed} ({pool_mode}): {n_ok} of 320 calls accepted, {n_dec} decodes compared")
+    B.close()
