@@ -32,6 +32,7 @@ int orc_tensor_release(orc_pool* p, int32_t id);
 int orc_tensor_is_released(orc_pool* p, int32_t id);
 int orc_tensor_acquire(orc_pool* p, int64_t need, int64_t max_tokens, uint32_t flags, int32_t* out);
 int orc_kv_premap_next(orc_pool* p, const int32_t* ids, int32_t batch, uint32_t flags, int32_t* n_mapped);
+int orc_kv_premap_ahead(orc_pool* p, const int32_t* ids, int32_t batch, int64_t tokens_ahead, uint32_t flags, int32_t* n_mapped);
 int orc_pool_transfer(orc_pool* p, const int32_t* ids, int32_t n, int new_owner);
 int orc_pool_set_act_busy(orc_pool* p, const int32_t* ids, int32_t n, int busy);
 int orc_kv_append(orc_pool* p, const int32_t* ids, int32_t batch, const int32_t* n_new, const uint16_t* k_new,
@@ -210,8 +211,14 @@ int main(int argc, char** argv) {
         op = "premap";
         pick_batch(true);
         int32_t na = -1, nb2 = -1;
-        a = lib.premap_next(tids.data(), (int32_t)tids.size(), fl, &na);
-        b = orc_kv_premap_next(orc, tids.data(), (int32_t)tids.size(), fl, &nb2);
+        if (rng.chance(50)) {
+          a = lib.premap_next(tids.data(), (int32_t)tids.size(), fl, &na);
+          b = orc_kv_premap_next(orc, tids.data(), (int32_t)tids.size(), fl, &nb2);
+        } else {
+          const int64_t ahead = rng.range(0, 40);
+          a = lib.premap_ahead(tids.data(), (int32_t)tids.size(), ahead, fl, &na);
+          b = orc_kv_premap_ahead(orc, tids.data(), (int32_t)tids.size(), ahead, fl, &nb2);
+        }
         if (a == 0 && b == 0 && na != nb2) die(seed, step, op, "mapped counts differ", na, nb2);
       } break;
       default:
