@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libellm.so")
 SOURCES = ["pool_core.cpp", "ellm_api.cpp", "kernels.hip"]
-HEADERS = ["pool_core.hpp", "kernels.hpp", os.path.join(ROOT, "include", "ellm.h")]
+HEADERS = ["pool_core.hpp", "kernels.hpp", "map_queue.hpp", os.path.join(ROOT, "include", "ellm.h")]
 
 # packed-fp32 instructions are switched off for all device code of this library
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

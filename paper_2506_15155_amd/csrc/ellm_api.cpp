@@ -5,21 +5,17 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
-#include <atomic>
 #include <chrono>
 #include <cmath>
-#include <condition_variable>
 #include <cstdio>
 #include <cstring>
-#include <deque>
 #include <memory>
-#include <mutex>
 #include <string>
 #include <map>
-#include <thread>
 #include <vector>
 
 #include "kernels.hpp"
+#include "map_queue.hpp"
 #include "pool_core.hpp"
 
 namespace {
@@ -44,6 +40,36 @@ int hip_err(hipError_t e, const char* where) {
   } while (0)
 
 }  // namespace
+
+// the driver calls of a driver-mapped pool, as the pool's mapper thread makes them
+struct HipMapDriver {
+  int device = 0;
+  size_t chunk_bytes = 0;
+  const char* call = "";
+  void thread_begin() { (void)hipSetDevice(device); }
+  int wait_event(void* ev) {
+    const hipError_t e = hipEventSynchronize((hipEvent_t)ev);
+    (void)hipEventDestroy((hipEvent_t)ev);
+    call = "hipEventSynchronize(before unmap)";
+    return (int)e;
+  }
+  int map(char* at, void* handle) {
+    call = "hipMemMap(tensor slot)";
+    hipError_t e = hipMemMap(at, chunk_bytes, 0, (hipMemGenericAllocationHandle_t)handle, 0);
+    if (e != hipSuccess) return (int)e;
+    hipMemAccessDesc acc = {};
+    acc.location.type = hipMemLocationTypeDevice;
+    acc.location.id = device;
+    acc.flags = hipMemAccessFlagsProtReadWrite;
+    call = "hipMemSetAccess(tensor slot)";
+    return (int)hipMemSetAccess(at, chunk_bytes, &acc, 1);
+  }
+  int unmap(char* at) {
+    call = "hipMemUnmap(tensor slot)";
+    return (int)hipMemUnmap(at, chunk_bytes);
+  }
+  const char* last_call() const { return call; }
+};
 
 struct ellm_pool {
   ellm::Geometry geom;
@@ -111,31 +137,11 @@ struct ellm_pool {
   std::vector<int32_t> vmm_mapped;     // per (tensor, slot): chunk the driver has mapped there, -1 = none
   uint64_t* d_vbase = nullptr;         // device copy of vbase
   std::vector<int32_t> vbase_dirty;    // tensor handles whose base the device copy does not have yet
-  double vmm_map_us = 0, vmm_unmap_us = 0;   // host time spent in the driver's map (+ set-access) and unmap calls
-  int64_t vmm_maps = 0, vmm_unmaps = 0;      // (written by the mapper thread; read after a drain)
-  double vmm_wait_us = 0;                    // time callers spent waiting for the mapper thread
   // The driver calls run on a thread of the pool's own, in the order they were asked for (paper
   // Sec. 3.1: mappings made ahead of time and unmappings both happen beside the computation).
-  struct MapJob {
-    uint64_t seq;
-    char* at;                                // address in a tensor's range
-    hipMemGenericAllocationHandle_t handle;  // chunk to map there (map jobs)
-    bool unmap;
-    hipEvent_t after;                        // not NULL: kernels that may read `at` end before this event
-  };
-  std::thread vmm_thread;
-  std::mutex vmm_mu;
-  std::condition_variable vmm_cv_work, vmm_cv_done;
-  std::deque<MapJob> vmm_queue;              // guarded by vmm_mu
-  bool vmm_stop = false;                     // guarded by vmm_mu
-  std::atomic<uint64_t> vmm_done{0};         // jobs finished (their sequence numbers are 1, 2, ...)
-  int vmm_error = 0;                         // first hipError_t a job met (guarded by vmm_mu); sticky
-  std::atomic<bool> vmm_failed{false};       // set with it: no kernel may be launched on this pool any more
-  std::string vmm_error_where;
-  uint64_t vmm_seq = 0;                      // jobs asked for
+  std::unique_ptr<ellm::MapQueue<HipMapDriver>> mapq;
   uint64_t vmm_last_map = 0;                 // newest map job
   bool vmm_async = true;                     // false: every call waits for the jobs it asked for
-  std::atomic<int> vmm_fail_in{0};           // test hook: the n-th map job from now reports a driver error
   std::vector<uint64_t> vmm_slot_job;        // per (tensor, slot): the map job that makes it readable
   std::vector<uint64_t> vmm_tensor_job;      // per tensor: the newest of those
   int32_t split_override = 0;
@@ -493,101 +499,25 @@ hipMemAllocationProp vmm_prop(int dev) {
   return prop;
 }
 
-void vmm_worker(ellm_pool* p) {
-  using clk = std::chrono::steady_clock;
-  auto us_since = [](clk::time_point t0) { return std::chrono::duration<double, std::micro>(clk::now() - t0).count(); };
-  const size_t cb = p->geom.chunk_bytes;
-  hipMemAccessDesc acc = {};
-  acc.location.type = hipMemLocationTypeDevice;
-  acc.location.id = p->vmm_device;
-  acc.flags = hipMemAccessFlagsProtReadWrite;
-  hipError_t e = hipSetDevice(p->vmm_device);
-  const char* where = "hipSetDevice(mapper thread)";
-  for (;;) {
-    ellm_pool::MapJob job;
-    {
-      std::unique_lock<std::mutex> lk(p->vmm_mu);
-      if (e != hipSuccess && !p->vmm_error) {
-        p->vmm_error = (int)e;
-        p->vmm_error_where = where;
-        p->vmm_failed.store(true, std::memory_order_release);
-      }
-      p->vmm_cv_work.wait(lk, [&] { return p->vmm_stop || !p->vmm_queue.empty(); });
-      if (p->vmm_queue.empty()) return;      // asked to stop, nothing left to do
-      job = p->vmm_queue.front();
-      p->vmm_queue.pop_front();
-    }
-    e = hipSuccess;
-    if (job.after) {
-      e = hipEventSynchronize(job.after);
-      where = "hipEventSynchronize(before unmap)";
-      (void)hipEventDestroy(job.after);
-    }
-    // after an error the queue is still worked off (so that nobody waits for ever), but the driver
-    // is not asked for anything more
-    bool skip;
-    {
-      std::lock_guard<std::mutex> lk(p->vmm_mu);
-      skip = p->vmm_error != 0;
-    }
-    if (e == hipSuccess && !skip && !job.unmap && p->vmm_fail_in.load() > 0 && p->vmm_fail_in.fetch_sub(1) == 1) {
-      e = hipErrorUnknown;                   // the hook: as if the driver had refused; nothing is mapped
-      where = "hipMemMap(tensor slot): refused (debug hook)";
-    } else if (e == hipSuccess && !skip) {
-      const auto t0 = clk::now();
-      if (job.unmap) {
-        e = hipMemUnmap(job.at, cb);
-        where = "hipMemUnmap(tensor slot)";
-        p->vmm_unmap_us += us_since(t0);
-        p->vmm_unmaps++;
-      } else {
-        e = hipMemMap(job.at, cb, 0, job.handle, 0);
-        where = "hipMemMap(tensor slot)";
-        if (e == hipSuccess) {
-          e = hipMemSetAccess(job.at, cb, &acc, 1);
-          where = "hipMemSetAccess(tensor slot)";
-        }
-        p->vmm_map_us += us_since(t0);
-        p->vmm_maps++;
-      }
-    }
-    {
-      std::lock_guard<std::mutex> lk(p->vmm_mu);
-      if (e != hipSuccess && !p->vmm_error) {
-        p->vmm_error = (int)e;
-        p->vmm_error_where = where;
-        p->vmm_failed.store(true, std::memory_order_release);
-      }
-      p->vmm_done.store(job.seq, std::memory_order_release);
-    }
-    p->vmm_cv_done.notify_all();
-    e = hipSuccess;
-  }
-}
-
 // the caller waits until the mapper thread has finished job `seq`; reports what went wrong there
 int vmm_wait(ellm_pool* p, uint64_t seq) {
-  if (p->vmm_done.load(std::memory_order_acquire) < seq) {
-    const auto t0 = std::chrono::steady_clock::now();
-    std::unique_lock<std::mutex> lk(p->vmm_mu);
-    p->vmm_cv_done.wait(lk, [&] { return p->vmm_done.load(std::memory_order_acquire) >= seq; });
-    p->vmm_wait_us += std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
-  }
-  std::lock_guard<std::mutex> lk(p->vmm_mu);
-  if (p->vmm_error) return hip_err((hipError_t)p->vmm_error, p->vmm_error_where.c_str());
-  return ELLM_OK;
+  std::string where;
+  const int e = p->mapq->wait(seq, &where);
+  if (!e) return ELLM_OK;
+  if (e < 0) return set_err(ELLM_ERR_HIP, where);       // the test hook's refusal
+  return hip_err((hipError_t)e, where.c_str());
 }
 
-int vmm_drain(ellm_pool* p) { return p->vmm && p->vmm_thread.joinable() ? vmm_wait(p, p->vmm_seq) : ELLM_OK; }
+int vmm_drain(ellm_pool* p) { return p->vmm && p->mapq && p->mapq->running() ? vmm_wait(p, p->mapq->last()) : ELLM_OK; }
 
 // A compute call is about to touch the first ceil((len + extra) / tokens per chunk) slots of these
 // tensors: the map jobs of those slots must have finished. Slots mapped further ahead are not
 // waited for.
 int vmm_wait_slots(ellm_pool* p, const int32_t* ids, int32_t batch, int32_t extra) {
-  const uint64_t done = p->vmm_done.load(std::memory_order_acquire);
+  const uint64_t done = p->mapq->done();
   // after a driver error some slot may be without its chunk: nothing is launched on this pool again
   // (the thread sets the flag before it counts the job as done, so it is read after the count)
-  if (p->vmm_failed.load(std::memory_order_acquire)) return vmm_wait(p, 0);
+  if (p->mapq->failed()) return vmm_wait(p, 0);
   if (done >= p->vmm_last_map) return ELLM_OK;
   uint64_t need = 0;
   for (int32_t b = 0; b < batch; b++) {
@@ -606,7 +536,7 @@ int vmm_sync(ellm_pool* p) {
   if (changed.empty()) return ELLM_OK;
   const size_t cb = p->geom.chunk_bytes;
   const std::vector<int32_t>& tab = p->core->table();
-  std::vector<ellm_pool::MapJob> jobs;
+  std::vector<ellm::MapJob> jobs;
   bool kernels_may_read = false;             // an unmapped chunk may still be read by a kernel in flight
   for (int64_t flat : changed) {
     const int32_t id = (int32_t)(flat / p->geom.max_slots), slot = (int32_t)(flat % p->geom.max_slots);
@@ -623,13 +553,13 @@ int vmm_sync(ellm_pool* p) {
     char* at = p->vbase[id] + (size_t)slot * cb;
     if (have >= 0) {
       if (p->dev_ready && p->chunk_compute[have] > p->r_compute.done) kernels_may_read = true;
-      jobs.push_back({0, at, hipMemGenericAllocationHandle_t{}, true, nullptr});
+      jobs.push_back({at, nullptr, true, nullptr});
       p->vmm_mapped[flat] = -1;
     }
     if (want >= 0) {
-      jobs.push_back({0, at, p->vmm_handles[want], false, nullptr});
+      jobs.push_back({at, (void*)p->vmm_handles[want], false, nullptr});
       p->vmm_mapped[flat] = want;
-      p->vmm_slot_job[flat] = p->vmm_tensor_job[id] = p->vmm_last_map = p->vmm_seq + jobs.size();
+      p->vmm_slot_job[flat] = p->vmm_tensor_job[id] = p->vmm_last_map = p->mapq->last() + jobs.size();
     }
   }
   if (jobs.empty()) return ELLM_OK;
@@ -643,17 +573,10 @@ int vmm_sync(ellm_pool* p) {
       (void)hipEventDestroy(ev);
       return hip_err(e, "hipEventRecord(before unmap)");
     }
-    for (ellm_pool::MapJob& j : jobs)
-      if (j.unmap) { j.after = ev; break; }
+    for (ellm::MapJob& j : jobs)
+      if (j.unmap) { j.after = (void*)ev; break; }
   }
-  {
-    std::lock_guard<std::mutex> lk(p->vmm_mu);
-    for (ellm_pool::MapJob& j : jobs) {
-      j.seq = ++p->vmm_seq;
-      p->vmm_queue.push_back(j);
-    }
-  }
-  p->vmm_cv_work.notify_one();
+  p->mapq->push(jobs);
   return p->vmm_async ? ELLM_OK : vmm_drain(p);
 }
 
@@ -686,20 +609,16 @@ int vmm_setup(ellm_pool* p) {
   p->vmm_slot_job.assign((size_t)p->geom.max_tensors * p->geom.max_slots, 0);
   p->vmm_tensor_job.assign(p->geom.max_tensors, 0);
   p->core->log_map_changes(true);
-  p->vmm_thread = std::thread(vmm_worker, p);
+  HipMapDriver drv;
+  drv.device = p->vmm_device;
+  drv.chunk_bytes = cb;
+  p->mapq.reset(new ellm::MapQueue<HipMapDriver>(drv));
+  p->mapq->start();
   return ELLM_OK;
 }
 
 void vmm_teardown(ellm_pool* p) {
-  if (p->vmm_thread.joinable()) {
-    // the thread works off what is queued, then ends
-    {
-      std::lock_guard<std::mutex> lk(p->vmm_mu);
-      p->vmm_stop = true;
-    }
-    p->vmm_cv_work.notify_one();
-    p->vmm_thread.join();
-  }
+  if (p->mapq) p->mapq->stop();        // the thread works off what is queued, then ends
   const size_t cb = p->geom.chunk_bytes;
   for (size_t flat = 0; flat < p->vmm_mapped.size(); flat++)
     if (p->vmm_mapped[flat] >= 0) {
@@ -1248,16 +1167,16 @@ int ellm_pool_get_mapping_stats(ellm_pool* p, int64_t* n_map, double* us_map, in
   if (!p) return set_err(ELLM_ERR_INVALID, "NULL pool");
   int rc = vmm_drain(p);           // the figures are the mapper thread's: complete once it has nothing left to do
   if (rc) return rc;
-  if (n_map) *n_map = p->vmm_maps;
-  if (us_map) *us_map = p->vmm_map_us;
-  if (n_unmap) *n_unmap = p->vmm_unmaps;
-  if (us_unmap) *us_unmap = p->vmm_unmap_us;
+  if (n_map) *n_map = p->mapq ? p->mapq->maps : 0;
+  if (us_map) *us_map = p->mapq ? p->mapq->map_us : 0.0;
+  if (n_unmap) *n_unmap = p->mapq ? p->mapq->unmaps : 0;
+  if (us_unmap) *us_unmap = p->mapq ? p->mapq->unmap_us : 0.0;
   return ELLM_OK;
 }
 
 int ellm_pool_get_mapping_wait(ellm_pool* p, double* us_waited) {
   if (!p || !us_waited) return set_err(ELLM_ERR_INVALID, "get_mapping_wait: NULL argument");
-  *us_waited = p->vmm_wait_us;
+  *us_waited = p->mapq ? p->mapq->waited_us() : 0.0;
   return ELLM_OK;
 }
 
@@ -1269,7 +1188,7 @@ int ellm_debug_set_async_mapping(ellm_pool* p, int on) {
 
 int ellm_debug_fail_mapping(ellm_pool* p, int32_t nth) {
   if (!p || !p->vmm || nth < 0) return set_err(ELLM_ERR_INVALID, "fail_mapping: bad argument");
-  p->vmm_fail_in.store(nth);
+  p->mapq->fail_map_in(nth);
   return ELLM_OK;
 }
 
