@@ -13,7 +13,8 @@ CPU oracle timed on the host cores; `parity` the last timed step's output of one
 oracle on the same bits. With the default workload the line also carries, under `workloads`, the
 13B-shaped MHA layer and the 70B-shaped long-context layer measured the same way, the elastic step
 (chunks handed over from the activation side, a quarter of the requests offloaded to pinned host and
-fetched back) and the same model in a driver-mapped pool (the paper's own mapping mechanism).
+fetched back) and the same model in a driver-mapped pool (the paper's own mapping mechanism); then
+every workload runs in a process of its own, one after the other, and this one only merges their lines.
 """
 from __future__ import annotations
 
@@ -34,6 +35,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, public specification
 COPY_CALIBRATION_BYTES = 1 << 30
 DEFAULT_LAYERS = {"llama8b": 32, "mha13b": 2, "long70b": 4, "tiny": 4}
 METRIC = "decode-attention achieved HBM GB/s (% of peak) + tokens/s, chunk-backed KV, 1 GPU"
+
+
+LEGS = ["elastic", "driver_mapped", "long70b", "mha13b"]      # the other workloads of the default run
 
 
 def parse():
@@ -67,6 +71,8 @@ def parse():
     ap.add_argument("--vmm-latency", action="store_true", help="also time the driver's virtual-memory calls per chunk")
     ap.add_argument("--prefill-append", type=int, default=0, metavar="N",
                     help="also time a multi-token append of N tokens per request and layer")
+    ap.add_argument("--leg", default=None, choices=LEGS,
+                    help="measure only this one of the other workloads, in this process, and print its figures")
     return ap.parse_args()
 
 
@@ -654,21 +660,122 @@ def driver_mapped_compare(E, torch, W, args, K=30, Wm=5):
 
 
 # ------------------------------------------------------------------------------------------------------
+def run_in_processes(args):
+    """The default run: the headline workload and each of the other workloads in a process of its own, one
+    after the other; their figures are merged into the one line this process prints. A workload then sees
+    the GPU as a fresh process finds it: what an earlier one left behind in the allocator and the driver
+    (after tens of GB have been allocated and freed, kernels over memory allocated later run 4-9 % slower on
+    this machine, and opposite copies over PCIe take twice as long) is not charged to a later one. This
+    process starts the others before anything in it has touched the GPU, and never does."""
+    import subprocess
+
+    def child(extra, timeout):
+        cmd = [sys.executable, os.path.abspath(__file__), "--gpus", "1", *extra]
+        try:
+            r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=timeout, cwd=ROOT)
+        except subprocess.TimeoutExpired:
+            return None, f"no result within {timeout} s"
+        sys.stderr.write(r.stderr[-4000:])
+        lines = [l for l in r.stdout.splitlines() if l.startswith("{")]
+        if r.returncode != 0 or not lines:
+            return None, f"exit status {r.returncode}: {r.stderr.strip()[-300:]}"
+        return json.loads(lines[-1]), None
+
+    def memory_temperature():
+        """HBM temperature in degrees C as the driver's tool reports it, or None."""
+        try:
+            out = subprocess.run(["rocm-smi", "--showtemp", "--json"], stdout=subprocess.PIPE, stderr=subprocess.DEVNULL,
+                                 text=True, timeout=15).stdout
+            doc = json.loads([l for l in out.splitlines() if l.startswith("{")][-1])
+            vals = [float(v) for card in doc.values() for k, v in card.items() if "memory" in k.lower()]
+            return max(vals) if vals else None
+        except Exception:
+            return None
+
+    # A workload that follows another does not find the GPU as the first one does: on this machine the HBM
+    # sensor goes from 36 to 54 degrees within a second of full-rate reading, and for some seconds after such
+    # a stretch kernels move 4-8 % fewer bytes per second (the 13B-shaped layer: 3.31 ms when the GPU has been
+    # idle, 3.46-3.58 ms right after another workload, 3.31 ms again after 20-25 s of idling, although the
+    # sensor is back at 35 degrees within a few seconds). So that the two large layers are measured as the
+    # headline workload is (first thing on an idle GPU), the GPU is left idle for IDLE_BEFORE seconds before
+    # each of them, and until the sensor is back to within 3 degrees of its first reading; the readings and
+    # the idle times go into the line.
+    IDLE_BEFORE = {"long70b": 20.0, "mha13b": 20.0}
+    t_start = memory_temperature()
+    temps, idled = {}, {}
+
+    def cooled(at_least, patience=40.0):
+        t0 = time.perf_counter()
+        if at_least > 0:
+            time.sleep(at_least)
+        t = memory_temperature()
+        while t is not None and t_start is not None and t > t_start + 3.0 and time.perf_counter() - t0 < patience:
+            time.sleep(2.0)
+            t = memory_temperature()
+        return t, round(time.perf_counter() - t0, 1)
+
+    passed = ["--steps", str(args.steps), "--warmup", str(args.warmup)]
+    for flag, on in (("--no-cpu-baseline", args.no_cpu_baseline), ("--no-kernel-events", args.no_kernel_events),
+                     ("--no-ceilings", args.no_ceilings), ("--separate-calls", args.separate_calls),
+                     ("--turnover", args.turnover), ("--vmm-latency", args.vmm_latency)):
+        if on:
+            passed.append(flag)
+    if args.event_stride:
+        passed += ["--event-stride", str(args.event_stride)]
+    if args.placement != "shuffled":
+        passed += ["--placement", args.placement]
+    if args.prefill_append:
+        passed += ["--prefill-append", str(args.prefill_append)]
+    res, err = child(["--config", args.config, "--no-extras", *passed], 900)
+    if res is None:
+        print("bench.py: the headline measurement failed: " + err, file=sys.stderr)
+        return 1
+    temps["headline"] = [t_start, memory_temperature()]
+    workloads = {}
+    for name in LEGS:
+        leg_flags = ["--leg", name] + (["--no-ceilings"] if args.no_ceilings else [])
+        before, idled[name] = cooled(IDLE_BEFORE.get(name, 0.0))
+        got, err = child(leg_flags, 600)
+        temps[name] = [before, memory_temperature()]
+        workloads[name] = got if got is not None else {"error": err}
+    res["workloads"] = workloads
+    res["hbm_temperature_C_before_and_after"] = temps
+    res["seconds_idle_before"] = idled
+    res["config"]["workload"] += ("; also, under `workloads`: long70b and mha13b layers measured the same way, the elastic step "
+                                  "(ownership transfer + offload / fetch of every 4th request) and the same model in a "
+                                  "driver-mapped pool; every workload in a process of its own")
+    print(json.dumps(res))
+    return 0
+
+
+# ------------------------------------------------------------------------------------------------------
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
               "(the path needs no collective and nothing in it spans GPUs)", file=sys.stderr)
         sys.exit(2)
+    extras = args.extras if args.extras is not None else (args.config == "llama8b" and args.pool == "plain"
+                                                          and args.pool_memory == "malloc" and not args.split
+                                                          and not args.waves_percent and not args.layers
+                                                          and not args.leg)
+    if extras:
+        # every workload in a process of its own, one after the other, started by this one, which never
+        # touches the GPU itself (see run_in_processes)
+        sys.exit(run_in_processes(args))
     import torch
     import paper_2506_15155_amd as E
     import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    extras = args.extras if args.extras is not None else (args.config == "llama8b" and args.pool == "plain"
-                                                          and args.pool_memory == "malloc" and not args.split
-                                                          and not args.waves_percent and not args.layers)
+    if args.leg:
+        fn = {"elastic": lambda: elastic_step(E, torch, W, args),
+              "driver_mapped": lambda: driver_mapped_compare(E, torch, W, args),
+              "long70b": lambda: sub_workload(E, torch, W, "long70b", 20, 5, args, 3),
+              "mha13b": lambda: sub_workload(E, torch, W, "mha13b", 20, 5, args, 4)}[args.leg]
+        print(json.dumps(fn()))
+        return
     K, Wm = args.steps, args.warmup
     if args.config in ("mha13b", "long70b"):
         K, Wm = min(K, 20), min(Wm, 5)
@@ -726,30 +833,6 @@ def main():
     del wl
     torch.cuda.empty_cache()
 
-    workloads = None
-    if extras:
-        # The two small-pool measurements come first: once a process has allocated and freed tens of GB of
-        # device memory (the two large layers do), back-to-back copies in opposite directions between the GPU
-        # and pinned memory take twice as long on this machine (a plain 40 GB allocate-and-free ahead of the
-        # elastic step shows the same), which would be charged to the elastic step.
-        workloads = {}
-
-        def leg(name, fn):
-            # a leg that cannot run on this machine (an error returned by the library or the runtime) is
-            # reported as such; the headline figures above do not depend on it
-            try:
-                workloads[name] = fn()
-            except (E.EllmError, RuntimeError, MemoryError) as exc:
-                workloads[name] = {"error": f"{type(exc).__name__}: {exc}"}
-                torch.cuda.empty_cache()
-
-        leg("elastic", lambda: elastic_step(E, torch, W, args))
-        leg("driver_mapped", lambda: driver_mapped_compare(E, torch, W, args))
-        leg("long70b", lambda: sub_workload(E, torch, W, "long70b", 20, 5, args, 3))
-        leg("mha13b", lambda: sub_workload(E, torch, W, "mha13b", 20, 5, args, 4))
-        desc += ("; also, under `workloads`: long70b and mha13b layers measured the same way, the elastic step "
-                 "(ownership transfer + offload / fetch of every 4th request) and the same model in a driver-mapped pool")
-
     res = {
         "metric": METRIC, "value": head["value"], "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -765,8 +848,6 @@ def main():
                    "algorithmic_bytes_per_step": head["algorithmic_bytes_per_step"], "pool_chunks": n_chunks_head},
         "roofline": roofline, "cpu_baseline": cpu, "parity": parity,
     }
-    if workloads:
-        res["workloads"] = workloads
     if pre:
         res["prefill_append"] = pre
     if turn:
