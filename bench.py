@@ -71,6 +71,8 @@ def parse():
     ap.add_argument("--vmm-latency", action="store_true", help="also time the driver's virtual-memory calls per chunk")
     ap.add_argument("--prefill-append", type=int, default=0, metavar="N",
                     help="also time a multi-token append of N tokens per request and layer")
+    ap.add_argument("--preheat", type=float, default=0.0, metavar="S",
+                    help="read at full rate (decode calls, no append) for S seconds before the warm-up steps")
     ap.add_argument("--leg", default=None, choices=LEGS,
                     help="measure only this one of the other workloads, in this process, and print its figures")
     return ap.parse_args()
@@ -241,13 +243,24 @@ class Workload:
         self.host = None
 
 
-def measure(wl, K, Wm, event_stride=0, use_events=True):
+def measure(wl, K, Wm, event_stride=0, use_events=True, preheat_s=0.0):
     """Wm untimed steps, then K timed steps between device synchronisations: wall clock for the mean
     (inputs resident in HBM), one stream event per step for the spread, the library's own event pairs
-    around every event_stride-th attention kernel for the roofline."""
+    around every event_stride-th attention kernel for the roofline. preheat_s: before all that, the
+    layers' decode calls (no append: the lengths stay) are repeated for that many seconds, so that the
+    timed steps run on a GPU that has been reading at full rate for a while."""
     E, torch, W, cfg = wl.E, wl.torch, wl.W, wl.cfg
     if not event_stride:
         event_stride = 13 if wl.name in ("llama8b", "tiny") else 1
+    if preheat_s > 0:
+        t_end = time.perf_counter() + preheat_s
+        while time.perf_counter() < t_end:
+            for _ in range(8):
+                for l in range(wl.n_layers):
+                    rc = E.lib.ellm_decode_attention(wl.c_pool, wl.c_ids[l], cfg.batch, wl.c_q[l], wl.c_o[l], wl.c_scale, wl.c_stream)
+                    if rc:
+                        raise E.EllmError(rc, E.ellm_last_error())
+            torch.cuda.synchronize()
     for _ in range(Wm):
         wl.step()
     torch.cuda.synchronize()
@@ -663,10 +676,9 @@ def driver_mapped_compare(E, torch, W, args, K=30, Wm=5):
 def run_in_processes(args):
     """The default run: the headline workload and each of the other workloads in a process of its own, one
     after the other; their figures are merged into the one line this process prints. A workload then sees
-    the GPU as a fresh process finds it: what an earlier one left behind in the allocator and the driver
-    (after tens of GB have been allocated and freed, kernels over memory allocated later run 4-9 % slower on
-    this machine, and opposite copies over PCIe take twice as long) is not charged to a later one. This
-    process starts the others before anything in it has touched the GPU, and never does."""
+    the GPU as a fresh process finds it, and this process can leave the GPU idle between two of them (see
+    IDLE_BEFORE below). This process starts the others before anything in it has touched the GPU, and
+    never does."""
     import subprocess
 
     def child(extra, timeout):
@@ -692,15 +704,17 @@ def run_in_processes(args):
         except Exception:
             return None
 
-    # A workload that follows another does not find the GPU as the first one does: on this machine the HBM
-    # sensor goes from 36 to 54 degrees within a second of full-rate reading, and for some seconds after such
-    # a stretch kernels move 4-8 % fewer bytes per second (the 13B-shaped layer: 3.31 ms when the GPU has been
-    # idle, 3.46-3.58 ms right after another workload, 3.31 ms again after 20-25 s of idling, although the
-    # sensor is back at 35 degrees within a few seconds). So that the two large layers are measured as the
-    # headline workload is (first thing on an idle GPU), the GPU is left idle for IDLE_BEFORE seconds before
-    # each of them, and until the sensor is back to within 3 degrees of its first reading; the readings and
-    # the idle times go into the line.
-    IDLE_BEFORE = {"long70b": 20.0, "mha13b": 20.0}
+    # A workload that follows another does not find the GPU as the first one does: for some seconds after a
+    # process that held tens of GB of device memory has let go of them, kernels of the next process move
+    # 4-8 % fewer bytes per second (the 13B-shaped layer: 3.31 ms on a GPU that has been idle, 3.46-3.58 ms
+    # right after another large workload has ended, 3.31 ms again after 20-25 s), and copies over PCIe are
+    # slower as well. It is not the heat: the same layer takes 3.33 ms after three seconds of reading at
+    # full rate, HBM sensor at 57 degrees, and the 8B-shaped step takes the same time warm or cool (the line
+    # carries that measurement too). Something is still at work on the memory that was given back. So that
+    # every workload is measured as on an idle GPU, the GPU is left idle for IDLE_BEFORE seconds first, and
+    # until the HBM sensor is back to within 3 degrees of its first reading; the idle times and the sensor's
+    # readings go into the line.
+    IDLE_BEFORE = {"headline": 15.0, "long70b": 20.0, "mha13b": 20.0}
     t_start = memory_temperature()
     temps, idled = {}, {}
 
@@ -726,12 +740,27 @@ def run_in_processes(args):
         passed += ["--placement", args.placement]
     if args.prefill_append:
         passed += ["--prefill-append", str(args.prefill_append)]
+    # whatever ran on the GPU before this program (tests, another benchmark) is given time to wear off too
+    t_head, idled["headline"] = cooled(IDLE_BEFORE["headline"])
     res, err = child(["--config", args.config, "--no-extras", *passed], 900)
     if res is None:
         print("bench.py: the headline measurement failed: " + err, file=sys.stderr)
         return 1
-    temps["headline"] = [t_start, memory_temperature()]
+    temps["headline"] = [t_head, memory_temperature()]
     workloads = {}
+    # the headline workload once more, this time after three seconds of reading at full rate (the HBM
+    # sensor then shows 55-60 degrees instead of 35): what a service that never lets the GPU rest gets
+    got, err = child(["--config", args.config, "--no-extras", "--no-cpu-baseline", "--no-ceilings", "--preheat", "3",
+                      "--steps", str(args.steps), "--warmup", str(args.warmup)], 600)
+    if got is not None:
+        keep = ("value", "pct_of_peak", "ms_per_step", "ms_per_step_median", "ms_per_step_p10", "ms_per_step_p90")
+        workloads["headline_after_3s_at_full_rate"] = {k: got[k] for k in keep}
+        if got.get("roofline"):
+            workloads["headline_after_3s_at_full_rate"]["attention_kernel_us"] = got["roofline"]["avg_launch_us"]
+            workloads["headline_after_3s_at_full_rate"]["attention_kernel_frac_of_peak"] = got["roofline"]["frac"]
+    else:
+        workloads["headline_after_3s_at_full_rate"] = {"error": err}
+    temps["headline_after_3s_at_full_rate"] = [None, memory_temperature()]
     for name in LEGS:
         leg_flags = ["--leg", name] + (["--no-ceilings"] if args.no_ceilings else [])
         before, idled[name] = cooled(IDLE_BEFORE.get(name, 0.0))
@@ -790,7 +819,7 @@ def main():
                   waves_percent=args.waves_percent, extra_chunks=extra_chunks,
                   extra_tensors=n_layers * cfg.batch if args.prefill_append else 0)
     wl.fused = not args.separate_calls
-    head, ab, partial_bytes = measure(wl, K, Wm, args.event_stride, not args.no_kernel_events)
+    head, ab, partial_bytes = measure(wl, K, Wm, args.event_stride, not args.no_kernel_events, args.preheat)
     roofline = head.pop("roofline")
     if roofline is not None and not args.no_ceilings:
         roofline.update(read_ceilings(wl, partial_bytes, ab["kv"]))
