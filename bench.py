@@ -714,7 +714,7 @@ def run_in_processes(args):
     # every workload is measured as on an idle GPU, the GPU is left idle for IDLE_BEFORE seconds first, and
     # until the HBM sensor is back to within 3 degrees of its first reading; the idle times and the sensor's
     # readings go into the line.
-    IDLE_BEFORE = {"headline": 15.0, "long70b": 20.0, "mha13b": 20.0}
+    IDLE_BEFORE = {"headline": 20.0, "long70b": 20.0, "mha13b": 20.0}
     t_start = memory_temperature()
     temps, idled = {}, {}
 
