@@ -88,6 +88,7 @@ struct ellm_pool {
   hipStream_t side_in = nullptr;       // fetches (host -> device)
   hipStream_t side_out = nullptr;      // offloads (device -> host): a stream of its own, so that the two
                                        // directions use their own copy engines and run at the same time
+  bool one_allocation = false;         // the pool buffer lies inside one device allocation (asked once)
   hipStream_t last_stream = nullptr;   // last stream given to append / decode
   bool have_last_stream = false;
   hipEvent_t ev_switch = nullptr;      // orders a new compute stream behind the one used before
@@ -231,6 +232,15 @@ int ensure_device(ellm_pool* p) {
     const size_t vb = (size_t)p->geom.max_tensors * sizeof(uint64_t);
     HIP_TRY(hipMalloc((void**)&p->d_vbase, vb), "hipMalloc(tensor bases)");
     HIP_TRY(hipMemset(p->d_vbase, 0, vb), "hipMemset(tensor bases)");
+  }
+  if (!p->vmm && p->device_base) {
+    void* base = nullptr;
+    size_t size = 0;
+    const size_t pool_bytes = (size_t)p->geom.n_chunks * p->geom.chunk_bytes;
+    if (hipMemGetAddressRange((hipDeviceptr_t*)&base, &size, (hipDeviceptr_t)p->device_base) == hipSuccess)
+      p->one_allocation = (char*)base <= p->device_base && p->device_base + pool_bytes <= (char*)base + size;
+    else
+      (void)hipGetLastError();
   }
   HIP_TRY(hipStreamCreateWithFlags(&p->side_in, hipStreamNonBlocking), "hipStreamCreate(side)");
   HIP_TRY(hipStreamCreateWithFlags(&p->side_out, hipStreamNonBlocking), "hipStreamCreate(side)");
@@ -451,6 +461,20 @@ int enter_migration(ellm_pool* p, const std::vector<ellm::Move>& moves, bool fet
   }
   if ((rc = wait_for_compute(p, p->side_out, need_compute, p->out_waits_compute))) return rc;
   return wait_for(p->side_out, p->r_in, need_other, p->out_waits_in);
+}
+
+// Moves i, i + 1, ... whose chunks and whose host slots are both consecutive are one contiguous piece
+// of the pool and one of the host buffer: they travel as one copy (a 2 MiB copy reaches 44 GB/s on
+// this machine, a large one 57). Returns how many moves from i on form such a run. Only where the
+// pool is known to lie inside one device allocation: a pool whose chunks are mappings of their own
+// (a driver-mapped pool's window, a caller's buffer built the same way) is copied chunk by chunk.
+size_t move_run(const ellm_pool* p, const std::vector<ellm::Move>& moves, size_t i) {
+  size_t n = 1;
+  if (!p->one_allocation) return n;
+  while (i + n < moves.size() && moves[i + n].chunk == moves[i].chunk + (int32_t)n &&
+         moves[i + n].host_slot == moves[i].host_slot + (int32_t)n)
+    n++;
+  return n;
 }
 
 int leave_migration(ellm_pool* p, const std::vector<ellm::Move>& moves, bool fetch) {
@@ -1111,9 +1135,13 @@ int ellm_chunk_deflate_to_host(ellm_pool* p, ellm_tensor_id id, int32_t first_sl
     rc = enter_migration(p, p->moves, false);
     if (rc) return rc;
     const size_t cb = p->geom.chunk_bytes;
-    for (const ellm::Move& m : p->moves)
-      HIP_TRY(hipMemcpyAsync(p->host_base + (size_t)m.host_slot * cb, p->device_base + (size_t)m.chunk * cb, cb,
+    for (size_t i = 0; i < p->moves.size();) {
+      const size_t n = move_run(p, p->moves, i);
+      const ellm::Move& m = p->moves[i];
+      HIP_TRY(hipMemcpyAsync(p->host_base + (size_t)m.host_slot * cb, p->device_base + (size_t)m.chunk * cb, n * cb,
                              hipMemcpyDeviceToHost, p->side_out), "hipMemcpyAsync(offload)");
+      i += n;
+    }
     rc = leave_migration(p, p->moves, false);
     if (rc) return rc;
   }
@@ -1130,9 +1158,13 @@ int ellm_chunk_inflate_from_host(ellm_pool* p, ellm_tensor_id id, int32_t first_
     rc = enter_migration(p, p->moves, true);
     if (rc) return rc;
     const size_t cb = p->geom.chunk_bytes;
-    for (const ellm::Move& m : p->moves)
-      HIP_TRY(hipMemcpyAsync(p->device_base + (size_t)m.chunk * cb, p->host_base + (size_t)m.host_slot * cb, cb,
+    for (size_t i = 0; i < p->moves.size();) {
+      const size_t n = move_run(p, p->moves, i);
+      const ellm::Move& m = p->moves[i];
+      HIP_TRY(hipMemcpyAsync(p->device_base + (size_t)m.chunk * cb, p->host_base + (size_t)m.host_slot * cb, n * cb,
                              hipMemcpyHostToDevice, p->side_in), "hipMemcpyAsync(fetch)");
+      i += n;
+    }
     rc = leave_migration(p, p->moves, true);
     if (rc) return rc;
   }
