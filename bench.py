@@ -494,20 +494,45 @@ def elastic_step(E, torch, W, args, steps=3):
     layer by layer under the attention); and whether the output bits survive the remap."""
     name = "llama8b"
     n_layers = DEFAULT_LAYERS[name]
-    wl = Workload(E, torch, W, name, n_layers, 6 * steps + 4, host_for_quarter=True, extra_chunks=512)
+    wl = Workload(E, torch, W, name, n_layers, 10 * steps + 8, host_for_quarter=True, extra_chunks=512)
     cfg, pool, ids, Tc, B = wl.cfg, wl.pool, wl.ids, wl.cfg.tokens_per_chunk, wl.cfg.batch
     sel = list(range(0, B, 4))
 
     def slots(b, extra=0):
         return int(-(-(int(wl.lens[b]) + extra) // Tc))
 
+    # Which chunks a fetch goes into is the caller's choice. Left to the pool it is the lowest free ids,
+    # which here are the ones an offload has just let go of and is still reading: the fetch then waits
+    # for that offload and the two directions take turns. With `oldest_first` the step keeps its own
+    # list of free KV chunks in the order they became free and fetches into the ones free the longest.
+    free_fifo = []
+    oldest_first = [False]
+
+    def refill_fifo():
+        owner, state, _, _ = E.ellm_pool_get_owner_state(pool)
+        free_now = set(np.flatnonzero((owner == E.ELLM_OWNER_KV) & (state == E.ELLM_CHUNK_FREE)).tolist())
+        kept = [c for c in free_fifo if c in free_now]
+        known = set(kept)
+        free_fifo[:] = sorted(free_now - known) + kept      # chunks not seen before count as free the longest
+
     def offload_layer(l, extra=0):
         for b in sel:
-            E.ellm_chunk_deflate_to_host(pool, int(ids[l][b]), 0, slots(b, extra))
+            n = slots(b, extra)
+            if oldest_first[0]:
+                tab = E.ellm_tensor_get_table(pool, int(ids[l][b]))[0][:n]
+                free_fifo.extend(int(c) for c in tab if c >= 0)
+            E.ellm_chunk_deflate_to_host(pool, int(ids[l][b]), 0, n)
 
     def fetch_layer(l):
         for b in sel:
-            E.ellm_chunk_inflate_from_host(pool, int(ids[l][b]), 0, slots(b))
+            n = slots(b)
+            if oldest_first[0] and len(free_fifo) >= n + 128:
+                want = np.array(free_fifo[:n], np.int32)
+                if E.ellm_chunk_inflate_from_host(pool, int(ids[l][b]), 0, n, want, check=False) == 0:
+                    del free_fifo[:n]
+                    continue
+                refill_fifo()                                   # something else took one of them: start over
+            E.ellm_chunk_inflate_from_host(pool, int(ids[l][b]), 0, n)
 
     def sync():
         E.ellm_pool_sync(pool)
@@ -587,6 +612,11 @@ def elastic_step(E, torch, W, args, steps=3):
     t_layer = timed(layerwise)
     kern = E.ellm_pool_profile_collect(pool, steps * n_layers)
     E.ellm_pool_profile_enable(pool, 0)
+    oldest_first[0] = True
+    refill_fifo()
+    layerwise()                                                  # one step to get the rotation going
+    t_layer_oldest = timed(layerwise)
+    oldest_first[0] = False
     for l in range(n_layers):          # leave everything resident
         fetch_layer(l)
     sync()
@@ -603,6 +633,7 @@ def elastic_step(E, torch, W, args, steps=3):
         "offload_GBps": round(nbytes / (min(t_off, t_off2) * 1e-3) / 1e9, 2), "fetch_GBps": round(nbytes / (t_fetch * 1e-3) / 1e9, 2),
         "ms_step_no_migration": round(t_plain, 3),
         "ms_step_copies_then_compute": round(t_block, 3), "ms_step_layerwise": round(t_layer, 3),
+        "ms_step_layerwise_fetch_into_chunks_free_the_longest": round(t_layer_oldest, 3),
         "ms_hidden_by_layerwise": round(t_block - t_layer, 3),
         "ownership_transfer_us": round(us_hand, 1), "chunks_handed_over": n_hand,
         "output_bits_unchanged_by_remap": invariant, "slots_remapped_in_check": moved,
