@@ -570,7 +570,13 @@ int vmm_sync(ellm_pool* p) {
       // a tensor handle's range is reserved once, for the largest tensor the pool allows, and kept
       // for the handle's later lives
       void* va = nullptr;
-      HIP_TRY(hipMemAddressReserve(&va, (size_t)p->geom.max_slots * cb, 0, nullptr, 0), "hipMemAddressReserve(tensor)");
+      const hipError_t e = hipMemAddressReserve(&va, (size_t)p->geom.max_slots * cb, 0, nullptr, 0);
+      if (e != hipSuccess) {
+        // the table already names chunks that will never be mapped: no kernel may run on this pool again
+        p->mapq->fail_now((int)e, "hipMemAddressReserve(tensor)");
+        if (!jobs.empty()) p->mapq->push(jobs);
+        return hip_err(e, "hipMemAddressReserve(tensor)");
+      }
       p->vbase[id] = (char*)va;
       p->vbase_dirty.push_back(id);
     }
@@ -590,15 +596,23 @@ int vmm_sync(ellm_pool* p) {
   if (kernels_may_read && p->have_last_stream) {
     // one event behind everything launched so far covers every unmap of this call: the first of
     // them waits for it, the others run after that one
-    hipEvent_t ev;
-    HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming), "hipEventCreate(before unmap)");
-    hipError_t e = hipEventRecord(ev, p->last_stream);
-    if (e != hipSuccess) {
+    hipEvent_t ev = nullptr;
+    hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+    if (e == hipSuccess && (e = hipEventRecord(ev, p->last_stream)) != hipSuccess) {
       (void)hipEventDestroy(ev);
-      return hip_err(e, "hipEventRecord(before unmap)");
+      ev = nullptr;
     }
-    for (ellm::MapJob& j : jobs)
-      if (j.unmap) { j.after = (void*)ev; break; }
+    if (ev) {
+      for (ellm::MapJob& j : jobs)
+        if (j.unmap) { j.after = (void*)ev; break; }
+    } else {
+      // no event to be had: the jobs are already decided, so this thread waits for the kernels itself
+      (void)hipGetLastError();
+      if (hipStreamSynchronize(p->last_stream) != hipSuccess) {
+        p->mapq->fail_now((int)e, "hipEventRecord(before unmap)");
+        return hip_err(e, "hipEventRecord(before unmap)");
+      }
+    }
   }
   p->mapq->push(jobs);
   return p->vmm_async ? ELLM_OK : vmm_drain(p);

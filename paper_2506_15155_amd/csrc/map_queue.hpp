@@ -86,6 +86,17 @@ class MapQueue {
     thread_.join();
   }
 
+  // The pushing thread met an error of its own that leaves mappings missing (it could not prepare a
+  // job): recorded like a job's error, so that every later wait() reports it and failed() is set.
+  void fail_now(int code, const char* where) {
+    std::lock_guard<std::mutex> lk(mu_);
+    if (!error_) {
+      error_ = code;
+      error_where_ = where;
+    }
+    failed_.store(true, std::memory_order_release);
+  }
+
   // test hook: the n-th map job from now is not made and counts as refused by the driver (0: none)
   void fail_map_in(int n) { fail_in_.store(n); }
 

@@ -160,6 +160,19 @@ int main(int argc, char** argv) {
     if (q.wait(q.push(jobs), &where) != -1 || where.find("refused") == std::string::npos) die("hook");
     if (sh.mapped.size() != 2) die("hook: mappings made", (long)sh.mapped.size());
   }
+  // 4. an error of the pushing thread's own is reported like a job's
+  {
+    Shared sh;
+    ellm::MapQueue<FakeDriver> q(FakeDriver{&sh});
+    q.start();
+    std::vector<ellm::MapJob> jobs = {{space, (void*)handles, false, nullptr}};
+    std::string where;
+    if (q.wait(q.push(jobs), &where) != 0 || q.failed()) die("clean start");
+    q.fail_now(9, "reserve");
+    if (!q.failed() || q.wait(0, &where) != 9 || where != "reserve") die("fail_now");
+    jobs[0].at = space + 1;
+    if (q.wait(q.push(jobs), &where) != 9 || sh.mapped.size() != 1) die("driver called after fail_now");
+  }
   std::printf("mapper queue behaves\n");
   return 0;
 }
