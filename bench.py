@@ -607,6 +607,12 @@ def elastic_step(E, torch, W, args, steps=3):
     t_fetch = timed(lambda: [fetch_layer(l) for l in range(n_layers)], 1)
     t_off2 = timed(lambda: [offload_layer(l) for l in range(n_layers)], 1)     # parked again: the state between steps
     t_block = timed(blocking)
+    # the same with the library's copy kernel instead of the copy engines (the requests are parked at this point)
+    E.ellm_debug_set_copy_kernels(pool, 1)
+    t_fetch_k = timed(lambda: [fetch_layer(l) for l in range(n_layers)], 1)
+    t_off_k = timed(lambda: [offload_layer(l) for l in range(n_layers)], 1)
+    t_block_k = timed(blocking)
+    E.ellm_debug_set_copy_kernels(pool, 0)
     E.ellm_pool_profile_enable(pool, steps * n_layers)
     E.ellm_pool_profile_stride(pool, 13)
     t_layer = timed(layerwise)
@@ -634,6 +640,9 @@ def elastic_step(E, torch, W, args, steps=3):
         "ms_step_no_migration": round(t_plain, 3),
         "ms_step_copies_then_compute": round(t_block, 3), "ms_step_layerwise": round(t_layer, 3),
         "ms_step_layerwise_fetch_into_chunks_free_the_longest": round(t_layer_oldest, 3),
+        "with_copy_kernel_instead_of_copy_engines": {"offload_GBps": round(nbytes / t_off_k / 1e6, 2),
+                                                     "fetch_GBps": round(nbytes / t_fetch_k / 1e6, 2),
+                                                     "ms_step_copies_then_compute": round(t_block_k, 3)},
         "ms_hidden_by_layerwise": round(t_block - t_layer, 3),
         "ownership_transfer_us": round(us_hand, 1), "chunks_handed_over": n_hand,
         "output_bits_unchanged_by_remap": invariant, "slots_remapped_in_check": moved,

@@ -476,6 +476,12 @@ int ellm_debug_set_table_kernels(ellm_pool* pool, int on);
  * until the driver calls it asked for have been made (what the pool would cost without its mapper
  * thread); != 0 (the default) goes back to handing them over. INVALID for other pools. */
 int ellm_debug_set_async_mapping(ellm_pool* pool, int on);
+/* Offload and fetch move their chunks with the runtime's copy calls (copy engines, beside the
+ * kernels). on != 0 makes them use the library's copy kernel instead (one launch per call, the GPU
+ * reading or writing the pinned host buffer directly) where the GPU can address the host buffer:
+ * faster when nothing else runs, but it takes compute units from the kernels beside it. 0 (the
+ * default) goes back. For measurements; same bytes either way. */
+int ellm_debug_set_copy_kernels(ellm_pool* pool, int on);
 /* Test hook for the error path of a driver-mapped pool's mapper thread: the nth mapping it is asked
  * for from now on (1 = the next one; 0 = none) is not made and counts as refused by the driver. Every
  * later call that would launch a kernel on the pool, or that waits for the thread, then returns

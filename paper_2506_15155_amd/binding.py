@@ -88,6 +88,7 @@ _sigs = {
     "ellm_pool_get_mapping_stats": [_vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)],
     "ellm_debug_set_table_kernels": [_vp, C.c_int],
     "ellm_debug_set_async_mapping": [_vp, C.c_int],
+    "ellm_debug_set_copy_kernels": [_vp, C.c_int],
     "ellm_debug_fail_mapping": [_vp, C.c_int32],
     "ellm_pool_get_mapping_wait": [_vp, C.POINTER(C.c_double)],
     "ellm_pool_get_geometry": [_vp, _i32p, _i32p, _i32p, C.POINTER(C.c_uint64)],
@@ -380,6 +381,10 @@ def ellm_debug_set_table_kernels(pool, on, check=True):
 
 def ellm_debug_set_async_mapping(pool, on, check=True):
     return _ret(lib.ellm_debug_set_async_mapping(pool, int(bool(on))), check)
+
+
+def ellm_debug_set_copy_kernels(pool, on, check=True):
+    return _ret(lib.ellm_debug_set_copy_kernels(pool, int(bool(on))), check)
 
 
 def ellm_debug_fail_mapping(pool, nth, check=True):

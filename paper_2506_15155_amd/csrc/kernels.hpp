@@ -83,6 +83,15 @@ struct PatchArgs {
   int32_t val[MAX_PATCH];
 };
 
+// chunks copied by one launch between the pool and the pinned host buffer: move i is device chunk
+// chunk[i] <-> host slot host_slot[i]
+constexpr int MAX_COPY = 480;
+struct CopyArgs {
+  int32_t n;
+  int32_t chunk[MAX_COPY];
+  int32_t host_slot[MAX_COPY];
+};
+
 // resident waves of the partial-pass kernel per compute unit (occupancy query), per (head_dim, group)
 int partial_waves_per_cu(int head_dim, int group);
 
@@ -90,6 +99,9 @@ int partial_waves_per_cu(int head_dim, int group);
 int launch_table_patch(int32_t* table, const PatchArgs& a, hipStream_t stream);
 int launch_kv_append(const PoolView& pv, const void* k_new, const void* v_new, const AppendArgs& a,
                      hipStream_t stream);
+// Whole chunks between the pool (chunk c at pool + c * chunk_bytes) and the host buffer as the GPU
+// sees it (slot s at host + s * chunk_bytes); to_host: offload, else fetch.
+int launch_chunk_copy(char* pool, char* host, uint32_t chunk_bytes, const CopyArgs& a, bool to_host, hipStream_t stream);
 // k_new / v_new non-NULL: fused append. a.len then counts one token per request whose K/V row
 // ([request][kv head][dim], rows q_row0 .. of the caller's batch) is still in k_new / v_new; the
 // kernel uses it from there and writes it into the chunk.

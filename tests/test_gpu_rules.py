@@ -257,6 +257,8 @@ def test_random_walk_of_every_call_on_the_gpu(pool_mode, seed):
         B.orc.chunk_set_bytes(c, poison)
     P, O = B.pool, B.orc
     n_ok = n_dec = 0
+    if seed == 12:
+        E.ellm_debug_set_copy_kernels(P, 1)      # offload / fetch through the library's copy kernel in this one
 
     def some_ids(k=None):
         k = int(rng.integers(1, 5)) if k is None else k
