@@ -422,9 +422,10 @@ int ellm_decode_plan(ellm_pool* pool, const ellm_tensor_id* ids, int32_t batch,
  * cannot happen. */
 int ellm_pool_set_split_tokens(ellm_pool* pool, int32_t split_tokens);
 
-/* Measurement hooks. profile_enable(max_records > 0) makes each decode launch record a pair of
- * HIP events on the caller's stream around its partial-pass kernel (the kernel that streams K/V),
- * for up to max_records launches; max_records = 0 switches it off. profile_collect waits for the
+/* Measurement hooks. profile_enable(max_records > 0) makes each decode launch attach a pair of
+ * HIP events to its partial-pass kernel (the kernel that streams K/V) on the caller's stream, which
+ * take that kernel's own start and end times (the runtime's extended launch: no marker of its own
+ * goes into the stream), for up to max_records launches; max_records = 0 switches it off. profile_collect waits for the
  * recorded launches, writes their durations in milliseconds to ms (host, cap entries), stores the
  * number recorded in *n and starts over. Not part of the paper's method. */
 int ellm_pool_profile_enable(ellm_pool* pool, int32_t max_records);

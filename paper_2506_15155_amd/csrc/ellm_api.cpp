@@ -1127,11 +1127,12 @@ static int decode_impl(ellm_pool* p, const ellm_tensor_id* ids, int32_t batch, c
       p->prof_phase = (p->prof_phase + 1) % p->prof_stride;
     }
     if (launch_refused(p)) { err = set_err(ELLM_ERR_HIP, "decode partial launch: refused (debug hook)"); break; }
-    if (prof && hipEventRecord(p->prof_ev[2 * p->prof_used], stream) != hipSuccess) prof = false;
-    int e = ellm::launch_decode_partial(pv, q, k_new, v_new, ws, out, scale_log2, a, stream);
+    int e = ellm::launch_decode_partial(pv, q, k_new, v_new, ws, out, scale_log2, a, stream,
+                                        prof ? p->prof_ev[2 * p->prof_used] : nullptr,
+                                        prof ? p->prof_ev[2 * p->prof_used + 1] : nullptr);
     if (e) { err = hip_err((hipError_t)e, "decode partial launch"); break; }
     *n_launched += a.n_req;
-    if (prof && hipEventRecord(p->prof_ev[2 * p->prof_used + 1], stream) == hipSuccess) p->prof_used++;
+    if (prof) p->prof_used++;
     e = ellm::launch_decode_combine(pv, ws, out, a, stream);
     if (e) { err = hip_err((hipError_t)e, "decode combine launch"); break; }
   }

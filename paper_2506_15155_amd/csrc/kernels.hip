@@ -14,6 +14,7 @@
 #include "kernels.hpp"
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <type_traits>
@@ -952,10 +953,23 @@ int partial_waves_per_cu(int head_dim, int group) {
   return n;
 }
 
+// ev0 / ev1 (either may be NULL): events that take the kernel's own start and end times (the
+// runtime's extended launch attaches them to the kernel's dispatch, so no marker of its own goes
+// into the stream and the time between them is the kernel's duration)
 template <int D, int G, bool APPEND, bool DIRECT>
 static void launch_partial_i(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
-                             void* out, float scale_log2, int32_t g_first, const BatchArgs& a, hipStream_t stream) {
+                             void* out, float scale_log2, int32_t g_first, const BatchArgs& a, hipStream_t stream,
+                             hipEvent_t ev0, hipEvent_t ev1) {
   const unsigned grid = (unsigned)(a.waves_per_head * pv.n_kv_heads);
+  if (ev0 || ev1) {
+    if constexpr (G >= 4)
+      hipExtLaunchKernelGGL((decode_partial_kernel_wide<D, G, APPEND, DIRECT>), dim3(grid), dim3(64), 0, stream, ev0, ev1, 0, pv,
+                            (const uint16_t*)q, (const uint4*)k_new, (const uint4*)v_new, ws, (uint16_t*)out, scale_log2, g_first, a);
+    else
+      hipExtLaunchKernelGGL((decode_partial_kernel<D, G, APPEND, DIRECT>), dim3(grid), dim3(64), 0, stream, ev0, ev1, 0, pv,
+                            (const uint16_t*)q, (const uint4*)k_new, (const uint4*)v_new, ws, (uint16_t*)out, scale_log2, g_first, a);
+    return;
+  }
   if constexpr (G >= 4)
     hipLaunchKernelGGL((decode_partial_kernel_wide<D, G, APPEND, DIRECT>), dim3(grid), dim3(64), 0, stream, pv,
                        (const uint16_t*)q, (const uint4*)k_new, (const uint4*)v_new, ws, (uint16_t*)out, scale_log2, g_first, a);
@@ -966,24 +980,28 @@ static void launch_partial_i(const PoolView& pv, const void* q, const void* k_ne
 
 template <int D, int G>
 static void launch_partial_t(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
-                             void* out, float scale_log2, int32_t g_first, const BatchArgs& a, hipStream_t stream) {
-  if (k_new && pv.vbase) launch_partial_i<D, G, true, true>(pv, q, k_new, v_new, ws, out, scale_log2, g_first, a, stream);
-  else if (k_new) launch_partial_i<D, G, true, false>(pv, q, k_new, v_new, ws, out, scale_log2, g_first, a, stream);
-  else if (pv.vbase) launch_partial_i<D, G, false, true>(pv, q, nullptr, nullptr, ws, out, scale_log2, g_first, a, stream);
-  else launch_partial_i<D, G, false, false>(pv, q, nullptr, nullptr, ws, out, scale_log2, g_first, a, stream);
+                             void* out, float scale_log2, int32_t g_first, const BatchArgs& a, hipStream_t stream,
+                             hipEvent_t ev0, hipEvent_t ev1) {
+  if (k_new && pv.vbase) launch_partial_i<D, G, true, true>(pv, q, k_new, v_new, ws, out, scale_log2, g_first, a, stream, ev0, ev1);
+  else if (k_new) launch_partial_i<D, G, true, false>(pv, q, k_new, v_new, ws, out, scale_log2, g_first, a, stream, ev0, ev1);
+  else if (pv.vbase) launch_partial_i<D, G, false, true>(pv, q, nullptr, nullptr, ws, out, scale_log2, g_first, a, stream, ev0, ev1);
+  else launch_partial_i<D, G, false, false>(pv, q, nullptr, nullptr, ws, out, scale_log2, g_first, a, stream, ev0, ev1);
 }
 
 // a group size that is not 8, 4, 2 or 1 is covered by several launches over the same K/V
 template <int D>
 static int launch_partial_d(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
-                            void* out, float scale_log2, const BatchArgs& a, hipStream_t stream) {
+                            void* out, float scale_log2, const BatchArgs& a, hipStream_t stream, hipEvent_t ev_start,
+                            hipEvent_t ev_stop) {
   int done = 0;
   while (done < pv.group) {
     const int step = group_step(pv.group - done);
-    if (step == 8) launch_partial_t<D, 8>(pv, q, k_new, v_new, ws, out, scale_log2, done, a, stream);
-    else if (step == 4) launch_partial_t<D, 4>(pv, q, k_new, v_new, ws, out, scale_log2, done, a, stream);
-    else if (step == 2) launch_partial_t<D, 2>(pv, q, k_new, v_new, ws, out, scale_log2, done, a, stream);
-    else launch_partial_t<D, 1>(pv, q, k_new, v_new, ws, out, scale_log2, done, a, stream);
+    // the first launch of the call takes the start time, the last one the end time
+    hipEvent_t ev0 = done == 0 ? ev_start : nullptr, ev1 = done + step >= pv.group ? ev_stop : nullptr;
+    if (step == 8) launch_partial_t<D, 8>(pv, q, k_new, v_new, ws, out, scale_log2, done, a, stream, ev0, ev1);
+    else if (step == 4) launch_partial_t<D, 4>(pv, q, k_new, v_new, ws, out, scale_log2, done, a, stream, ev0, ev1);
+    else if (step == 2) launch_partial_t<D, 2>(pv, q, k_new, v_new, ws, out, scale_log2, done, a, stream, ev0, ev1);
+    else launch_partial_t<D, 1>(pv, q, k_new, v_new, ws, out, scale_log2, done, a, stream, ev0, ev1);
     ELLM_HIP_CHECK_LAUNCH();
     done += step;
   }
@@ -991,10 +1009,11 @@ static int launch_partial_d(const PoolView& pv, const void* q, const void* k_new
 }
 
 int launch_decode_partial(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
-                          void* out, float scale_log2, const BatchArgs& a, hipStream_t stream) {
+                          void* out, float scale_log2, const BatchArgs& a, hipStream_t stream, hipEvent_t ev_start,
+                          hipEvent_t ev_stop) {
   if (a.n_req <= 0 || a.waves_per_head <= 0) return 0;
-  return pv.head_dim == 128 ? launch_partial_d<128>(pv, q, k_new, v_new, ws, out, scale_log2, a, stream)
-                            : launch_partial_d<64>(pv, q, k_new, v_new, ws, out, scale_log2, a, stream);
+  return pv.head_dim == 128 ? launch_partial_d<128>(pv, q, k_new, v_new, ws, out, scale_log2, a, stream, ev_start, ev_stop)
+                            : launch_partial_d<64>(pv, q, k_new, v_new, ws, out, scale_log2, a, stream, ev_start, ev_stop);
 }
 
 int launch_decode_combine(const PoolView& pv, const float* ws, void* out, const BatchArgs& a, hipStream_t stream) {

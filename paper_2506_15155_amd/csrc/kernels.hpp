@@ -106,8 +106,11 @@ int launch_chunk_copy(char* pool, char* host, uint32_t chunk_bytes, const CopyAr
 // ([request][kv head][dim], rows q_row0 .. of the caller's batch) is still in k_new / v_new; the
 // kernel uses it from there and writes it into the chunk.
 // out: the caller's output rows; requests with n_part == 1 are finished by the partial pass itself.
+// ev_start / ev_stop (may be NULL): events that receive the start time of the call's first attention
+// kernel and the end time of its last one, taken from the kernels' own dispatches.
 int launch_decode_partial(const PoolView& pv, const void* q, const void* k_new, const void* v_new, float* ws,
-                          void* out, float scale_log2, const BatchArgs& a, hipStream_t stream);
+                          void* out, float scale_log2, const BatchArgs& a, hipStream_t stream,
+                          hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 int launch_decode_combine(const PoolView& pv, const float* ws, void* out, const BatchArgs& a, hipStream_t stream);
 
 // Device address and size of the library's fixed workspace on the current device (resolved once per
