@@ -713,6 +713,13 @@ def driver_mapped_compare(E, torch, W, args, K=30, Wm=5):
 
 
 # ------------------------------------------------------------------------------------------------------
+def under_profiler():
+    """rocprofv3 (and its predecessors) announce themselves in the environment of the program they run."""
+    if any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ):
+        return True
+    return "rocprof" in os.environ.get("LD_PRELOAD", "").lower()
+
+
 def run_in_processes(args):
     """The default run: the headline workload and each of the other workloads in a process of its own, one
     after the other; their figures are merged into the one line this process prints. A workload then sees
@@ -828,6 +835,12 @@ def main():
                                                           and args.pool_memory == "malloc" and not args.split
                                                           and not args.waves_percent and not args.layers
                                                           and not args.leg)
+    if extras and under_profiler():
+        # a profiled program must not start other programs (the profiler has initialised the GPU in this
+        # process already): only the headline workload then, in this process
+        print("bench.py: running under a profiler: only the headline workload is measured, in this process "
+              "(same as --no-extras)", file=sys.stderr)
+        extras = False
     if extras:
         # every workload in a process of its own, one after the other, started by this one, which never
         # touches the GPU itself (see run_in_processes)
