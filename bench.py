@@ -845,6 +845,10 @@ def main():
         # every workload in a process of its own, one after the other, started by this one, which never
         # touches the GPU itself (see run_in_processes)
         sys.exit(run_in_processes(args))
+    # the oracle's library is loaded (and, if it is missing, compiled: a child process) before anything
+    # in this process touches the GPU
+    from oracle import model as _oracle_model
+    _oracle_model.load()
     import torch
     import paper_2506_15155_amd as E
     import workloads as W

@@ -10,6 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # The oracle's library is loaded here (and compiled first if it is missing: a child process), before
+    # the check below or any test touches the GPU; a process that has done that starts no other programs.
+    from oracle import model
+    model.load()
 
 
 def _has_gpu():
